@@ -1,0 +1,174 @@
+/*
+ * wq.h -- C ABI of the WindowQuant hot path on AMD MI355X (gfx950).
+ *
+ * WindowQuant (window-adaptive mixed-precision KV-cache quantization for video-language models)
+ * has three data-parallel stages; this library implements them as four calls:
+ *
+ *   wq_window_scores     window-level quantization search, scoring   (Sec. 3.2.1, similarity equation)
+ *   wq_assign_bits       ... and bit-width decision per window        (Sec. 3.2.1 threshold rule, Sec. 3.2.2
+ *                                                                      first-window pin; rank/quota rule)
+ *   wq_reorder_quantize  window-level KV cache computation, prefill   (Sec. 3.3.1, Sec. 3.3.3, Alg. 2 first half)
+ *   wq_decode_attention  ... and decoding over the mixed cache        (Alg. 2 second half, Sec. 3.3.2)
+ *
+ * Conventions
+ *   - Every pointer named "dev" or documented as device memory is a HIP device pointer on the current
+ *     device; every scalar and the structs themselves live on the host.  The library reads no device
+ *     table on the host and never synchronises: each call only enqueues kernels on the context's stream.
+ *   - The caller owns every buffer.  The library allocates nothing after wq_create (and nothing at all
+ *     when wq_create is given a workspace).
+ *   - Every call returns WQ_OK (0) or a negative wq_status; it never aborts.  Host-checkable argument
+ *     errors are reported before anything is enqueued; wq_last_error() gives a message.
+ *   - Conditions only visible on the device (a class buffer too small for what the bit assignment
+ *     produced) set a bit in a device status word that wq_device_status() reads back.
+ *   - Shapes: head_dim hd in {64, 128}; group in {32, 64, 128} dividing hd; Hq a multiple of Hkv with
+ *     Hq/Hkv <= 8.  Anything else is WQ_ERR_UNSUPPORTED.
+ *
+ * Sequences and windows
+ *   A batch has B sequences.  Sequence b has win_off[b+1]-win_off[b] windows of win_size[b] tokens
+ *   (Sec. 3.2.1: W_i = {v_{iS} .. v_{iS+S-1}}, floor(M/S) windows).  Visual tokens that do not fill a
+ *   window, text tokens and generated tokens stay 16-bit (Sec. 3.1).
+ *
+ * Bit classes
+ *   class 0,1,2 = 2,4,8-bit codes; the 16-bit segment holds everything else.  In memory the order is
+ *   2-bit, 4-bit, 8-bit, 16-bit (the order of Alg. 2, with the appendable 16-bit block last); inside a
+ *   class windows keep ascending index (Alg. 2 appends in index order).
+ *
+ * Quantization (Sec. 3.3.3, asymmetric round-to-nearest, unsigned range [0, 2^b-1])
+ *   A group is `group` consecutive channels of one token of one KV head.  With lo/hi the group's
+ *   min/max, all in fp32 without fused multiply-add:
+ *       m = f16(lo);  s = f16((hi - m) / (2^b-1));  if (s == 0) s = 1;  inv = 1.0f / s;
+ *       code = clamp((int)rint((x - m) * inv), 0, 2^b-1)          (ties to even)
+ *   and the value a code stands for is  m + s*code.  s and m are stored as IEEE binary16.
+ *   Inputs must be finite with |x| <= 65504.
+ *
+ * Storage layout of a class buffer (b = bits, G = hd/group, cap = capacity in tokens, a multiple of 32)
+ *   codes : bytes [plane][Hkv][cap*hd*b/8], plane 0 = K, 1 = V.  Codes are b-bit fields; field n of a
+ *           tile/block sits at bit n*b (low bits of low bytes first).
+ *           K plane, tiles of 16 tokens: token m of the tile, channel ch = j*(hd/4)+e
+ *                    -> n = (j*16 + m)*(hd/4) + e
+ *           V plane, blocks of 32 tokens: token u of the block, channel ch = 16*ct + mm
+ *                    -> jj = (u%16)/4, tau = 4*(u/16) + u%4,  n = ((jj*16 + mm)*(hd/16) + ct)*8 + tau
+ *           (both are exactly the per-lane operand order of the 16x16x32 matrix instruction, so a
+ *           wavefront reads whole tiles with one coalesced load per lane and no shuffles).
+ *   meta  : uint32 [plane][Hkv][cap/16][G][16]; low half = f16 s, high half = f16 m of (token, group).
+ *   Sequence b owns tokens cls_off[c][b] .. cls_off[c][b]+cls_len[c][b]-1 of class c; cls_off entries are
+ *   multiples of 32 and the padding up to the next multiple of 32 holds zero codes and zero metadata.
+ *   16-bit segment: k16/v16 [cap16][Hkv][hd] elements of dtype16, sequence b at rows
+ *   off16[b] .. off16[b]+len16[b]-1; 16-bit windows first (index order), then the video tail and text
+ *   in their original order; the caller appends generated tokens and bumps len16[b] (Sec. 2.2).
+ */
+#ifndef WQ_H
+#define WQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wq_ctx wq_ctx;
+
+typedef enum { WQ_F32 = 0, WQ_BF16 = 1, WQ_F16 = 2 } wq_dtype;
+typedef enum { WQ_OK = 0, WQ_ERR_ARG = -1, WQ_ERR_UNSUPPORTED = -2, WQ_ERR_HIP = -3, WQ_ERR_WORKSPACE = -4 } wq_status;
+typedef enum { WQ_SCORE_AUTO = 0, WQ_SCORE_PAIRWISE_MFMA = 1, WQ_SCORE_POOLED = 2 } wq_score_algo;
+typedef enum { WQ_MODE_QUOTA = 0, WQ_MODE_THRESHOLD = 1 } wq_assign_mode;
+typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } wq_decode_algo;
+
+/* device status bits (wq_device_status) */
+#define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
+#define WQ_DEV_SEG16_OVERFLOW 2u /* 16-bit rows of a sequence exceeded off16[b+1]-off16[b] or cap16        */
+
+/* ---- context ----------------------------------------------------------------------------------------------
+ * hip_stream   : a hipStream_t (NULL = the default stream); all work of this context is enqueued on it.
+ * workspace    : device memory of workspace_bytes that the library may scribble on, or NULL to let
+ *                wq_create allocate workspace_bytes itself (freed by wq_destroy).  Size it with
+ *                wq_workspace_bytes; calls that need more return WQ_ERR_WORKSPACE.
+ * wq_create touches no GPU when it is given a workspace (or workspace_bytes == 0).                          */
+int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes);
+int wq_destroy(wq_ctx* ctx);
+int wq_set_stream(wq_ctx* ctx, void* hip_stream);
+const char* wq_last_error(const wq_ctx* ctx);
+/* Blocks until the stream drains, then returns the device status word in *bits and clears it. */
+int wq_device_status(wq_ctx* ctx, uint32_t* bits);
+
+/* Host-only, pure.  Workspace needed by the largest call with these bounds (any argument may be 0). */
+size_t wq_workspace_bytes(int B, int Hq, int hd, int max_splits, int64_t total_vis, int64_t total_txt, int D);
+/* Host-only, pure.  Bytes of codes (return value) and metadata (*meta_bytes) of one class buffer with
+ * capacity cap_tokens (rounded up to 32 here), both planes and all KV heads.  0 on unsupported shapes.      */
+size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group, size_t* meta_bytes);
+/* Host-only, pure.  Split count wq_decode_attention picks for num_splits = 0. */
+int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens);
+
+/* ---- a1: window scores (Sec. 3.2.1) ----------------------------------------------------------------------
+ * score[i] = 1/(S N) sum_{k in window i} sum_j cos(t_j, w_k), cosine := 0 for a zero vector.
+ * vis_emb [total_vis, D], txt_emb [total_txt, D]  device, row-major, element type `dtype`
+ * vis_off, txt_off [B+1], win_size [B], win_off [B+1]   device int32; window i of sequence b covers rows
+ *          vis_off[b] + i*win_size[b] .. + win_size[b]-1
+ * total_vis, total_txt, total_win : host copies of vis_off[B], txt_off[B], win_off[B] (grid bounds)
+ * algo    : WQ_SCORE_POOLED uses the identity score = (mean_j t_j/|t_j|) . (mean_k w_k/|w_k|) and reads each
+ *           embedding once (HBM-bound); WQ_SCORE_PAIRWISE_MFMA forms the [tokens x text] product on the
+ *           matrix cores (bf16/fp16 inputs only) and normalises/reduces it in the epilogue.
+ * scores  [total_win] device fp32, written.   Accumulation is fp32; no atomics, results are deterministic. */
+int wq_window_scores(wq_ctx* ctx, const void* vis_emb, const void* txt_emb, int dtype, int B, int D,
+                     const int32_t* vis_off, const int32_t* txt_off, const int32_t* win_size, const int32_t* win_off,
+                     int64_t total_vis, int64_t total_txt, int64_t total_win, int algo, float* scores);
+
+/* ---- a2: bit-width per window ----------------------------------------------------------------------------
+ * mode WQ_MODE_THRESHOLD (Sec. 3.2.1): score > T_high -> top_bits, score < T_low -> 2, else 4 (strict).
+ * mode WQ_MODE_QUOTA: windows ordered by score descending, equal scores by ascending index (NaN ranks last);
+ *      the first n_top get top_bits, the next n4 get 4, the rest 2; quotas are clipped to the window count.
+ * pin_first (Sec. 3.2.2): window 0 gets top_bits whatever its score; under quotas it leaves the ranking and
+ *      uses one slot of the highest-precision class with a non-zero quota.
+ * top_bits : 8, or 16 to keep the top tier unquantized as the paper does.
+ * scores [total_win] fp32, win_off [B+1], quota [B,3] = {n_top, n4, n2} int32 (quota mode),
+ * thresholds [B,2] = {T_low, T_high} fp32 (threshold mode): device.  max_windows: host bound on windows per
+ * sequence (<= 8192).   Outputs (device): bits [total_win] uint8; perm [total_win] int32, per sequence the
+ * window indices of class 2, then 4, 8, 16, each ascending; seg_windows [B,4] counts {n2,n4,n8,n16}.        */
+int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
+                   const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
+                   int32_t* perm, int32_t* seg_windows);
+
+/* ---- packed mixed-precision cache of one layer (layout: see the header comment) -------------------------- */
+typedef struct {
+    int32_t B, Hkv, hd, group;
+    int32_t dtype16;       /* WQ_BF16 or WQ_F16: element type of k16/v16                                   */
+    int32_t reserved;
+    void* codes[3];        /* device, wq_packed_bytes(bits, cap[c], ...) bytes each                         */
+    void* meta[3];         /* device                                                                        */
+    int64_t cap[3];        /* host: capacity in tokens per (plane, head), multiple of 32                    */
+    int32_t* cls_off[3];   /* device [B+1], written by wq_reorder_quantize                                  */
+    int32_t* cls_len[3];   /* device [B],   written by wq_reorder_quantize                                  */
+    void* k16;             /* device [cap16][Hkv][hd]                                                       */
+    void* v16;
+    int64_t cap16;         /* host                                                                          */
+    int32_t* off16;        /* device [B+1], set by the caller: first row of each sequence, [B] = end        */
+    int32_t* len16;        /* device [B], written by wq_reorder_quantize, bumped by the caller on append    */
+} wq_packed_kv;
+
+/* ---- a3: reorder + quantize + pack (Alg. 2, prefill half) ------------------------------------------------
+ * K, V [total_rows, Hkv, hd] device, element type `dtype`; sequence b owns rows kv_off[b]..kv_off[b+1]-1:
+ * its windows first, then tail and text rows (kept 16-bit).  bits/perm/seg_windows as written by
+ * wq_assign_bits.  dtype16 must be WQ_BF16 for bf16 input, WQ_F16 for fp16 and fp32 input (fp32 values are
+ * rounded to nearest even).  total_rows: host copy of kv_off[B].  Fills every field of *out marked
+ * "written"; all of out's pointers and capacities are set by the caller.                                    */
+int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
+                        const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
+                        const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out);
+
+/* ---- a4: decode attention over the packed cache (Alg. 2, decode half) -------------------------------------
+ * out[b,h,:] = sum_t softmax_t(sm_scale * q[b,h].k^_t) v^_t over the 2-, 4-, 8- and 16-bit segments of
+ * sequence b, one softmax over all of them, no mask (Sec. 2.1); head h reads KV head h/(Hq/Hkv).
+ * Codes are expanded in registers; the token axis is split over num_splits workgroups per (b, KV head)
+ * and merged by log-sum-exp in a fixed order (deterministic, no float atomics).
+ * q [B,Hq,hd] device, element type q_dtype; out [B,Hq,hd] device fp32; lse [B,Hq] device fp32 or NULL
+ * (natural-log sum of exp of the scaled logits).  num_splits 0 = automatic.  max_seq_tokens: host bound on
+ * tokens of any one sequence (used only to size the automatic split).  algo: WQ_DECODE_AUTO picks the
+ * matrix-core kernel when hd/group == 2, else the generic one.                                               */
+int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
+                        float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WQ_H */

@@ -268,7 +268,7 @@ void wqo_rank_by_counting(const float *s, int W, int first, int32_t *rank)
 /*   zero-point is kept in its floating form, the group minimum:              */
 /*        code = rne((x - m) / s),   x^ = m + s * code.                        */
 /*   Exact fp32 sequence (no fused multiply-add), s and m stored as binary16:  */
-/*        lo = min x, hi = max x                                               */
+/*        lo = min x (-0 counts as +0), hi = max x                             */
 /*        m  = f16(lo)                  r  = hi - m                            */
 /*        s  = f16(r / qmax)            if s == 0: s = 1                       */
 /*        inv = 1.0f / s                                                       */
@@ -284,6 +284,8 @@ void wqo_quantize_group(const float *x, int n, int bits, uint8_t *codes, uint16_
         if (x[i] > hi)
             hi = x[i];
     }
+    if (lo == 0.0f)
+        lo = 0.0f;                                /* a zero minimum is stored as +0 */
     int qmax = (1 << bits) - 1;
     uint16_t mb = wqo_f32_to_f16_bits(lo);
     volatile float m = (float)wqo_f16_bits_to_f64(mb);

@@ -1,0 +1,221 @@
+// C-ABI entry points of libwq: context handling, host-side argument validation, dispatch.
+// Every check that needs only host data happens here, before anything is enqueued.
+#include <new>
+#include <string.h>
+
+#include "wq_internal.h"
+
+namespace {
+
+bool shape_ok(int Hkv, int hd, int group)
+{
+    return Hkv > 0 && (hd == 64 || hd == 128) && (group == 32 || group == 64 || group == 128) && hd % group == 0;
+}
+
+bool dtype_ok(int d) { return d == WQ_F32 || d == WQ_BF16 || d == WQ_F16; }
+
+int check_packed(wq_ctx* ctx, const wq_packed_kv* kv, int B, bool need_tables)
+{
+    if (!kv) return wq_fail(ctx, WQ_ERR_ARG, "packed cache descriptor is NULL");
+    if (kv->B != B) return wq_fail(ctx, WQ_ERR_ARG, "packed cache is for B=%d, call has B=%d", kv->B, B);
+    if (!shape_ok(kv->Hkv, kv->hd, kv->group))
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "unsupported shape Hkv=%d hd=%d group=%d", kv->Hkv, kv->hd, kv->group);
+    if (kv->dtype16 != WQ_BF16 && kv->dtype16 != WQ_F16)
+        return wq_fail(ctx, WQ_ERR_ARG, "dtype16 must be WQ_BF16 or WQ_F16");
+    for (int c = 0; c < 3; c++) {
+        if (kv->cap[c] < 0 || kv->cap[c] % 32 != 0)
+            return wq_fail(ctx, WQ_ERR_ARG, "cap[%d]=%lld is not a non-negative multiple of 32", c, (long long)kv->cap[c]);
+        if (kv->cap[c] > (int64_t)1 << 30) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "cap[%d] too large", c);
+        if (kv->cap[c] > 0 && (!kv->codes[c] || !kv->meta[c]))
+            return wq_fail(ctx, WQ_ERR_ARG, "class %d has capacity but NULL codes/meta", c);
+        if (need_tables && (!kv->cls_off[c] || !kv->cls_len[c]))
+            return wq_fail(ctx, WQ_ERR_ARG, "class %d offset/length tables are NULL", c);
+    }
+    if (kv->cap16 < 0 || kv->cap16 > (int64_t)1 << 30) return wq_fail(ctx, WQ_ERR_ARG, "bad cap16");
+    if (kv->cap16 > 0 && (!kv->k16 || !kv->v16)) return wq_fail(ctx, WQ_ERR_ARG, "16-bit segment has capacity but NULL k16/v16");
+    if (!kv->off16 || !kv->len16) return wq_fail(ctx, WQ_ERR_ARG, "off16/len16 tables are NULL");
+    return WQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes)
+{
+    if (!out) return WQ_ERR_ARG;
+    *out = nullptr;
+    wq_ctx* ctx = new (std::nothrow) wq_ctx();
+    if (!ctx) return WQ_ERR_ARG;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->ws = static_cast<char*>(workspace);
+    ctx->ws_bytes = workspace_bytes;
+    ctx->owns_ws = false;
+    ctx->err[0] = 0;
+    if (!workspace && workspace_bytes > 0) {
+        void* p = nullptr;
+        if (hipMalloc(&p, workspace_bytes) != hipSuccess) {
+            delete ctx;
+            return WQ_ERR_HIP;
+        }
+        ctx->ws = static_cast<char*>(p);
+        ctx->owns_ws = true;
+    }
+    if (ctx->ws && ctx->ws_bytes >= WQ_WS_HEADER && ctx->owns_ws) {
+        if (hipMemsetAsync(ctx->ws, 0, WQ_WS_HEADER, ctx->stream) != hipSuccess) {
+            (void)hipFree(ctx->ws);
+            delete ctx;
+            return WQ_ERR_HIP;
+        }
+    }
+    *out = ctx;
+    return WQ_OK;
+}
+
+int wq_destroy(wq_ctx* ctx)
+{
+    if (!ctx) return WQ_OK;
+    if (ctx->owns_ws && ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+    return WQ_OK;
+}
+
+int wq_set_stream(wq_ctx* ctx, void* hip_stream)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    return WQ_OK;
+}
+
+const char* wq_last_error(const wq_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+int wq_device_status(wq_ctx* ctx, uint32_t* bits)
+{
+    if (!ctx || !bits) return WQ_ERR_ARG;
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    WQ_HIP_CHECK(ctx, hipMemcpyAsync(bits, ctx->ws, sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+    WQ_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+    WQ_HIP_CHECK(ctx, hipMemsetAsync(ctx->ws, 0, sizeof(uint32_t), ctx->stream));
+    return WQ_OK;
+}
+
+size_t wq_workspace_bytes(int B, int Hq, int hd, int max_splits, int64_t total_vis, int64_t total_txt, int D)
+{
+    size_t a = wq_decode_ws_bytes(B, Hq, hd, max_splits);
+    size_t b = wq_scores_ws_bytes(B, total_vis, total_txt, D);
+    size_t c = wq_align256(sizeof(int32_t) * (size_t)(B > 0 ? B + 1 : 1));   // prefix of 16-bit rows (a3)
+    size_t m = a > b ? a : b;
+    if (c > m) m = c;
+    return WQ_WS_HEADER + m;
+}
+
+size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group, size_t* meta_bytes)
+{
+    if (meta_bytes) *meta_bytes = 0;
+    if (!(bits == 2 || bits == 4 || bits == 8) || cap_tokens < 0 || !shape_ok(Hkv, hd, group)) return 0;
+    int64_t cap = (cap_tokens + 31) / 32 * 32;
+    if (meta_bytes) *meta_bytes = (size_t)2 * Hkv * cap * (hd / group) * 4;
+    return (size_t)2 * Hkv * cap * hd * bits / 8;
+}
+
+int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens)
+{
+    if (B <= 0 || Hkv <= 0) return 1;
+    // aim at ~4 workgroups per compute unit (256 CUs), but keep at least 256 tokens per split
+    int64_t want = (1024 + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
+    int64_t most = max_seq_tokens > 0 ? (max_seq_tokens + 255) / 256 : 1;
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    if (want > 256) want = 256;
+    return (int)want;
+}
+
+int wq_window_scores(wq_ctx* ctx, const void* vis_emb, const void* txt_emb, int dtype, int B, int D,
+                     const int32_t* vis_off, const int32_t* txt_off, const int32_t* win_size, const int32_t* win_off,
+                     int64_t total_vis, int64_t total_txt, int64_t total_win, int algo, float* scores)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || D <= 0 || total_vis < 0 || total_txt < 0 || total_win < 0)
+        return wq_fail(ctx, WQ_ERR_ARG, "negative size (B=%d D=%d)", B, D);
+    if (!dtype_ok(dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown dtype %d", dtype);
+    if (algo != WQ_SCORE_AUTO && algo != WQ_SCORE_PAIRWISE_MFMA && algo != WQ_SCORE_POOLED)
+        return wq_fail(ctx, WQ_ERR_ARG, "unknown scoring algorithm %d", algo);
+    if (total_vis > INT32_MAX || total_txt > INT32_MAX) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "too many rows");
+    if (B == 0 || total_win == 0) return WQ_OK;
+    if (!vis_off || !txt_off || !win_size || !win_off || !scores) return wq_fail(ctx, WQ_ERR_ARG, "NULL table or output");
+    if ((total_vis > 0 && !vis_emb) || (total_txt > 0 && !txt_emb)) return wq_fail(ctx, WQ_ERR_ARG, "NULL embeddings");
+    if (algo == WQ_SCORE_PAIRWISE_MFMA && dtype == WQ_F32)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path takes bf16 or fp16 embeddings");
+    if (algo == WQ_SCORE_PAIRWISE_MFMA && D % 8 != 0)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path needs D %% 8 == 0");
+    if (ctx->ws_bytes < WQ_WS_HEADER + wq_scores_ws_bytes(B, total_vis, total_txt, D))
+        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for scoring");
+    return wq_launch_scores(ctx, vis_emb, txt_emb, dtype, B, D, vis_off, txt_off, win_size, win_off, total_vis,
+                            total_txt, total_win, algo, scores);
+}
+
+int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
+                   const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
+                   int32_t* perm, int32_t* seg_windows)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || max_windows < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    if (mode != WQ_MODE_QUOTA && mode != WQ_MODE_THRESHOLD) return wq_fail(ctx, WQ_ERR_ARG, "unknown mode %d", mode);
+    if (top_bits != 8 && top_bits != 16) return wq_fail(ctx, WQ_ERR_ARG, "top_bits must be 8 or 16, got %d", top_bits);
+    if (max_windows > WQ_MAX_WINDOWS)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "more than %d windows per sequence", WQ_MAX_WINDOWS);
+    if (B == 0) return WQ_OK;
+    if (!win_off || !seg_windows) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
+    if (max_windows > 0 && (!scores || !bits || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL scores or output");
+    if (mode == WQ_MODE_QUOTA && !quota) return wq_fail(ctx, WQ_ERR_ARG, "quota mode without quota table");
+    if (mode == WQ_MODE_THRESHOLD && !thresholds) return wq_fail(ctx, WQ_ERR_ARG, "threshold mode without thresholds");
+    return wq_launch_assign(ctx, scores, B, win_off, max_windows, mode, quota, thresholds, top_bits, pin_first != 0,
+                            bits, perm, seg_windows);
+}
+
+int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
+                        const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
+                        const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || total_rows < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    if (!dtype_ok(dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown dtype %d", dtype);
+    int rc = check_packed(ctx, out, B, true);
+    if (rc != WQ_OK) return rc;
+    if ((dtype == WQ_BF16) != (out->dtype16 == WQ_BF16))
+        return wq_fail(ctx, WQ_ERR_ARG, "dtype16 must be bf16 for bf16 input and fp16 for fp16/fp32 input");
+    if (total_rows > INT32_MAX) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "too many rows");
+    if (B == 0) return WQ_OK;
+    if (!kv_off || !win_size || !win_off || !seg_windows) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
+    if (total_rows > 0 && (!K || !V || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL K, V or perm");
+    if (ctx->ws_bytes < WQ_WS_HEADER + wq_align256(sizeof(int32_t) * (size_t)(B + 1)))
+        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for reorder_quantize");
+    return wq_launch_quantize(ctx, K, V, dtype, B, kv_off, win_size, win_off, perm, seg_windows, total_rows, out);
+}
+
+int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
+                        float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
+    if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
+    int rc = check_packed(ctx, kv, B, true);
+    if (rc != WQ_OK) return rc;
+    if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
+                       Hq, kv->Hkv, WQ_MAX_REP);
+    if (algo != WQ_DECODE_AUTO && algo != WQ_DECODE_GENERIC && algo != WQ_DECODE_MFMA)
+        return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
+    if (algo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
+    if (num_splits < 0 || num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
+    if (!(sm_scale == sm_scale)) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale is NaN");
+    if (B == 0) return WQ_OK;
+    if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
+    if (num_splits == 0) num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
+    if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, num_splits))
+        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for %d splits", num_splits);
+    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse);
+}
+
+}  // extern "C"

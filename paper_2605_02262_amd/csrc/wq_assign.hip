@@ -1,0 +1,95 @@
+// a2: bit-width per window and the stable class order (Sec. 3.2.1 threshold rule, Sec. 3.2.2 first-window
+// pin, Alg. 2 prefill loop; rank/quota rule).  One workgroup per sequence; at most WQ_MAX_WINDOWS windows.
+// Ranks come from counting (rank_i = #{j : s_j > s_i or (s_j == s_i and j < i)}), which needs no sort and is
+// exact on fp32 compares; class positions come from counting equal-class predecessors.  Integer-only
+// results, so the output is bit-exact by construction.
+#include "wq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ int class_of(int bits) { return bits == 2 ? 0 : (bits == 4 ? 1 : (bits == 8 ? 2 : 3)); }
+
+__global__ __launch_bounds__(256) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
+                                                const int32_t* __restrict__ quota, const float* __restrict__ thresholds,
+                                                int top_bits, int pin_first, uint8_t* __restrict__ bits,
+                                                int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
+{
+    __shared__ float s_key[WQ_MAX_WINDOWS];
+    __shared__ uint8_t s_bits[WQ_MAX_WINDOWS];
+    __shared__ int s_cnt[4];
+    const int b = blockIdx.x;
+    const int w0 = win_off[b];
+    int W = win_off[b + 1] - w0;
+    if (W > WQ_MAX_WINDOWS) W = WQ_MAX_WINDOWS;   // host validated max_windows; never index past the arrays
+    const int tid = threadIdx.x;
+    if (tid < 4) s_cnt[tid] = 0;
+    for (int i = tid; i < W; i += 256) {
+        float s = scores[w0 + i];
+        s_key[i] = (s != s) ? -INFINITY : s;
+    }
+    __syncthreads();
+
+    if (mode == WQ_MODE_THRESHOLD) {
+        float lo = thresholds[2 * b], hi = thresholds[2 * b + 1];
+        for (int i = tid; i < W; i += 256) {
+            float s = scores[w0 + i];   // raw value: NaN compares false both ways -> 4
+            int bt = s > hi ? top_bits : (s < lo ? 2 : 4);
+            if (pin_first && i == 0) bt = top_bits;
+            s_bits[i] = (uint8_t)bt;
+        }
+    } else {
+        int n_top = quota[3 * b], n4 = quota[3 * b + 1];
+        int first = 0;
+        if (pin_first && W > 0) {
+            first = 1;
+            if (n_top > 0) n_top--;
+            else if (n4 > 0) n4--;
+        }
+        int n = W - first;
+        n_top = min(max(n_top, 0), n);
+        n4 = min(max(n4, 0), n - n_top);
+        for (int i = tid; i < W; i += 256) {
+            int bt;
+            if (i < first) {
+                bt = top_bits;
+            } else {
+                float si = s_key[i];
+                int r = 0;
+                for (int j = first; j < W; j++) {
+                    float sj = s_key[j];
+                    r += (sj > si || (sj == si && j < i)) ? 1 : 0;
+                }
+                bt = r < n_top ? top_bits : (r < n_top + n4 ? 4 : 2);
+            }
+            s_bits[i] = (uint8_t)bt;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < W; i += 256) {
+        bits[w0 + i] = s_bits[i];
+        atomicAdd(&s_cnt[class_of(s_bits[i])], 1);   // integer counts: order-independent
+    }
+    __syncthreads();
+    if (tid < 4) seg_windows[4 * b + tid] = s_cnt[tid];
+    for (int i = tid; i < W; i += 256) {
+        int c = class_of(s_bits[i]);
+        int pos = 0;
+        for (int k = 0; k < c; k++) pos += s_cnt[k];
+        uint8_t me = s_bits[i];
+        for (int j = 0; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
+        perm[w0 + pos] = i;
+    }
+}
+
+}  // namespace
+
+int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
+                     const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
+                     int32_t* perm, int32_t* seg_windows)
+{
+    (void)max_windows;
+    hipLaunchKernelGGL(k_assign, dim3(B), dim3(256), 0, ctx->stream, scores, win_off, mode, quota, thresholds, top_bits,
+                       pin_first, bits, perm, seg_windows);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}

@@ -1,0 +1,299 @@
+// a4: decode attention over the packed mixed-precision cache (Alg. 2 decode half; Sec. 3.3.2 shows that the
+// block order does not matter without a mask, which is also what makes the split over tokens legal).
+//
+// One workgroup per (split, KV head, sequence) walks its share of the 2-, 4-, 8- and 16-bit segments with an
+// online softmax (running max m, running sum l, unnormalised accumulator), writes one partial (m, l, acc) per
+// query head; k_combine merges the partials of all splits by log-sum-exp in split order.  No float atomics:
+// the result is deterministic for a given split count.
+//
+// k_decode_generic: plain vector-ALU kernel that reads codes field by field from the storage layout.  It
+// handles every supported (hd, group) and is the reference implementation inside the library; the
+// matrix-core kernel in wq_decode_mfma.hip is the fast path for hd/group == 2.
+#include "wq_internal.h"
+
+namespace {
+
+struct DecodeArgs {
+    const void* q;
+    int q_dtype;
+    int B, Hq, rep, splits;
+    float sm_scale;
+    wq_packed_kv kv;
+    float* part;   // [B][Hkv][splits][rep][hd + 2]
+};
+
+__device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
+{
+    if (dtype == WQ_F32) return static_cast<const float*>(q)[i];
+    if (dtype == WQ_BF16) return wq_bf16_bits_to_float(static_cast<const uint16_t*>(q)[i]);
+    return wq_f16_bits_to_float(static_cast<const uint16_t*>(q)[i]);
+}
+
+// field n (BITS wide) of a little-endian packed byte image
+template <int BITS>
+__device__ __forceinline__ int field(const uint8_t* base, int64_t n)
+{
+    int64_t bit = n * BITS;
+    return (base[bit >> 3] >> (bit & 7)) & ((1 << BITS) - 1);
+}
+
+template <int HD>
+struct Smem {
+    float q[WQ_MAX_REP][HD];
+    float logit[WQ_MAX_REP][32];
+    float p[WQ_MAX_REP][32];
+    float red[256 / HD][WQ_MAX_REP][HD];
+};
+
+// One 32-token step: logits are in sm.logit (-inf for invalid tokens); updates m, l, rescales acc and leaves
+// the weights in sm.p.  Every thread executes the same arithmetic in the same order, so all copies of m and l agree.
+template <int HD>
+__device__ __forceinline__ void softmax_step(Smem<HD>& sm, int rep, float* m, float* l, float* acc)
+{
+    const int tid = threadIdx.x;
+    for (int r = 0; r < rep; r++) {
+        float bm = -INFINITY;
+        for (int u = 0; u < 32; u++) bm = fmaxf(bm, sm.logit[r][u]);
+        float mn = fmaxf(m[r], bm);
+        float sc = (mn == -INFINITY) ? 1.0f : __expf(m[r] - mn);
+        acc[r] *= sc;
+        float ls = 0.f;
+        for (int u = 0; u < 32; u++) ls += (mn == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - mn);
+        l[r] = l[r] * sc + ls;
+        m[r] = mn;
+    }
+    if (tid < rep * 32) {
+        int r = tid >> 5, u = tid & 31;
+        sm.p[r][u] = (m[r] == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - m[r]);
+    }
+    __syncthreads();
+}
+
+template <int HD, int BITS>
+__device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int split, float* m, float* l, float* acc)
+{
+    constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
+    constexpr int Q = HD / 4, CT = HD / 16, PARTS = 256 / HD;
+    const wq_packed_kv& kv = a.kv;
+    const int tid = threadIdx.x;
+    const int G = HD / kv.group;
+    const int len = kv.cls_len[C][b];
+    const int nblk = (len + 31) / 32;
+    const int blk_lo = (int)((int64_t)split * nblk / a.splits), blk_hi = (int)((int64_t)(split + 1) * nblk / a.splits);
+    const int64_t tok_base = kv.cls_off[C][b];
+    const int64_t cap = kv.cap[C];
+    const uint8_t* kcodes = static_cast<const uint8_t*>(kv.codes[C]) + (int64_t)kvh * cap * HD * BITS / 8;
+    const uint8_t* vcodes = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kv.Hkv + kvh) * cap * HD * BITS / 8;
+    const uint32_t* kmeta = static_cast<const uint32_t*>(kv.meta[C]) + (int64_t)kvh * cap * G;
+    const uint32_t* vmeta = static_cast<const uint32_t*>(kv.meta[C]) + ((int64_t)kv.Hkv + kvh) * cap * G;
+
+    for (int blk = blk_lo; blk < blk_hi; blk++) {
+        const int64_t t0 = tok_base + (int64_t)blk * 32;       // absolute token slot of the block
+        // ---- logits: thread = (token u, eighth p of the channels) ----
+        {
+            const int u = tid >> 3, p = tid & 7;
+            const int64_t t = t0 + u;
+            const int64_t tile = t >> 4;
+            const int mrow = (int)(t & 15);
+            const uint8_t* tb = kcodes + tile * (16 * HD * BITS / 8);
+            float part[WQ_MAX_REP];
+#pragma unroll
+            for (int r = 0; r < WQ_MAX_REP; r++) part[r] = 0.f;
+            for (int i = 0; i < HD / 8; i++) {
+                int ch = p * (HD / 8) + i;
+                int j = ch / Q, e = ch % Q;
+                int code = field<BITS>(tb, (int64_t)(j * 16 + mrow) * Q + e);
+                uint32_t w = kmeta[(tile * G + ch / kv.group) * 16 + mrow];
+                float kh = fmaf(wq_f16_bits_to_float(w & 0xFFFF), (float)code, wq_f16_bits_to_float(w >> 16));
+#pragma unroll
+                for (int r = 0; r < WQ_MAX_REP; r++)
+                    if (r < a.rep) part[r] = fmaf(sm.q[r][ch], kh, part[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < WQ_MAX_REP; r++) {
+                float v = part[r];
+                v += __shfl_xor(v, 1, 64);
+                v += __shfl_xor(v, 2, 64);
+                v += __shfl_xor(v, 4, 64);
+                if (p == 0 && r < a.rep) sm.logit[r][u] = (blk * 32 + u < len) ? v * a.sm_scale : -INFINITY;
+            }
+        }
+        __syncthreads();
+        softmax_step<HD>(sm, a.rep, m, l, acc);
+        // ---- values: thread = (channel c, token part tp) ----
+        {
+            const int c = tid % HD, tp = tid / HD;
+            const int ct = c / 16, mm = c % 16;
+            const uint8_t* vb = vcodes + (t0 >> 5) * (32 * HD * BITS / 8);
+            for (int u = tp * (32 / PARTS); u < (tp + 1) * (32 / PARTS); u++) {
+                int jj = (u % 16) / 4, tau = 4 * (u / 16) + u % 4;
+                int code = field<BITS>(vb, ((int64_t)(jj * 16 + mm) * CT + ct) * 8 + tau);
+                const int64_t t = t0 + u;
+                uint32_t w = vmeta[((t >> 4) * G + c / kv.group) * 16 + (t & 15)];
+                float vh = fmaf(wq_f16_bits_to_float(w & 0xFFFF), (float)code, wq_f16_bits_to_float(w >> 16));
+#pragma unroll
+                for (int r = 0; r < WQ_MAX_REP; r++)
+                    if (r < a.rep) acc[r] = fmaf(sm.p[r][u], vh, acc[r]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int HD>
+__device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int split, float* m, float* l, float* acc)
+{
+    constexpr int PARTS = 256 / HD;
+    const wq_packed_kv& kv = a.kv;
+    const int tid = threadIdx.x;
+    const int len = kv.len16[b];
+    const int nblk = (len + 31) / 32;
+    const int blk_lo = (int)((int64_t)split * nblk / a.splits), blk_hi = (int)((int64_t)(split + 1) * nblk / a.splits);
+    const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16);
+    const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16);
+    const bool bf = kv.dtype16 == WQ_BF16;
+    for (int blk = blk_lo; blk < blk_hi; blk++) {
+        {
+            const int u = tid >> 3, p = tid & 7;
+            const int i = blk * 32 + u;
+            const bool valid = i < len;
+            const int64_t row = ((int64_t)kv.off16[b] + (valid ? i : 0)) * kv.Hkv + kvh;
+            float part[WQ_MAX_REP];
+#pragma unroll
+            for (int r = 0; r < WQ_MAX_REP; r++) part[r] = 0.f;
+            for (int k = 0; k < HD / 8; k++) {
+                int ch = p * (HD / 8) + k;
+                uint32_t h = valid ? k16[row * HD + ch] : 0;
+                float kh = bf ? wq_bf16_bits_to_float(h) : wq_f16_bits_to_float(h);
+#pragma unroll
+                for (int r = 0; r < WQ_MAX_REP; r++)
+                    if (r < a.rep) part[r] = fmaf(sm.q[r][ch], kh, part[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < WQ_MAX_REP; r++) {
+                float v = part[r];
+                v += __shfl_xor(v, 1, 64);
+                v += __shfl_xor(v, 2, 64);
+                v += __shfl_xor(v, 4, 64);
+                if (p == 0 && r < a.rep) sm.logit[r][u] = valid ? v * a.sm_scale : -INFINITY;
+            }
+        }
+        __syncthreads();
+        softmax_step<HD>(sm, a.rep, m, l, acc);
+        {
+            const int c = tid % HD, tp = tid / HD;
+            for (int u = tp * (32 / PARTS); u < (tp + 1) * (32 / PARTS); u++) {
+                const int i = blk * 32 + u;
+                if (i >= len) break;
+                const int64_t row = ((int64_t)kv.off16[b] + i) * kv.Hkv + kvh;
+                uint32_t h = v16[row * HD + c];
+                float vh = bf ? wq_bf16_bits_to_float(h) : wq_f16_bits_to_float(h);
+#pragma unroll
+                for (int r = 0; r < WQ_MAX_REP; r++)
+                    if (r < a.rep) acc[r] = fmaf(sm.p[r][u], vh, acc[r]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
+{
+    __shared__ Smem<HD> sm;
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < a.rep * HD; i += 256) {
+        int r = i / HD, ch = i % HD;
+        sm.q[r][ch] = load_q(a.q, a.q_dtype, ((int64_t)b * a.Hq + kvh * a.rep + r) * HD + ch);
+    }
+    __syncthreads();
+    float m[WQ_MAX_REP], l[WQ_MAX_REP], acc[WQ_MAX_REP];
+#pragma unroll
+    for (int r = 0; r < WQ_MAX_REP; r++) {
+        m[r] = -INFINITY;
+        l[r] = 0.f;
+        acc[r] = 0.f;
+    }
+    walk_class<HD, 2>(a, sm, b, kvh, split, m, l, acc);
+    walk_class<HD, 4>(a, sm, b, kvh, split, m, l, acc);
+    walk_class<HD, 8>(a, sm, b, kvh, split, m, l, acc);
+    walk_seg16<HD>(a, sm, b, kvh, split, m, l, acc);
+
+    // reduce the token parts, write the partial
+    constexpr int PARTS = 256 / HD;
+    const int c = tid % HD, tp = tid / HD;
+    for (int r = 0; r < a.rep; r++) sm.red[tp][r][c] = acc[r];
+    __syncthreads();
+    float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.splits + split) * a.rep * (HD + 2);
+    if (tp == 0) {
+        for (int r = 0; r < a.rep; r++) {
+            float s = 0.f;
+            for (int k = 0; k < PARTS; k++) s += sm.red[k][r][c];
+            out[r * (HD + 2) + c] = s;
+        }
+    }
+    if (tid < a.rep) {
+        out[tid * (HD + 2) + HD] = m[tid];
+        out[tid * (HD + 2) + HD + 1] = l[tid];
+    }
+}
+
+// out[b,h,:] = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M},  M = max_s m_s;  lse = M + log(sum)
+__global__ void k_combine(const float* __restrict__ part, int Hq, int rep, int splits, int hd, float* __restrict__ out,
+                          float* __restrict__ lse)
+{
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int kvh = h / rep, r = h % rep;
+    const int Hkv = Hq / rep;
+    const int c = threadIdx.x;
+    const float* base = part + (((int64_t)b * Hkv + kvh) * splits) * rep * (hd + 2) + (int64_t)r * (hd + 2);
+    const int64_t stride = (int64_t)rep * (hd + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < splits; s++) M = fmaxf(M, base[s * stride + hd]);
+    float L = 0.f, acc = 0.f;
+    for (int s = 0; s < splits; s++) {
+        float ms = base[s * stride + hd];
+        if (ms == -INFINITY) continue;
+        float w = __expf(ms - M);
+        L = fmaf(base[s * stride + hd + 1], w, L);
+        acc = fmaf(base[s * stride + c], w, acc);
+    }
+    out[((int64_t)b * Hq + h) * hd + c] = L > 0.f ? acc / L : 0.f;
+    if (lse && c == 0) lse[(int64_t)b * Hq + h] = L > 0.f ? M + logf(L) : -INFINITY;
+}
+
+}  // namespace
+
+size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
+{
+    if (B <= 0 || Hq <= 0 || hd <= 0 || splits <= 0) return 0;
+    return wq_align256(sizeof(float) * (size_t)B * Hq * splits * (hd + 2));
+}
+
+int wq_launch_decode_mfma(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
+                          int num_splits, float* part);
+
+int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
+                     int num_splits, int algo, float* out, float* lse)
+{
+    DecodeArgs a;
+    a.q = q;
+    a.q_dtype = q_dtype;
+    a.B = B;
+    a.Hq = Hq;
+    a.rep = Hq / kv->Hkv;
+    a.splits = num_splits;
+    a.sm_scale = sm_scale;
+    a.kv = *kv;
+    a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
+    dim3 grid(num_splits, kv->Hkv, B);
+    (void)algo;
+    if (kv->hd == 128)
+        hipLaunchKernelGGL(k_decode_generic<128>, grid, dim3(256), 0, ctx->stream, a);
+    else
+        hipLaunchKernelGGL(k_decode_generic<64>, grid, dim3(256), 0, ctx->stream, a);
+    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(kv->hd), 0, ctx->stream, a.part, Hq, a.rep, num_splits, kv->hd, out, lse);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}

@@ -1,0 +1,82 @@
+// Internal declarations shared by the translation units of libwq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/wq.h"
+
+struct wq_ctx {
+    hipStream_t stream;
+    char* ws;            // device workspace
+    size_t ws_bytes;
+    bool owns_ws;
+    char err[256];
+};
+
+constexpr size_t WQ_WS_HEADER = 256;   // status word lives in the first bytes of the workspace
+constexpr int WQ_MAX_REP = 8;          // query heads per KV head
+constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
+
+inline int wq_fail(wq_ctx* ctx, int code, const char* fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define WQ_HIP_CHECK(ctx, expr)                                                              \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) return wq_fail(ctx, WQ_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline size_t wq_align256(size_t x) { return (x + 255) & ~size_t(255); }
+inline uint32_t* wq_status_ptr(wq_ctx* ctx) { return reinterpret_cast<uint32_t*>(ctx->ws); }
+
+// element loads -> float (exact for all three storage types)
+__device__ __forceinline__ float wq_ld(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float wq_ld(const __hip_bfloat16* p, int64_t i)
+{
+    return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(p)[i]) << 16);
+}
+__device__ __forceinline__ float wq_ld(const __half* p, int64_t i) { return __half2float(p[i]); }
+
+__device__ __forceinline__ float wq_bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ float wq_f16_bits_to_float(uint32_t h)
+{
+    return __half2float(__ushort_as_half(static_cast<unsigned short>(h)));
+}
+
+// first b in [0,B) with off[b+1] > x  (off ascending, off[0] <= x < off[B] assumed)
+__device__ __forceinline__ int wq_find_seq(const int32_t* off, int B, int64_t x)
+{
+    int lo = 0, hi = B;            // invariant: off[lo] <= x < off[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (off[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// launchers (one per stage), defined next to their kernels
+int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, int B, int D, const int32_t* vis_off,
+                     const int32_t* txt_off, const int32_t* win_size, const int32_t* win_off, int64_t total_vis,
+                     int64_t total_txt, int64_t total_win, int algo, float* scores);
+int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
+                     const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
+                     int32_t* perm, int32_t* seg_windows);
+int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
+                       const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
+                       const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out);
+int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
+                     int num_splits, int algo, float* out, float* lse);
+size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits);
+size_t wq_scores_ws_bytes(int B, int64_t total_vis, int64_t total_txt, int D);

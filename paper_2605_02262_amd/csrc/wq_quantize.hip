@@ -1,0 +1,282 @@
+// a3: reorder + asymmetric round-to-nearest quantization + packing (Sec. 3.3.1, Sec. 3.3.3, Alg. 2 prefill half).
+//
+//   k_plan      one workgroup: per-class padded offsets / lengths of every sequence, 16-bit row counts,
+//               capacity checks (device status word)
+//   k_quantize  one workgroup per (32-token destination block, KV head): gathers the source rows through
+//               perm (the window reorder is fused into the load), finds each group's min/max with
+//               wavefront shuffles, computes codes with the exact fp32 sequence of the format definition,
+//               stages them in LDS and writes the K tile / V block / metadata images with coalesced stores
+//   k_copy16    16-bit windows, video tail and text rows -> k16/v16
+// HBM-bound: reads 2 x 2 bytes per (K,V) element pair once, writes b/8 + 4/group bytes per element.
+// This file is compiled with floating-point contraction off: the code sequence must round exactly as stated.
+#include <type_traits>
+
+#include "wq_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+__device__ __forceinline__ int pad32(int n) { return (n + 31) & ~31; }
+
+__global__ __launch_bounds__(256) void k_plan(int B, const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
+                                              const int32_t* __restrict__ win_off, const int32_t* __restrict__ seg_windows,
+                                              wq_packed_kv pk, int32_t* __restrict__ pre16, uint32_t* __restrict__ status)
+{
+    const int tid = threadIdx.x;
+    if (tid < 3) {
+        const int c = tid;
+        int32_t* off = pk.cls_off[c];
+        int32_t* len = pk.cls_len[c];
+        int64_t run = 0;
+        bool over = false;
+        off[0] = 0;
+        for (int b = 0; b < B; b++) {
+            int n = seg_windows[4 * b + c] * win_size[b];
+            int64_t nxt = run + pad32(n);
+            if (nxt > pk.cap[c]) {          // does not fit: drop the sequence's share of this class
+                over = true;
+                n = 0;
+                nxt = run;
+            }
+            len[b] = n;
+            run = nxt;
+            off[b + 1] = (int32_t)run;
+        }
+        if (over) atomicOr(status, WQ_DEV_CLASS_OVERFLOW);
+    } else if (tid == 3) {
+        int64_t run = 0;
+        bool over = false;
+        pre16[0] = 0;
+        for (int b = 0; b < B; b++) {
+            int W = win_off[b + 1] - win_off[b];
+            int rows = kv_off[b + 1] - kv_off[b];
+            int n = seg_windows[4 * b + 3] * win_size[b] + (rows - W * win_size[b]);
+            int room = pk.off16[b + 1] - pk.off16[b];
+            if (n > room || (int64_t)pk.off16[b] + n > pk.cap16 || pk.off16[b] < 0) {
+                over = true;
+                n = 0;
+            }
+            pk.len16[b] = n;
+            run += n;
+            pre16[b + 1] = (int32_t)run;
+        }
+        if (over) atomicOr(status, WQ_DEV_SEG16_OVERFLOW);
+    }
+}
+
+// bits -> class index
+__host__ __device__ constexpr int cls_index(int bits) { return bits == 2 ? 0 : (bits == 4 ? 1 : 2); }
+
+template <typename T, int HD, int BITS>
+__global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const T* __restrict__ V, int B, int group,
+                                                  const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
+                                                  const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
+                                                  const int32_t* __restrict__ seg_windows, wq_packed_kv pk)
+{
+    constexpr int C = cls_index(BITS);
+    constexpr int QMAX = (1 << BITS) - 1;
+    constexpr int CPT = HD / 8;                 // channels per thread: 8 threads share one token row
+    constexpr int PER_DW = 32 / BITS;           // codes per output dword
+    __shared__ __align__(16) uint8_t s_code[2][32][HD];
+    __shared__ uint32_t s_meta[2][4][32];       // [plane][group][token]
+    const int tid = threadIdx.x;
+    const int blk = blockIdx.x;
+    const int kvh = blockIdx.y;
+    const int Hkv = pk.Hkv;
+    const int G = HD / group;
+    const int32_t* off = pk.cls_off[C];
+    const int64_t tok0 = (int64_t)blk * 32;
+    if (tok0 >= off[B]) return;                 // unused capacity
+    const int b = wq_find_seq(off, B, tok0);
+    const int d0 = (int)(tok0 - off[b]);        // first destination token of the block inside the segment
+    const int len = pk.cls_len[C][b];
+    const int S = win_size[b];
+    int pos0 = 0;                               // windows of lower classes come first in perm
+    for (int c = 0; c < C; c++) pos0 += seg_windows[4 * b + c];
+
+    // ---- gather + quantize: thread = (token u, part p) -------------------------------------------------
+    const int u = tid >> 3, p = tid & 7;
+    const int d = d0 + u;
+    const bool valid = d < len;
+    int64_t src = 0;
+    if (valid) {
+        int r = d / S, o = d - r * S;
+        int win = perm[win_off[b] + pos0 + r];
+        src = (int64_t)kv_off[b] + (int64_t)win * S + o;
+    }
+    const int tpg = group / CPT;                // threads per group (2, 4 or 8; 16 when group=128, hd=64 is excluded)
+#pragma unroll
+    for (int plane = 0; plane < 2; plane++) {
+        const T* X = plane == 0 ? K : V;
+        float x[CPT];
+        float lo = INFINITY, hi = -INFINITY;
+        if (valid) {
+            const int64_t base = (src * Hkv + kvh) * HD + p * CPT;
+#pragma unroll
+            for (int i = 0; i < CPT; i++) {
+                x[i] = wq_ld(X, base + i);
+                lo = fminf(lo, x[i]);
+                hi = fmaxf(hi, x[i]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CPT; i++) x[i] = 0.f;
+            lo = hi = 0.f;
+        }
+        for (int o = 1; o < tpg; o <<= 1) {     // lanes p..p+tpg-1 of a token are adjacent lanes of one wavefront
+            lo = fminf(lo, __shfl_xor(lo, o, 64));
+            hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+        }
+        if (lo == 0.0f) lo = 0.0f;               // a zero minimum is stored as +0
+        const __half mh = __float2half_rn(lo);
+        const float m = __half2float(mh);
+        const float r = hi - m;
+        const float s0 = r / (float)QMAX;       // correctly rounded fp32 divide
+        __half sh = __float2half_rn(s0);
+        float s = __half2float(sh);
+        if (s == 0.0f) {
+            s = 1.0f;
+            sh = __float2half_rn(1.0f);
+        }
+        const float inv = 1.0f / s;
+        uint8_t* dst = &s_code[plane][u][p * CPT];
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            float t = (x[i] - m) * inv;         // contraction is off: subtract, round, multiply, round
+            float q = rintf(t);
+            q = fminf(fmaxf(q, 0.0f), (float)QMAX);
+            dst[i] = valid ? (uint8_t)(int)q : (uint8_t)0;
+        }
+        if ((p * CPT) % group == 0) {
+            uint32_t word = valid ? ((uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(mh) << 16)) : 0u;
+            s_meta[plane][(p * CPT) / group][u] = word;
+        }
+    }
+    __syncthreads();
+
+    // ---- K plane: two tiles of 16 tokens, field n = (j*16 + m)*(HD/4) + e ----------------------------------
+    {
+        constexpr int Q = HD / 4;
+        constexpr int TILE_DW = 16 * HD * BITS / 32;
+        uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(pk.codes[C]) +
+                                                   ((int64_t)kvh * pk.cap[C] + tok0) * HD * BITS / 8);
+        for (int w = tid; w < 2 * TILE_DW; w += 256) {
+            int tile = w / TILE_DW, n0 = (w - tile * TILE_DW) * PER_DW;
+            int j = n0 / (16 * Q), mrow = (n0 / Q) % 16, e0 = n0 % Q;
+            const uint8_t* srcp = &s_code[0][tile * 16 + mrow][j * Q + e0];
+            uint32_t word = 0;
+#pragma unroll
+            for (int k = 0; k < PER_DW; k++) word |= (uint32_t)srcp[k] << (k * BITS);
+            out[w] = word;
+        }
+    }
+    // ---- V plane: block of 32 tokens, field n = ((jj*16 + mm)*(HD/16) + ct)*8 + tau ----------------------
+    {
+        constexpr int CT = HD / 16;
+        constexpr int BLK_DW = 32 * HD * BITS / 32;
+        uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(pk.codes[C]) +
+                                                   (((int64_t)Hkv + kvh) * pk.cap[C] + tok0) * HD * BITS / 8);
+        for (int w = tid; w < BLK_DW; w += 256) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int k = 0; k < PER_DW; k++) {
+                int n = w * PER_DW + k;
+                int tau = n & 7, ct = (n >> 3) % CT, lane = (n >> 3) / CT;
+                int jj = lane >> 4, mm = lane & 15;
+                int tok = 16 * (tau >> 2) + 4 * jj + (tau & 3);
+                word |= (uint32_t)s_code[1][tok][16 * ct + mm] << (k * BITS);
+            }
+            out[w] = word;
+        }
+    }
+    // ---- metadata: [tile of 16][group][16 tokens] ---------------------------------------------------------
+    for (int w = tid; w < 2 * 32 * G; w += 256) {
+        int plane = w / (32 * G), r = w - plane * 32 * G;
+        int tile = r / (16 * G), gi = (r / 16) % G, mrow = r % 16;
+        uint32_t* out = static_cast<uint32_t*>(pk.meta[C]) + (((int64_t)plane * Hkv + kvh) * pk.cap[C] + tok0) * G;
+        out[r] = s_meta[plane][gi][tile * 16 + mrow];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_copy16(const T* __restrict__ K, const T* __restrict__ V, int B, int row_elems,
+                                                const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
+                                                const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
+                                                const int32_t* __restrict__ seg_windows, const int32_t* __restrict__ pre16,
+                                                wq_packed_kv pk)
+{
+    const int64_t r = blockIdx.x;               // global index over all 16-bit rows of the batch
+    if (r >= pre16[B]) return;
+    const int b = wq_find_seq(pre16, B, r);
+    const int i = (int)(r - pre16[b]);
+    const int S = win_size[b];
+    const int W = win_off[b + 1] - win_off[b];
+    const int n16w = seg_windows[4 * b + 3] * S;
+    int64_t src;
+    if (i < n16w) {
+        int pos0 = seg_windows[4 * b] + seg_windows[4 * b + 1] + seg_windows[4 * b + 2];
+        int rr = i / S, o = i - rr * S;
+        src = (int64_t)kv_off[b] + (int64_t)perm[win_off[b] + pos0 + rr] * S + o;
+    } else {
+        src = (int64_t)kv_off[b] + (int64_t)W * S + (i - n16w);
+    }
+    const int64_t dst = (int64_t)pk.off16[b] + i;
+    uint16_t* k16 = static_cast<uint16_t*>(pk.k16) + dst * row_elems;
+    uint16_t* v16 = static_cast<uint16_t*>(pk.v16) + dst * row_elems;
+    for (int e = threadIdx.x; e < row_elems; e += 256) {
+        float kx = wq_ld(K, src * row_elems + e), vx = wq_ld(V, src * row_elems + e);
+        if constexpr (std::is_same_v<T, __hip_bfloat16>) {          // bf16 -> bf16
+            k16[e] = (uint16_t)(__float_as_uint(kx) >> 16);
+            v16[e] = (uint16_t)(__float_as_uint(vx) >> 16);
+        } else {                                                           // fp16 / fp32 -> fp16 (nearest even)
+            k16[e] = __half_as_ushort(__float2half_rn(kx));
+            v16[e] = __half_as_ushort(__float2half_rn(vx));
+        }
+    }
+}
+
+template <typename T, int HD>
+int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_off, const int32_t* win_size,
+        const int32_t* win_off, const int32_t* perm, const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* pk)
+{
+    const T* K = static_cast<const T*>(K_);
+    const T* V = static_cast<const T*>(V_);
+    hipStream_t st = ctx->stream;
+    int32_t* pre16 = reinterpret_cast<int32_t*>(ctx->ws + WQ_WS_HEADER);
+    hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 0, st, B, kv_off, win_size, win_off, seg_windows, *pk, pre16,
+                       wq_status_ptr(ctx));
+    dim3 blk(256);
+    if (pk->cap[0] > 0)
+        hipLaunchKernelGGL((k_quantize<T, HD, 2>), dim3((unsigned)(pk->cap[0] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+                           kv_off, win_size, win_off, perm, seg_windows, *pk);
+    if (pk->cap[1] > 0)
+        hipLaunchKernelGGL((k_quantize<T, HD, 4>), dim3((unsigned)(pk->cap[1] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+                           kv_off, win_size, win_off, perm, seg_windows, *pk);
+    if (pk->cap[2] > 0)
+        hipLaunchKernelGGL((k_quantize<T, HD, 8>), dim3((unsigned)(pk->cap[2] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+                           kv_off, win_size, win_off, perm, seg_windows, *pk);
+    if (total_rows > 0 && pk->cap16 > 0)
+        hipLaunchKernelGGL(k_copy16<T>, dim3((unsigned)total_rows), blk, 0, st, K, V, B, pk->Hkv * HD, kv_off, win_size,
+                           win_off, perm, seg_windows, pre16, *pk);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
+
+}  // namespace
+
+int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
+                       const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
+                       const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out)
+{
+    if (out->hd == 64 && out->group == 128) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "group larger than hd");
+#define WQ_RUN(T)                                                                                                   \
+    (out->hd == 128 ? run<T, 128>(ctx, K, V, B, kv_off, win_size, win_off, perm, seg_windows, total_rows, out)      \
+                    : run<T, 64>(ctx, K, V, B, kv_off, win_size, win_off, perm, seg_windows, total_rows, out))
+    switch (dtype) {
+        case WQ_F32: return WQ_RUN(float);
+        case WQ_BF16: return WQ_RUN(__hip_bfloat16);
+        default: return WQ_RUN(__half);
+    }
+#undef WQ_RUN
+}

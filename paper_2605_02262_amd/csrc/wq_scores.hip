@@ -1,0 +1,142 @@
+// a1: window/text similarity (Sec. 3.2.1, similarity equation).
+//
+// Pooled path: by linearity the mean of all pairwise cosines of a window equals
+//     (mean_j t_j/|t_j|) . (mean_k w_k/|w_k|),
+// so every embedding row is read exactly once: the kernels are bound by HBM bandwidth.
+//   k_text_norm   one wavefront per text token  -> 1/|t_j|                       (0 for a zero row)
+//   k_text_mean   thread per channel            -> tbar[b][d] = 1/N sum_j t_j[d]/|t_j|
+//   k_token_score one wavefront per visual row  -> c_k = (w_k . tbar) / |w_k|    (0 for a zero row)
+//   k_window_mean one wavefront per window      -> score = 1/S sum_k c_k, fixed order
+// All accumulation is fp32 and every reduction has a fixed order (no atomics): results are deterministic.
+#include "wq_internal.h"
+
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_text_norm(const T* __restrict__ txt, int D, int64_t total_txt,
+                                                   float* __restrict__ inv_norm)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= total_txt) return;
+    int lane = threadIdx.x & 63;
+    const T* p = txt + row * D;
+    float ss = 0.f;
+    for (int d = lane; d < D; d += WAVE) {
+        float x = wq_ld(p, d);
+        ss = fmaf(x, x, ss);
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) inv_norm[row] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_text_mean(const T* __restrict__ txt, const float* __restrict__ inv_norm, int D,
+                                                   const int32_t* __restrict__ txt_off, float* __restrict__ tbar)
+{
+    int b = blockIdx.y;
+    int d = blockIdx.x * 256 + threadIdx.x;
+    if (d >= D) return;
+    int j0 = txt_off[b], j1 = txt_off[b + 1];
+    float acc = 0.f;
+    for (int j = j0; j < j1; j++) acc = fmaf(wq_ld(txt, (int64_t)j * D + d), inv_norm[j], acc);
+    tbar[(int64_t)b * D + d] = j1 > j0 ? acc / (float)(j1 - j0) : 0.f;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_token_score(const T* __restrict__ vis, const float* __restrict__ tbar, int D, int B,
+                                                     const int32_t* __restrict__ vis_off, int64_t total_vis,
+                                                     float* __restrict__ tok_score)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= total_vis) return;
+    int lane = threadIdx.x & 63;
+    int b = wq_find_seq(vis_off, B, row);
+    const T* p = vis + row * D;
+    const float* t = tbar + (int64_t)b * D;
+    float ss = 0.f, dt = 0.f;
+    for (int d = lane; d < D; d += WAVE) {
+        float x = wq_ld(p, d);
+        ss = fmaf(x, x, ss);
+        dt = fmaf(x, t[d], dt);
+    }
+    ss = wave_sum(ss);
+    dt = wave_sum(dt);
+    if (lane == 0) tok_score[row] = ss > 0.f ? dt / sqrtf(ss) : 0.f;
+}
+
+__global__ __launch_bounds__(256) void k_window_mean(const float* __restrict__ tok_score, int B,
+                                                     const int32_t* __restrict__ vis_off, const int32_t* __restrict__ txt_off,
+                                                     const int32_t* __restrict__ win_size, const int32_t* __restrict__ win_off,
+                                                     int64_t total_win, float* __restrict__ scores)
+{
+    int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= total_win) return;
+    int lane = threadIdx.x & 63;
+    int b = wq_find_seq(win_off, B, w);
+    int S = win_size[b];
+    int64_t r0 = (int64_t)vis_off[b] + (w - win_off[b]) * S;
+    float acc = 0.f;
+    for (int k = lane; k < S; k += WAVE) acc += tok_score[r0 + k];
+    acc = wave_sum(acc);
+    if (lane == 0) scores[w] = (S > 0 && txt_off[b + 1] > txt_off[b]) ? acc / (float)S : 0.f;
+}
+
+template <typename T>
+int run_pooled(wq_ctx* ctx, const void* vis_, const void* txt_, int B, int D, const int32_t* vis_off, const int32_t* txt_off,
+               const int32_t* win_size, const int32_t* win_off, int64_t total_vis, int64_t total_txt, int64_t total_win,
+               float* scores)
+{
+    const T* vis = static_cast<const T*>(vis_);
+    const T* txt = static_cast<const T*>(txt_);
+    char* ws = ctx->ws + WQ_WS_HEADER;
+    float* inv_norm = reinterpret_cast<float*>(ws);
+    ws += wq_align256(sizeof(float) * (size_t)(total_txt > 0 ? total_txt : 1));
+    float* tbar = reinterpret_cast<float*>(ws);
+    ws += wq_align256(sizeof(float) * (size_t)B * D);
+    float* tok_score = reinterpret_cast<float*>(ws);
+    hipStream_t st = ctx->stream;
+    if (total_txt > 0)
+        hipLaunchKernelGGL(k_text_norm<T>, dim3((unsigned)((total_txt + 3) / 4)), dim3(256), 0, st, txt, D, total_txt, inv_norm);
+    hipLaunchKernelGGL(k_text_mean<T>, dim3((D + 255) / 256, B), dim3(256), 0, st, txt, inv_norm, D, txt_off, tbar);
+    if (total_vis > 0)
+        hipLaunchKernelGGL(k_token_score<T>, dim3((unsigned)((total_vis + 3) / 4)), dim3(256), 0, st, vis, tbar, D, B, vis_off,
+                           total_vis, tok_score);
+    hipLaunchKernelGGL(k_window_mean, dim3((unsigned)((total_win + 3) / 4)), dim3(256), 0, st, tok_score, B, vis_off, txt_off,
+                       win_size, win_off, total_win, scores);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
+
+}  // namespace
+
+size_t wq_scores_ws_bytes(int B, int64_t total_vis, int64_t total_txt, int D)
+{
+    if (B <= 0 || D <= 0) return 0;
+    return wq_align256(sizeof(float) * (size_t)(total_txt > 0 ? total_txt : 1)) + wq_align256(sizeof(float) * (size_t)B * D) +
+           wq_align256(sizeof(float) * (size_t)(total_vis > 0 ? total_vis : 1));
+}
+
+int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, int B, int D, const int32_t* vis_off,
+                     const int32_t* txt_off, const int32_t* win_size, const int32_t* win_off, int64_t total_vis,
+                     int64_t total_txt, int64_t total_win, int algo, float* scores)
+{
+    if (algo == WQ_SCORE_PAIRWISE_MFMA)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "matrix-core scoring path is not built yet");
+    switch (dtype) {
+        case WQ_F32:
+            return run_pooled<float>(ctx, vis, txt, B, D, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores);
+        case WQ_BF16:
+            return run_pooled<__hip_bfloat16>(ctx, vis, txt, B, D, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores);
+        default:
+            return run_pooled<__half>(ctx, vis, txt, B, D, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores);
+    }
+}

@@ -195,8 +195,11 @@ def embeddings(w: Workload, b: int):
     s = w.seqs[b]
     rng = _rng(w, b, 0, 0)
     et = rng.standard_normal((s.n_text, w.D), dtype=np.float32)
-    u = et.astype(np.float64).mean(axis=0)
-    u = (u / np.linalg.norm(u)).astype(np.float32)
+    if s.n_text > 0:
+        u = et.astype(np.float64).mean(axis=0)
+        u = (u / np.linalg.norm(u)).astype(np.float32)
+    else:
+        u = np.zeros(w.D, dtype=np.float32)
     n_rows = s.n_vis
     alpha = rng.random(max(s.n_win, 1), dtype=np.float32)
     ev = rng.standard_normal((n_rows, w.D), dtype=np.float32)

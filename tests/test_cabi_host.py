@@ -1,0 +1,90 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and rejects bad arguments
+before touching a GPU.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2605_02262_amd", "libwq.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2605_02262_amd import build
+        build.build(verbose=False)
+    from paper_2605_02262_amd import binding
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "wq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(wq_[a-z0-9_]+)\s*\(", hdr))
+    assert {"wq_window_scores", "wq_assign_bits", "wq_reorder_quantize", "wq_decode_attention"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in wq.h but not exported"
+
+
+def test_pure_size_helpers(lib):
+    from paper_2605_02262_amd import binding as W
+    # codes only, hd=128, 4 KV heads, K+V: 2-bit token = 2*4*32 B; padded to 32 tokens
+    cb, mb = W.packed_bytes(2, 12564, 4, 128, 64)
+    assert cb == 12576 * 4 * 2 * 32 and mb == 12576 * 4 * 2 * 2 * 4
+    assert W.packed_bytes(4, 32, 2, 64, 32) == (32 * 2 * 2 * 32, 32 * 2 * 2 * 2 * 4)
+    assert W.packed_bytes(3, 32, 2, 64, 32) == (0, 0)            # unsupported width
+    assert W.packed_bytes(8, 32, 2, 96, 32) == (0, 0)            # unsupported head dim
+    assert W.workspace_bytes(4, 28, 128, 64) >= 256 + 4 * 28 * 64 * 130 * 4
+    assert 1 <= W.auto_splits(4, 4, 50688) <= 256
+    assert W.auto_splits(1, 2, 100) == 1
+
+
+def test_argument_errors_are_reported_without_a_gpu(lib):
+    from paper_2605_02262_amd import binding as W
+    h = C.c_void_p()
+    fake_ws = C.c_void_p(0x1000)          # never dereferenced: every call below fails validation first
+    assert lib.wq_create(C.byref(h), None, fake_ws, 1 << 20) == 0
+    try:
+        one = C.c_void_p(0x2000)
+        # unknown dtype
+        rc = lib.wq_window_scores(h, one, one, 7, 1, 64, one, one, one, one, 10, 10, 1, 0, one)
+        assert rc == -1 and b"dtype" in lib.wq_last_error(h)
+        # matrix-core scoring refuses fp32
+        rc = lib.wq_window_scores(h, one, one, W.F32, 1, 64, one, one, one, one, 10, 10, 1, W.SCORE_PAIRWISE_MFMA, one)
+        assert rc == -2
+        # bad top_bits / too many windows
+        assert lib.wq_assign_bits(h, one, 1, one, 8, 0, one, None, 4, 1, one, one, one) == -1
+        assert lib.wq_assign_bits(h, one, 1, one, 10000, 0, one, None, 8, 1, one, one, one) == -2
+        assert lib.wq_assign_bits(h, one, 1, one, 8, 0, None, None, 8, 1, one, one, one) == -1   # quota mode, no quotas
+        # packed descriptor checks
+        d = W._PackedKV()
+        d.B, d.Hkv, d.hd, d.group, d.dtype16 = 1, 4, 128, 64, W.BF16
+        for c in range(3):
+            d.cap[c] = 33                                               # not a multiple of 32
+        rc = lib.wq_reorder_quantize(h, one, one, W.BF16, 1, one, one, one, one, one, 10, C.byref(d))
+        assert rc == -1 and b"multiple of 32" in lib.wq_last_error(h)
+        for c in range(3):
+            d.cap[c] = 64
+            d.codes[c] = 0x3000
+            d.meta[c] = 0x3000
+            d.cls_off[c] = 0x3000
+            d.cls_len[c] = 0x3000
+        d.off16, d.len16 = 0x3000, 0x3000
+        d.hd = 96
+        assert lib.wq_decode_attention(h, one, W.BF16, 1, 28, C.byref(d), 0.1, 0, 100, 0, one, None) == -2
+        d.hd = 128
+        assert lib.wq_decode_attention(h, one, W.BF16, 1, 30, C.byref(d), 0.1, 0, 100, 0, one, None) == -2  # Hq % Hkv
+        assert lib.wq_decode_attention(h, one, W.BF16, 2, 28, C.byref(d), 0.1, 0, 100, 0, one, None) == -1  # B mismatch
+        assert lib.wq_reorder_quantize(h, one, one, W.F16, 1, one, one, one, one, one, 10, C.byref(d)) == -1  # dtype16
+        # workspace too small
+        h2 = C.c_void_p()
+        assert lib.wq_create(C.byref(h2), None, fake_ws, 512) == 0
+        assert lib.wq_decode_attention(h2, one, W.BF16, 1, 28, C.byref(d), 0.1, 64, 100, 0, one, None) == -4
+        lib.wq_destroy(h2)
+        # empty batch is a no-op
+        d.B = 0
+        assert lib.wq_decode_attention(h, one, W.BF16, 0, 28, C.byref(d), 0.1, 0, 0, 0, None, None) == 0
+    finally:
+        lib.wq_destroy(h)

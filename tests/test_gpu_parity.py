@@ -1,0 +1,115 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_02262_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _h():
+    from tests import wq_harness as H
+    return H
+
+
+def _check(bt, H, **kw):
+    g = H.run_gpu(bt, **kw)
+    o = H.run_oracle(bt, scores_override=None if g.scores is None else g.scores.cpu().numpy(),
+                     **{k: v for k, v in kw.items() if k in ("mode", "thresholds", "cap", "off16", "with_scores")})
+    if g.scores is not None:
+        H.assert_scores_close(g.scores, o.scores)
+    assert np.array_equal(g.bits.cpu().numpy(), o.bits)
+    assert np.array_equal(g.perm.cpu().numpy(), o.perm)
+    assert np.array_equal(g.seg.cpu().numpy(), o.seg)
+    H.assert_packed_equal(g, o)
+    err = H.attention_error(g.out.cpu().numpy(), o.out)
+    assert err <= H.ATTN_TOL, f"attention error {err:.3e}"
+    lse_g, lse_o = g.lse.cpu().numpy().astype(np.float64), o.lse
+    fin = np.isfinite(lse_o)
+    assert np.abs(lse_g[fin] - lse_o[fin]).max(initial=0.0) <= 2e-3
+    assert g.ctx.device_status() == 0
+    return g, o, err
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_configs_small(cfg):
+    H = _h()
+    bt = synth.batch(synth.workload(cfg))
+    for splits in (1, 3, 0):
+        _check(bt, H, splits=splits)
+
+
+def _custom(seed, hd, g, Hkv, rep, dtype, specs, top_bits=8, pin=1, D=64, sigma=1.0):
+    w = synth.Workload(f"custom-{seed}", dtype, synth.BF16 if dtype == synth.BF16 else synth.F16, Hkv * rep, Hkv, hd, g,
+                       D, sigma, specs, seed, top_bits=top_bits, pin_first=pin)
+    return synth.batch(w)
+
+
+@pytest.mark.parametrize("hd,g", [(64, 32), (64, 64), (128, 32), (128, 64), (128, 128)])
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16, synth.F32])
+def test_shapes_and_dtypes_ragged(hd, g, dtype):
+    H = _h()
+    specs = [synth.SeqSpec(5, 21, 15, 9, (2, 3, 2)),              # 105 tokens, S=15 -> 7 windows, no tail
+             synth.SeqSpec(3, 10, 7, 0, (1, 1, 2), tail=3),       # tail of 5 (33 = 4*7+5), no text
+             synth.SeqSpec(0, 10, 4, 5, (0, 0, 0)),               # no visual tokens at all
+             synth.SeqSpec(9, 16, 16, 40, (3, 3, 3))]
+    bt = _custom(100 + hd + g + dtype, hd, g, 2, 7, dtype, specs)
+    _check(bt, H, splits=2)
+
+
+def test_paper_tiers_threshold_mode_and_16bit_top():
+    """The paper's own rule: thresholds, top tier kept 16-bit, first window pinned (Sec. 3.2.1-3.2.2)."""
+    H = _h()
+    specs = [synth.SeqSpec(12, 32, 32, 24, (0, 0, 0)), synth.SeqSpec(7, 32, 32, 8, (0, 0, 0))]
+    bt = _custom(7, 128, 64, 4, 7, synth.BF16, specs, top_bits=16, pin=1, D=128)
+    # thresholds straddling the score range so that all three tiers appear
+    th = np.array([[0.004, 0.03], [0.0, 0.02]], dtype=np.float32)
+    cap = [12 * 32 + 7 * 32] * 3
+    off16 = np.array([0, 12 * 32 + 24, 12 * 32 + 24 + 7 * 32 + 8], dtype=np.int32)
+    g, o, _ = _check(bt, H, mode=1, thresholds=th, cap=cap, off16=off16, splits=4)
+    assert o.bits[0] == 16 and o.bits[12] == 16
+    assert len(set(o.bits.tolist())) >= 2
+
+
+def test_rep_variants_and_single_head():
+    H = _h()
+    for rep, Hkv in ((1, 3), (4, 2), (8, 1)):
+        specs = [synth.SeqSpec(6, 20, 20, 11, (2, 2, 2))]
+        bt = _custom(40 + rep, 128, 64, Hkv, rep, synth.BF16, specs)
+        _check(bt, H, splits=2)
+
+
+def test_all_one_class_and_capacity_overflow_flag():
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    for quota in ((6, 0, 0), (0, 6, 0), (0, 0, 6)):
+        specs = [synth.SeqSpec(6, 33, 33, 5, quota)]
+        bt = _custom(50 + quota[0], 128, 64, 4, 7, synth.BF16, specs, pin=0)
+        _check(bt, H, splits=2)
+    # a class buffer that is too small: flagged on the device, nothing written out of bounds
+    specs = [synth.SeqSpec(6, 33, 33, 5, (2, 2, 2))]
+    bt = _custom(60, 128, 64, 4, 7, synth.BF16, specs, pin=0)
+    g = H.run_gpu(bt, cap=[32, 96, 96], splits=1)
+    assert g.ctx.device_status() & W.DEV_CLASS_OVERFLOW
+    assert int(g.pk.cls_len[0][0]) == 0
+
+
+def test_scores_only_larger_D():
+    """Scores at the 7B embedding width on a ragged batch, against the fp64 oracle."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(3, 196, 196, 256, (1, 1, 1)), synth.SeqSpec(5, 196, 98, 100, (3, 3, 4))]
+    w = synth.Workload("scores", synth.BF16, synth.BF16, 28, 4, 128, 64, 3584, 1.5, specs, 5)
+    t = synth.tables(w)
+    ets, evs = zip(*[synth.embeddings(w, b) for b in range(w.B)])
+    Et, Ev = np.concatenate(ets), np.concatenate(evs)
+    ctx = W.Context(W.workspace_bytes(w.B, 0, 0, 0, Ev.shape[0], Et.shape[0], w.D))
+    s = W.wq_window_scores(ctx, H.to_dev(Ev, w.dtype), H.to_dev(Et, w.dtype), H.i32(t.vis_off), H.i32(t.txt_off),
+                           H.i32(t.win_size), H.i32(t.win_off), Ev.shape[0], Et.shape[0], int(t.win_off[-1]))
+    torch.cuda.synchronize()
+    want = O.window_scores(Ev, Et, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pooled")
+    H.assert_scores_close(s, want)
+    pair = O.window_scores(Ev[:196], Et[:256], [0, 196], [0, 256], [196], [0, 1], form="pairwise")
+    assert abs(pair[0] - want[0]) < 1e-12
