@@ -209,7 +209,7 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (algo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
     if (num_splits < 0 || num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
-    if (!(sm_scale == sm_scale)) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale is NaN");
+    if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
     if (B == 0) return WQ_OK;
     if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
     if (num_splits == 0) num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);

@@ -8,7 +8,7 @@
 //
 // k_decode_generic: plain vector-ALU kernel that reads codes field by field from the storage layout.  It
 // handles every supported (hd, group) and is the reference implementation inside the library; the
-// matrix-core kernel in wq_decode_mfma.hip is the fast path for hd/group == 2.
+// matrix-core body in wq_decode_mfma.h is the fast path for hd/group == 2.
 #include "wq_internal.h"
 
 namespace {
@@ -18,8 +18,10 @@ struct DecodeArgs {
     int q_dtype;
     int B, Hq, rep, splits;
     float sm_scale;
+    int splits16, nparts;   // workgroups on the 16-bit segment; nparts = splits + splits16 partials per (b, KV head)
+    int use_mfma;
     wq_packed_kv kv;
-    float* part;   // [B][Hkv][splits][rep][hd + 2]
+    float* part;            // [B][Hkv][nparts][rep][hd + 2]
 };
 
 __device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
@@ -28,6 +30,12 @@ __device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
     if (dtype == WQ_BF16) return wq_bf16_bits_to_float(static_cast<const uint16_t*>(q)[i]);
     return wq_f16_bits_to_float(static_cast<const uint16_t*>(q)[i]);
 }
+
+}  // namespace
+
+#include "wq_decode_mfma.h"
+
+namespace {
 
 // field n (BITS wide) of a little-endian packed byte image
 template <int BITS>
@@ -51,7 +59,9 @@ template <int HD>
 __device__ __forceinline__ void softmax_step(Smem<HD>& sm, int rep, float* m, float* l, float* acc)
 {
     const int tid = threadIdx.x;
-    for (int r = 0; r < rep; r++) {
+#pragma unroll
+    for (int r = 0; r < WQ_MAX_REP; r++) {
+        if (r >= rep) break;
         float bm = -INFINITY;
         for (int u = 0; u < 32; u++) bm = fmaxf(bm, sm.logit[r][u]);
         float mn = fmaxf(m[r], bm);
@@ -62,15 +72,17 @@ __device__ __forceinline__ void softmax_step(Smem<HD>& sm, int rep, float* m, fl
         l[r] = l[r] * sc + ls;
         m[r] = mn;
     }
-    if (tid < rep * 32) {
-        int r = tid >> 5, u = tid & 31;
-        sm.p[r][u] = (m[r] == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - m[r]);
-    }
+#pragma unroll
+    for (int r = 0; r < WQ_MAX_REP; r++)      // static indexing keeps m[] in registers
+        if (r < rep && (tid >> 5) == r) {
+            const int u = tid & 31;
+            sm.p[r][u] = (m[r] == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - m[r]);
+        }
     __syncthreads();
 }
 
 template <int HD, int BITS>
-__device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int split, float* m, float* l, float* acc)
+__device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* m, float* l, float* acc)
 {
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
     constexpr int Q = HD / 4, CT = HD / 16, PARTS = 256 / HD;
@@ -79,7 +91,7 @@ __device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
     const int G = HD / kv.group;
     const int len = kv.cls_len[C][b];
     const int nblk = (len + 31) / 32;
-    const int blk_lo = (int)((int64_t)split * nblk / a.splits), blk_hi = (int)((int64_t)(split + 1) * nblk / a.splits);
+    const int blk_lo = (int)((int64_t)share * nblk / nshare), blk_hi = (int)((int64_t)(share + 1) * nblk / nshare);
     const int64_t tok_base = kv.cls_off[C][b];
     const int64_t cap = kv.cap[C];
     const uint8_t* kcodes = static_cast<const uint8_t*>(kv.codes[C]) + (int64_t)kvh * cap * HD * BITS / 8;
@@ -141,14 +153,14 @@ __device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
 }
 
 template <int HD>
-__device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int split, float* m, float* l, float* acc)
+__device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* m, float* l, float* acc)
 {
     constexpr int PARTS = 256 / HD;
     const wq_packed_kv& kv = a.kv;
     const int tid = threadIdx.x;
     const int len = kv.len16[b];
     const int nblk = (len + 31) / 32;
-    const int blk_lo = (int)((int64_t)split * nblk / a.splits), blk_hi = (int)((int64_t)(split + 1) * nblk / a.splits);
+    const int blk_lo = (int)((int64_t)share * nblk / nshare), blk_hi = (int)((int64_t)(share + 1) * nblk / nshare);
     const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16);
     const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16);
     const bool bf = kv.dtype16 == WQ_BF16;
@@ -198,10 +210,10 @@ __device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
 }
 
 template <int HD>
-__global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
+__device__ void decode_generic_body(const DecodeArgs& a, void* smem_raw, bool quantized, int share, int nshare, int part_idx)
 {
-    __shared__ Smem<HD> sm;
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    Smem<HD>& sm = *reinterpret_cast<Smem<HD>*>(smem_raw);
+    const int kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x;
     for (int i = tid; i < a.rep * HD; i += 256) {
         int r = i / HD, ch = i % HD;
@@ -215,17 +227,21 @@ __global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
         l[r] = 0.f;
         acc[r] = 0.f;
     }
-    walk_class<HD, 2>(a, sm, b, kvh, split, m, l, acc);
-    walk_class<HD, 4>(a, sm, b, kvh, split, m, l, acc);
-    walk_class<HD, 8>(a, sm, b, kvh, split, m, l, acc);
-    walk_seg16<HD>(a, sm, b, kvh, split, m, l, acc);
+    if (quantized) {
+        walk_class<HD, 2>(a, sm, b, kvh, share, nshare, m, l, acc);
+        walk_class<HD, 4>(a, sm, b, kvh, share, nshare, m, l, acc);
+        walk_class<HD, 8>(a, sm, b, kvh, share, nshare, m, l, acc);
+    }
+    walk_seg16<HD>(a, sm, b, kvh, share, nshare, m, l, acc);
 
     // reduce the token parts, write the partial
     constexpr int PARTS = 256 / HD;
     const int c = tid % HD, tp = tid / HD;
-    for (int r = 0; r < a.rep; r++) sm.red[tp][r][c] = acc[r];
+#pragma unroll
+    for (int r = 0; r < WQ_MAX_REP; r++)
+        if (r < a.rep) sm.red[tp][r][c] = acc[r];
     __syncthreads();
-    float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.splits + split) * a.rep * (HD + 2);
+    float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts + part_idx) * a.rep * (HD + 2);
     if (tp == 0) {
         for (int r = 0; r < a.rep; r++) {
             float s = 0.f;
@@ -233,10 +249,33 @@ __global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
             out[r * (HD + 2) + c] = s;
         }
     }
-    if (tid < a.rep) {
-        out[tid * (HD + 2) + HD] = m[tid];
-        out[tid * (HD + 2) + HD + 1] = l[tid];
-    }
+#pragma unroll
+    for (int r = 0; r < WQ_MAX_REP; r++)
+        if (tid == r && r < a.rep) {
+            out[r * (HD + 2) + HD] = m[r];
+            out[r * (HD + 2) + HD + 1] = l[r];
+        }
+}
+
+template <int HD>
+constexpr size_t decode_smem_bytes()
+{
+    return sizeof(Smem<HD>) > sizeof(MfmaSmem<HD>) ? sizeof(Smem<HD>) : sizeof(MfmaSmem<HD>);
+}
+
+// blockIdx.x < splits: quantized classes (matrix-core body, or everything in the generic body);
+// blockIdx.x >= splits: the 16-bit segment, generic body (matrix-core launches only).
+template <int HD>
+__global__ __launch_bounds__(256) void k_decode(DecodeArgs a)
+{
+    __shared__ __align__(16) unsigned char smem[decode_smem_bytes<HD>()];
+    const int x = blockIdx.x;
+    if (!a.use_mfma)
+        decode_generic_body<HD>(a, smem, true, x, a.splits, x);
+    else if (x < a.splits)
+        wq_decode_mfma_body<HD>(a, smem);
+    else
+        decode_generic_body<HD>(a, smem, false, x - a.splits, a.splits16, x);
 }
 
 // out[b,h,:] = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M},  M = max_s m_s;  lse = M + log(sum)
@@ -265,14 +304,20 @@ __global__ void k_combine(const float* __restrict__ part, int Hq, int rep, int s
 
 }  // namespace
 
+// workgroups per (sequence, KV head) given to the 16-bit segment by the matrix-core launch: about one per
+// 64 rows of the average sequence's capacity, between 1 and 32
+static int wq_decode_splits16(int B, int64_t cap16)
+{
+    int64_t per = B > 0 ? cap16 / B : 0;
+    int64_t n = (per + 63) / 64;
+    return (int)(n < 1 ? 1 : (n > 32 ? 32 : n));
+}
+
 size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
 {
     if (B <= 0 || Hq <= 0 || hd <= 0 || splits <= 0) return 0;
-    return wq_align256(sizeof(float) * (size_t)B * Hq * splits * (hd + 2));
+    return wq_align256(sizeof(float) * (size_t)B * Hq * (splits + 32) * (hd + 2));
 }
-
-int wq_launch_decode_mfma(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
-                          int num_splits, float* part);
 
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
                      int num_splits, int algo, float* out, float* lse)
@@ -285,15 +330,17 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.rep = Hq / kv->Hkv;
     a.splits = num_splits;
     a.sm_scale = sm_scale;
+    a.use_mfma = (algo == WQ_DECODE_MFMA) || (algo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
+    a.splits16 = a.use_mfma ? wq_decode_splits16(B, kv->cap16) : 0;
+    a.nparts = a.splits + a.splits16;
     a.kv = *kv;
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
-    dim3 grid(num_splits, kv->Hkv, B);
-    (void)algo;
+    dim3 grid(a.nparts, kv->Hkv, B);
     if (kv->hd == 128)
-        hipLaunchKernelGGL(k_decode_generic<128>, grid, dim3(256), 0, ctx->stream, a);
+        hipLaunchKernelGGL(k_decode<128>, grid, dim3(256), 0, ctx->stream, a);
     else
-        hipLaunchKernelGGL(k_decode_generic<64>, grid, dim3(256), 0, ctx->stream, a);
-    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(kv->hd), 0, ctx->stream, a.part, Hq, a.rep, num_splits, kv->hd, out, lse);
+        hipLaunchKernelGGL(k_decode<64>, grid, dim3(256), 0, ctx->stream, a);
+    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(kv->hd), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

@@ -1,0 +1,389 @@
+// a4, matrix-core path: decode attention over the packed cache for hd/group == 2 (Alg. 2 decode half).
+//
+// One wavefront walks 32-token blocks of a class on its own (no workgroup barrier inside the loop):
+//
+//   S^T = K_codes . Q^T      v_mfma_f32_16x16x32_f16, A = 16 tokens x 32 contraction slots of raw codes,
+//                            B = query heads.  The 16 output columns are (group g, head h): B is block-diagonal,
+//                            slots 0..15 carry group-0 channels and feed columns 0..7, slots 16..31 carry group-1
+//                            channels and feed columns 8..15, so one accumulator tile holds both groups' integer
+//                            dot products and every lane of the softmax has real work (7 of 8 columns per half).
+//   dequant                  logit = s0*D0 + m0*sum(q over group 0) + s1*D1 + m1*sum(q over group 1): each lane
+//                            applies its own group's (s, m), the two halves meet with one DPP row rotate.
+//   online softmax           running max shared by the wavefront's four lane groups; it is re-synchronised (and
+//                            the output accumulators rescaled) only when some logit exceeds it.
+//   O^T += V_codes^T . P'^T  P' = p * s_v (per value group, hence the same 16 columns), raw V codes as A; the
+//                            m_v part of the dequantised values is the scalar sum  p * m_v  kept per lane.
+//
+// Codes go into the f16 operands without arithmetic: a b-bit field masked in place inside a 16-bit half is the
+// f16 subnormal  code * 2^(shift-24), which the matrix cores consume exactly; the per-slot power of two is
+// folded into the other operand (q or P'), the common 2^-24 into constants applied after the contraction.
+//
+// The storage layout (wq.h) is exactly the per-lane operand order, so every load is one contiguous piece per
+// lane, a whole tile per wavefront.  The 16-bit segment is handled by extra workgroups of the generic kernel.
+#pragma once
+// (included by wq_decode.hip, after DecodeArgs and load_q)
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct U4 {
+    uint32_t x, y, z, w;
+};
+
+__device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    U4 u{a, b, c, d};
+    return __builtin_bit_cast(half8, u);
+}
+
+__device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float f16lo(uint32_t w) { return wq_f16_bits_to_float(w & 0xFFFFu); }
+__device__ __forceinline__ float f16hi(uint32_t w) { return wq_f16_bits_to_float(w >> 16); }
+
+// rotate by 8 lanes inside each row of 16 lanes: lane (g,h) <-> lane (1-g,h)
+__device__ __forceinline__ float ror8(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, false));
+}
+
+// ---- where the matrix instruction's contraction slot e (0..7) of k-step r finds its channel and bit shift ----
+// Returns the channel inside the lane's quarter (hd/4 channels) and the left shift the code keeps in its f16 half.
+template <int BITS>
+__device__ __forceinline__ void k_slot(int r, int e, int& ch, int& sh)
+{
+    const int v = e >> 1, hi = e & 1;
+    if (BITS == 2) {            // dword d = r/2 holds 16 fields; pair p = 4*(r%2)+v is (field p, field p+8)
+        const int d = r >> 1, p = 4 * (r & 1) + v;
+        ch = 16 * d + p + 8 * hi;
+        sh = p <= 4 ? 2 * p : 2 * (p - 5);
+    } else if (BITS == 4) {     // dword r holds 8 fields; pair v is (field v, field v+4)
+        ch = 8 * r + v + 4 * hi;
+        sh = 4 * (v & 1);
+    } else {                    // dwords 2r, 2r+1; register v = (dword v/2, bytes (v%2, v%2+2))
+        const int d = 2 * r + (v >> 1);
+        ch = 4 * d + (v & 1) + 2 * hi;
+        sh = 0;
+    }
+}
+
+// unpack the K chunk of one lane (hd/4 codes of one token) into the A operand of k-step r
+template <int BITS>
+__device__ __forceinline__ half8 k_operand(const uint32_t* x, int r)
+{
+    if (BITS == 2) {
+        const uint32_t w = x[r >> 1];
+        if ((r & 1) == 0)
+            return as_half8(w & 0x00030003u, w & 0x000C000Cu, w & 0x00300030u, w & 0x00C000C0u);
+        const uint32_t y = w >> 10;
+        return as_half8(w & 0x03000300u, y & 0x00030003u, y & 0x000C000Cu, y & 0x00300030u);
+    } else if (BITS == 4) {
+        const uint32_t w = x[r], y = w >> 8;
+        return as_half8(w & 0x000F000Fu, w & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
+    } else {
+        const uint32_t w0 = x[2 * r], w1 = x[2 * r + 1];
+        return as_half8(w0 & 0x00FF00FFu, __builtin_amdgcn_perm(0u, w0, 0x0c030c01u), w1 & 0x00FF00FFu,
+                        __builtin_amdgcn_perm(0u, w1, 0x0c030c01u));
+    }
+}
+
+// power of two that P' carries in register v (slots 2v, 2v+1) so that V's in-place codes come out unscaled
+template <int BITS>
+__device__ __forceinline__ float v_slot_scale(int v)
+{
+    if (BITS == 2) return v == 0 ? 1.0f : (v == 1 ? 0.25f : (v == 2 ? 0.0625f : 0.015625f));
+    if (BITS == 4) return (v & 1) ? 0.0625f : 1.0f;
+    return 1.0f;
+}
+
+// unpack the V fragment of one lane (for channel tile ct: 8 tokens of one channel) into an A operand
+template <int BITS>
+__device__ __forceinline__ half8 v_operand(const uint32_t* x, int ct)
+{
+    if (BITS == 2) {            // dword ct/2: fields 0..7 = even tile, 8..15 = odd tile
+        uint32_t y = __builtin_amdgcn_perm(0u, x[ct >> 1], 0x03010200u);   // bytes (b0,b2,b1,b3)
+        if (ct & 1) y >>= 8;
+        return as_half8(y & 0x00030003u, y & 0x000C000Cu, y & 0x00300030u, y & 0x00C000C0u);
+    } else if (BITS == 4) {
+        const uint32_t w = x[ct], y = w >> 8;
+        return as_half8(w & 0x000F000Fu, w & 0x00F000F0u, y & 0x000F000Fu, y & 0x00F000F0u);
+    } else {                    // dwords 2ct (tokens tau 0..3), 2ct+1 (tau 4..7)
+        const uint32_t lo = x[2 * ct], hi = x[2 * ct + 1];
+        return as_half8(__builtin_amdgcn_perm(hi, lo, 0x0c040c00u), __builtin_amdgcn_perm(hi, lo, 0x0c050c01u),
+                        __builtin_amdgcn_perm(hi, lo, 0x0c060c02u), __builtin_amdgcn_perm(hi, lo, 0x0c070c03u));
+    }
+}
+
+template <int HD>
+struct WaveState {
+    floatx4 O[HD / 16];   // O^T tiles: row = channel 16ct + 4j + i, column = (g,h)
+    float m;              // running max of this column's logits, log2 domain, shared by the four lane groups
+    float l;              // this lane's share of sum p
+    float accM;           // this lane's share of sum p * m_v
+};
+
+template <int HD>
+struct MfmaSmem {
+    _Float16 q[WQ_MAX_REP][HD];       // query, per head scaled by a power of two into [-1, 1]
+    float qexp[WQ_MAX_REP];           // that power of two
+    float O[4][WQ_MAX_REP][HD];       // per-wave numerators for the merge
+    float ml[4][WQ_MAX_REP][2];
+};
+
+// One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
+template <int HD, int BITS>
+__device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, int b, int kvh, int share, int nshare, float c_log2,
+                                WaveState<HD>& st)
+{
+    constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
+    constexpr int NK = HD / 32;                    // k-steps of the logit product per 16-token tile
+    constexpr int CT = HD / 16;                    // channel tiles of the value product
+    constexpr int KDW = (HD / 4) * BITS / 32;      // dwords of K codes per lane per tile
+    constexpr int VDW = (HD / 16) * 8 * BITS / 32; // dwords of V codes per lane per block
+    const int lane = threadIdx.x & 63;
+    const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
+
+    const int len = kv.cls_len[C][b];
+    const int nblk = (len + 31) >> 5;
+    const int blk_lo = (int)((int64_t)share * nblk / nshare), blk_hi = (int)((int64_t)(share + 1) * nblk / nshare);
+    if (blk_lo >= blk_hi) return;
+
+    // ---- B operand of the logit product for this class: q (scaled into [-1,1]) times 2^-shift of its slot ----
+    half8 Bq[NK];
+    float qsum = 0.f;                              // sum of q' over this lane's group (all four quarters' worth)
+    {
+        const bool mine = (j >> 1) == g;           // slots 8j.. belong to channel quarter j, group j/2
+#pragma unroll
+        for (int r = 0; r < NK; r++) {
+            half8 v;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                int ch, sh;
+                k_slot<BITS>(r, e, ch, sh);
+                float qv = (mine && h < WQ_MAX_REP) ? (float)sm.q[h][j * (HD / 4) + ch] : 0.f;
+                v[e] = (_Float16)(qv * __builtin_ldexpf(1.0f, -sh));
+            }
+            Bq[r] = v;
+        }
+        for (int ch = 0; ch < HD / 2; ch++) qsum += (float)sm.q[h][g * (HD / 2) + ch];
+    }
+    // logits come out of the matrix cores as 2^-24 * sum q' code; fold 2^24, the head's power of two and
+    // sm_scale*log2(e) into one constant, and pre-divide the m-term by 2^24 so both terms share it.
+    const float cexp = c_log2 * sm.qexp[h] * 16777216.0f;
+    const float qs = qsum * (1.0f / 16777216.0f);
+
+    const int64_t cap = kv.cap[C];
+    const int64_t tok_base = kv.cls_off[C][b];
+    const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok_base) * HD * BITS / 8;
+    const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * HD * BITS / 8;
+    const uint32_t* kmeta = static_cast<const uint32_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok_base) * 2;
+    const uint32_t* vmeta = static_cast<const uint32_t*>(kv.meta[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * 2;
+    const int moff = g * 16 + 4 * j;               // word offset of (group g, tokens 4j..4j+3) inside a metadata tile
+
+    struct Frag {
+        uint32_t k[2][KDW];
+        uint32_t v[VDW];
+        uint4 km[2], vm[2];
+    };
+    auto load = [&](int blk, Frag& f) {
+        const uint8_t* kp = kbase + (int64_t)blk * (32 * HD * BITS / 8) + lane * (KDW * 4);
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(kp + t * (16 * HD * BITS / 8));
+            if constexpr (KDW == 1) {
+                f.k[t][0] = p[0];
+            } else if constexpr (KDW == 2) {
+                uint2 u = *reinterpret_cast<const uint2*>(p);
+                f.k[t][0] = u.x;
+                f.k[t][1] = u.y;
+            } else {
+#pragma unroll
+                for (int d = 0; d < KDW; d += 4) {
+                    uint4 u = *reinterpret_cast<const uint4*>(p + d);
+                    f.k[t][d] = u.x;
+                    f.k[t][d + 1] = u.y;
+                    f.k[t][d + 2] = u.z;
+                    f.k[t][d + 3] = u.w;
+                }
+            }
+        }
+        const uint32_t* vp = reinterpret_cast<const uint32_t*>(vbase + (int64_t)blk * (32 * HD * BITS / 8) + lane * (VDW * 4));
+        if constexpr (VDW == 2) {
+            uint2 u = *reinterpret_cast<const uint2*>(vp);
+            f.v[0] = u.x;
+            f.v[1] = u.y;
+        } else {
+#pragma unroll
+            for (int d = 0; d < VDW; d += 4) {
+                uint4 u = *reinterpret_cast<const uint4*>(vp + d);
+                f.v[d] = u.x;
+                f.v[d + 1] = u.y;
+                f.v[d + 2] = u.z;
+                f.v[d + 3] = u.w;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            f.km[t] = *reinterpret_cast<const uint4*>(kmeta + ((int64_t)blk * 2 + t) * 32 + moff);
+            f.vm[t] = *reinterpret_cast<const uint4*>(vmeta + ((int64_t)blk * 2 + t) * 32 + moff);
+        }
+    };
+
+    Frag cur;
+    load(blk_lo, cur);
+    for (int blk = blk_lo; blk < blk_hi; blk++) {
+        Frag nxt;
+        if (blk + 1 < blk_hi) load(blk + 1, nxt);
+
+        // ---- logits of the two 16-token tiles ----
+        float x[8];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < NK; r++) acc = mfma(k_operand<BITS>(cur.k[t], r), Bq[r], acc);
+            const uint32_t mw[4] = {cur.km[t].x, cur.km[t].y, cur.km[t].z, cur.km[t].w};
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                float y = fmaf(f16lo(mw[i]), acc[i], f16hi(mw[i]) * qs);
+                x[4 * t + i] = y + ror8(y);
+            }
+        }
+        const int nv = len - blk * 32;             // valid tokens in this block (only the last one is short)
+        if (nv < 32) {
+#pragma unroll
+            for (int t = 0; t < 2; t++)
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    if (16 * t + 4 * j + i >= nv) x[4 * t + i] = -INFINITY;
+        }
+        // ---- running max: touch the other lane groups only when some logit beats it ----
+        float lm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        lm *= cexp;                                // cexp > 0
+        if (__builtin_amdgcn_ballot_w64(lm > st.m) != 0) {
+            lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
+            lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
+            const float mn = fmaxf(st.m, lm);
+            const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);  // 0 on the first block
+            st.m = mn;
+            st.l *= alpha;
+            st.accM *= alpha;
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
+        }
+        // ---- weights, P' = p * s_v * slot scale, and the m_v part ----
+        const uint32_t vw[8] = {cur.vm[0].x, cur.vm[0].y, cur.vm[0].z, cur.vm[0].w,
+                                cur.vm[1].x, cur.vm[1].y, cur.vm[1].z, cur.vm[1].w};
+        _Float16 pp[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -st.m));
+            st.l += p;
+            st.accM = fmaf(p, f16hi(vw[k]), st.accM);
+            pp[k] = (_Float16)(p * v_slot_scale<BITS>(k & 3) * f16lo(vw[k]));
+        }
+        half8 Bp;
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+            Bp[2 * v] = pp[v];                     // tile 0, token 4j+v
+            Bp[2 * v + 1] = pp[4 + v];             // tile 1, token 4j+v
+        }
+        // ---- values ----
+#pragma unroll
+        for (int ct = 0; ct < CT; ct++) st.O[ct] = mfma(v_operand<BITS>(cur.v, ct), Bp, st.O[ct]);
+        cur = nxt;
+    }
+}
+
+template <int HD>
+__device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
+{
+    MfmaSmem<HD>& sm = *reinterpret_cast<MfmaSmem<HD>*>(smem_raw);
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
+    constexpr int CT = HD / 16;
+
+    // ---- query: per head, scale by a power of two so that max |q| is in [0.5, 1]; keep it as f16 ----
+    if (wave < 2) {
+        for (int r = wave * 4; r < wave * 4 + 4; r++) {
+            float v0 = 0.f, v1 = 0.f;
+            if (r < a.rep) {
+                const int64_t base = ((int64_t)b * a.Hq + kvh * a.rep + r) * HD;
+                v0 = load_q(a.q, a.q_dtype, base + lane);
+                if (HD == 128) v1 = load_q(a.q, a.q_dtype, base + 64 + lane);
+            }
+            float mx = fmaxf(fabsf(v0), fabsf(v1));
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+            int ex = 0;
+            if (mx > 0.f && mx < INFINITY) (void)frexpf(mx, &ex);      // mx = f * 2^ex, f in [0.5, 1)
+            const float dn = __builtin_ldexpf(1.0f, -ex);
+            sm.q[r][lane] = (_Float16)(v0 * dn);
+            if (HD == 128) sm.q[r][64 + lane] = (_Float16)(v1 * dn);
+            if (lane == 0) sm.qexp[r] = __builtin_ldexpf(1.0f, ex);
+        }
+    }
+    __syncthreads();
+
+    WaveState<HD> st;
+#pragma unroll
+    for (int ct = 0; ct < CT; ct++) st.O[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+    st.m = -INFINITY;
+    st.l = 0.f;
+    st.accM = 0.f;
+    const float c_log2 = a.sm_scale * 1.4426950408889634f;
+    const int share = split * 4 + wave, nshare = a.splits * 4;
+    walk_class_mfma<HD, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    walk_class_mfma<HD, 4>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    walk_class_mfma<HD, 8>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+
+    // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
+    float l = st.l, am = st.accM;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    am += __shfl_xor(am, 16, 64);
+    am += __shfl_xor(am, 32, 64);
+    if (h < WQ_MAX_REP) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ct++) {
+            if ((ct >= CT / 2) == (g == 1)) {      // this column's group owns channel tile ct
+#pragma unroll
+                for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
+            }
+        }
+        if (j == 0 && g == 0) {
+            sm.ml[wave][h][0] = st.m;
+            sm.ml[wave][h][1] = l;
+        }
+    }
+    __syncthreads();
+    // ---- merge the four waves, write the partial (m in natural-log units) ----
+    float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts + split) * a.rep * (HD + 2);
+    for (int idx = tid; idx < a.rep * HD; idx += 256) {
+        const int r = idx / HD, ch = idx - r * HD;
+        float M = fmaxf(fmaxf(sm.ml[0][r][0], sm.ml[1][r][0]), fmaxf(sm.ml[2][r][0], sm.ml[3][r][0]));
+        float num = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const float mw = sm.ml[w][r][0];
+            if (mw != -INFINITY) {
+                const float s = exp2f(mw - M);
+                num = fmaf(sm.O[w][r][ch], s, num);
+                L = fmaf(sm.ml[w][r][1], s, L);
+            }
+        }
+        out[r * (HD + 2) + ch] = num;
+        if (ch == 0) {
+            out[r * (HD + 2) + HD] = M * 0.6931471805599453f;
+            out[r * (HD + 2) + HD + 1] = L;
+        }
+    }
+}
+
+}  // namespace

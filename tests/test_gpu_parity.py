@@ -32,12 +32,13 @@ def _check(bt, H, **kw):
     return g, o, err
 
 
+@pytest.mark.parametrize("algo", [1, 2], ids=["generic", "mfma"])
 @pytest.mark.parametrize("cfg", [0, 1])
-def test_configs_small(cfg):
+def test_configs_small(cfg, algo):
     H = _h()
     bt = synth.batch(synth.workload(cfg))
     for splits in (1, 3, 0):
-        _check(bt, H, splits=splits)
+        _check(bt, H, splits=splits, algo=algo)
 
 
 def _custom(seed, hd, g, Hkv, rep, dtype, specs, top_bits=8, pin=1, D=64, sigma=1.0):
