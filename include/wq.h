@@ -84,6 +84,7 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
  * workspace    : device memory of workspace_bytes that the library may scribble on, or NULL to let
  *                wq_create allocate workspace_bytes itself (freed by wq_destroy).  Size it with
  *                wq_workspace_bytes; calls that need more return WQ_ERR_WORKSPACE.
+ *                A caller-provided workspace must start with 256 zero bytes (the device status word).
  * wq_create touches no GPU when it is given a workspace (or workspace_bytes == 0).                          */
 int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes);
 int wq_destroy(wq_ctx* ctx);
@@ -167,6 +168,12 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * matrix-core kernel when hd/group == 2, else the generic one.                                               */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
+
+/* ---- measurement probe (not part of the method; for callers that cannot time a plain kernel themselves) ----
+ * Streams `bytes` (multiple of 16) of device memory with 16-byte loads from `blocks` workgroups of 256 lanes:
+ * read-only when dst is NULL, a plain copy otherwise.  Gives the achievable HBM rate and the reference that
+ * hardware byte counters are scaled by.                                                                       */
+int wq_probe_stream(wq_ctx* ctx, const void* src, void* dst, int64_t bytes, int blocks);
 
 #ifdef __cplusplus
 }

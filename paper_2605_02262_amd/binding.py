@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.wq_assign_bits.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
+        L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
         _lib = L
     return _lib
 
@@ -209,3 +210,9 @@ def wq_decode_attention(ctx: Context, q, kv: PackedKV, sm_scale: float, num_spli
     ctx.check(lib().wq_decode_attention(ctx.handle, _ptr(q), _dtype_id(q), B, Hq, C.byref(kv.desc), sm_scale, num_splits,
                                         max_seq_tokens, algo, _ptr(out), _ptr(lse)))
     return out
+
+
+def wq_probe_stream(ctx: Context, src: torch.Tensor, dst: Optional[torch.Tensor] = None, blocks: int = 4096):
+    nbytes = src.numel() * src.element_size() // 16 * 16
+    ctx.check(lib().wq_probe_stream(ctx.handle, src.data_ptr(), None if dst is None else dst.data_ptr(), nbytes, blocks))
+    return nbytes

@@ -51,38 +51,42 @@ struct Smem {
     float logit[WQ_MAX_REP][32];
     float p[WQ_MAX_REP][32];
     float red[256 / HD][WQ_MAX_REP][HD];
+    float m[WQ_MAX_REP], l[WQ_MAX_REP], scale[WQ_MAX_REP];
 };
 
-// One 32-token step: logits are in sm.logit (-inf for invalid tokens); updates m, l, rescales acc and leaves
-// the weights in sm.p.  Every thread executes the same arithmetic in the same order, so all copies of m and l agree.
+// One 32-token step: logits are in sm.logit (-inf for invalid tokens).  Thread (r = tid/32, u = tid%32) owns one
+// (head, token) pair: block max and sum by wavefront shuffles inside its 32 lanes, running (m, l) in LDS; leaves the
+// weights in sm.p and rescales every thread's accumulators.
 template <int HD>
-__device__ __forceinline__ void softmax_step(Smem<HD>& sm, int rep, float* m, float* l, float* acc)
+__device__ __forceinline__ void softmax_step(Smem<HD>& sm, int rep, float* acc)
 {
     const int tid = threadIdx.x;
+    const int r = tid >> 5, u = tid & 31;
+    const float lg = r < rep ? sm.logit[r][u] : -INFINITY;
+    float bm = lg;
 #pragma unroll
-    for (int r = 0; r < WQ_MAX_REP; r++) {
-        if (r >= rep) break;
-        float bm = -INFINITY;
-        for (int u = 0; u < 32; u++) bm = fmaxf(bm, sm.logit[r][u]);
-        float mn = fmaxf(m[r], bm);
-        float sc = (mn == -INFINITY) ? 1.0f : __expf(m[r] - mn);
-        acc[r] *= sc;
-        float ls = 0.f;
-        for (int u = 0; u < 32; u++) ls += (mn == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - mn);
-        l[r] = l[r] * sc + ls;
-        m[r] = mn;
+    for (int o = 16; o > 0; o >>= 1) bm = fmaxf(bm, __shfl_xor(bm, o, 64));
+    const float mo = sm.m[r];
+    const float mn = fmaxf(mo, bm);
+    const float p = (mn == -INFINITY) ? 0.f : __expf(lg - mn);
+    float ps = p;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) ps += __shfl_xor(ps, o, 64);
+    sm.p[r][u] = p;
+    __syncthreads();                      // every lane has read the old m before it changes
+    if (u == 0) {
+        const float sc = (mn == -INFINITY) ? 1.0f : __expf(mo - mn);
+        sm.scale[r] = sc;
+        sm.m[r] = mn;
+        sm.l[r] = sm.l[r] * sc + ps;
     }
-#pragma unroll
-    for (int r = 0; r < WQ_MAX_REP; r++)      // static indexing keeps m[] in registers
-        if (r < rep && (tid >> 5) == r) {
-            const int u = tid & 31;
-            sm.p[r][u] = (m[r] == -INFINITY) ? 0.f : __expf(sm.logit[r][u] - m[r]);
-        }
     __syncthreads();
+#pragma unroll
+    for (int k = 0; k < WQ_MAX_REP; k++) acc[k] *= sm.scale[k];
 }
 
 template <int HD, int BITS>
-__device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* m, float* l, float* acc)
+__device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* acc)
 {
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
     constexpr int Q = HD / 4, CT = HD / 16, PARTS = 256 / HD;
@@ -131,7 +135,7 @@ __device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
             }
         }
         __syncthreads();
-        softmax_step<HD>(sm, a.rep, m, l, acc);
+        softmax_step<HD>(sm, a.rep, acc);
         // ---- values: thread = (channel c, token part tp) ----
         {
             const int c = tid % HD, tp = tid / HD;
@@ -153,7 +157,7 @@ __device__ void walk_class(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
 }
 
 template <int HD>
-__device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* m, float* l, float* acc)
+__device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, int share, int nshare, float* acc)
 {
     constexpr int PARTS = 256 / HD;
     const wq_packed_kv& kv = a.kv;
@@ -191,7 +195,7 @@ __device__ void walk_seg16(const DecodeArgs& a, Smem<HD>& sm, int b, int kvh, in
             }
         }
         __syncthreads();
-        softmax_step<HD>(sm, a.rep, m, l, acc);
+        softmax_step<HD>(sm, a.rep, acc);
         {
             const int c = tid % HD, tp = tid / HD;
             for (int u = tp * (32 / PARTS); u < (tp + 1) * (32 / PARTS); u++) {
@@ -220,19 +224,21 @@ __device__ void decode_generic_body(const DecodeArgs& a, void* smem_raw, bool qu
         sm.q[r][ch] = load_q(a.q, a.q_dtype, ((int64_t)b * a.Hq + kvh * a.rep + r) * HD + ch);
     }
     __syncthreads();
-    float m[WQ_MAX_REP], l[WQ_MAX_REP], acc[WQ_MAX_REP];
+    if (tid < WQ_MAX_REP) {
+        sm.m[tid] = -INFINITY;
+        sm.l[tid] = 0.f;
+        sm.scale[tid] = 1.f;
+    }
+    __syncthreads();
+    float acc[WQ_MAX_REP];
 #pragma unroll
-    for (int r = 0; r < WQ_MAX_REP; r++) {
-        m[r] = -INFINITY;
-        l[r] = 0.f;
-        acc[r] = 0.f;
-    }
+    for (int r = 0; r < WQ_MAX_REP; r++) acc[r] = 0.f;
     if (quantized) {
-        walk_class<HD, 2>(a, sm, b, kvh, share, nshare, m, l, acc);
-        walk_class<HD, 4>(a, sm, b, kvh, share, nshare, m, l, acc);
-        walk_class<HD, 8>(a, sm, b, kvh, share, nshare, m, l, acc);
+        walk_class<HD, 2>(a, sm, b, kvh, share, nshare, acc);
+        walk_class<HD, 4>(a, sm, b, kvh, share, nshare, acc);
+        walk_class<HD, 8>(a, sm, b, kvh, share, nshare, acc);
     }
-    walk_seg16<HD>(a, sm, b, kvh, share, nshare, m, l, acc);
+    walk_seg16<HD>(a, sm, b, kvh, share, nshare, acc);
 
     // reduce the token parts, write the partial
     constexpr int PARTS = 256 / HD;
@@ -249,67 +255,86 @@ __device__ void decode_generic_body(const DecodeArgs& a, void* smem_raw, bool qu
             out[r * (HD + 2) + c] = s;
         }
     }
-#pragma unroll
-    for (int r = 0; r < WQ_MAX_REP; r++)
-        if (tid == r && r < a.rep) {
-            out[r * (HD + 2) + HD] = m[r];
-            out[r * (HD + 2) + HD + 1] = l[r];
-        }
+    if (tid < a.rep) {
+        out[tid * (HD + 2) + HD] = sm.m[tid];
+        out[tid * (HD + 2) + HD + 1] = sm.l[tid];
+    }
 }
 
+// Generic kernel: every segment (use_mfma == 0), or only the 16-bit segment next to a matrix-core launch, in
+// which case its partials follow the matrix-core ones (slot splits + x).
 template <int HD>
-constexpr size_t decode_smem_bytes()
+__global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
 {
-    return sizeof(Smem<HD>) > sizeof(MfmaSmem<HD>) ? sizeof(Smem<HD>) : sizeof(MfmaSmem<HD>);
-}
-
-// blockIdx.x < splits: quantized classes (matrix-core body, or everything in the generic body);
-// blockIdx.x >= splits: the 16-bit segment, generic body (matrix-core launches only).
-template <int HD>
-__global__ __launch_bounds__(256) void k_decode(DecodeArgs a)
-{
-    __shared__ __align__(16) unsigned char smem[decode_smem_bytes<HD>()];
+    __shared__ __align__(16) unsigned char smem[sizeof(Smem<HD>)];
     const int x = blockIdx.x;
     if (!a.use_mfma)
         decode_generic_body<HD>(a, smem, true, x, a.splits, x);
-    else if (x < a.splits)
-        wq_decode_mfma_body<HD>(a, smem);
     else
-        decode_generic_body<HD>(a, smem, false, x - a.splits, a.splits16, x);
+        decode_generic_body<HD>(a, smem, false, x, a.splits16, a.splits + x);
 }
 
-// out[b,h,:] = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M},  M = max_s m_s;  lse = M + log(sum)
-__global__ void k_combine(const float* __restrict__ part, int Hq, int rep, int splits, int hd, float* __restrict__ out,
-                          float* __restrict__ lse)
+// Matrix-core kernel: the quantized classes of one (split, KV head, sequence).
+template <int HD>
+__global__ __launch_bounds__(256) void k_decode_mfma(DecodeArgs a)
 {
+    __shared__ __align__(16) unsigned char smem[sizeof(MfmaSmem<HD>)];
+    wq_decode_mfma_body<HD>(a, smem);
+}
+
+// out[b,h,:] = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M},  M = max_s m_s;  lse = M + log(sum).
+// One workgroup per (b, h); the weights e^{m_s - M} are computed once in parallel, the sums run in split order
+// with all loads of a thread independent of each other (no data-dependent control flow around them).
+__global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part, int Hq, int rep, int nparts, int hd,
+                                                 float* __restrict__ out, float* __restrict__ lse)
+{
+    __shared__ float s_w[1024 + 32];
+    __shared__ float s_red[2];
     const int h = blockIdx.x, b = blockIdx.y;
     const int kvh = h / rep, r = h % rep;
     const int Hkv = Hq / rep;
-    const int c = threadIdx.x;
-    const float* base = part + (((int64_t)b * Hkv + kvh) * splits) * rep * (hd + 2) + (int64_t)r * (hd + 2);
+    const int tid = threadIdx.x;
     const int64_t stride = (int64_t)rep * (hd + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < splits; s++) M = fmaxf(M, base[s * stride + hd]);
-    float L = 0.f, acc = 0.f;
-    for (int s = 0; s < splits; s++) {
-        float ms = base[s * stride + hd];
-        if (ms == -INFINITY) continue;
-        float w = __expf(ms - M);
-        L = fmaf(base[s * stride + hd + 1], w, L);
-        acc = fmaf(base[s * stride + c], w, acc);
+    const float* base = part + (((int64_t)b * Hkv + kvh) * nparts) * stride + (int64_t)r * (hd + 2);
+    float mx = -INFINITY;
+    for (int s = tid; s < nparts; s += 128) mx = fmaxf(mx, base[s * stride + hd]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if ((tid & 63) == 0) s_red[tid >> 6] = mx;
+    __syncthreads();
+    const float M = fmaxf(s_red[0], s_red[1]);
+    for (int s = tid; s < nparts; s += 128) {
+        const float ms = base[s * stride + hd];
+        s_w[s] = (ms == -INFINITY) ? 0.f : __expf(ms - M);
     }
-    out[((int64_t)b * Hq + h) * hd + c] = L > 0.f ? acc / L : 0.f;
-    if (lse && c == 0) lse[(int64_t)b * Hq + h] = L > 0.f ? M + logf(L) : -INFINITY;
+    __syncthreads();
+    float L = 0.f;
+    for (int s = 0; s < nparts; s++) L = fmaf(base[s * stride + hd + 1], s_w[s], L);
+    if (tid < hd) {
+        float acc = 0.f;
+        int s = 0;
+        for (; s + 4 <= nparts; s += 4) {
+            const float a0 = base[(s + 0) * stride + tid], a1 = base[(s + 1) * stride + tid];
+            const float a2 = base[(s + 2) * stride + tid], a3 = base[(s + 3) * stride + tid];
+            acc = fmaf(a0, s_w[s], acc);
+            acc = fmaf(a1, s_w[s + 1], acc);
+            acc = fmaf(a2, s_w[s + 2], acc);
+            acc = fmaf(a3, s_w[s + 3], acc);
+        }
+        for (; s < nparts; s++) acc = fmaf(base[s * stride + tid], s_w[s], acc);
+        out[((int64_t)b * Hq + h) * hd + tid] = L > 0.f ? acc / L : 0.f;
+    }
+    if (lse && tid == 0) lse[(int64_t)b * Hq + h] = L > 0.f ? M + logf(L) : -INFINITY;
 }
 
 }  // namespace
 
 // workgroups per (sequence, KV head) given to the 16-bit segment by the matrix-core launch: about one per
-// 64 rows of the average sequence's capacity, between 1 and 32
+// 32 rows of the average sequence's capacity, between 1 and 32
 static int wq_decode_splits16(int B, int64_t cap16)
 {
     int64_t per = B > 0 ? cap16 / B : 0;
-    int64_t n = (per + 63) / 64;
+    int64_t n = (per + 31) / 32;
     return (int)(n < 1 ? 1 : (n > 32 ? 32 : n));
 }
 
@@ -335,12 +360,24 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.nparts = a.splits + a.splits16;
     a.kv = *kv;
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
-    dim3 grid(a.nparts, kv->Hkv, B);
-    if (kv->hd == 128)
-        hipLaunchKernelGGL(k_decode<128>, grid, dim3(256), 0, ctx->stream, a);
-    else
-        hipLaunchKernelGGL(k_decode<64>, grid, dim3(256), 0, ctx->stream, a);
-    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(kv->hd), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
+    const dim3 blk(256);
+    const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16, kv->Hkv, B);
+    if (kv->hd == 128) {
+        if (a.use_mfma) {
+            hipLaunchKernelGGL(k_decode_mfma<128>, grid_q, blk, 0, ctx->stream, a);
+            hipLaunchKernelGGL(k_decode_generic<128>, grid_16, blk, 0, ctx->stream, a);
+        } else {
+            hipLaunchKernelGGL(k_decode_generic<128>, grid_q, blk, 0, ctx->stream, a);
+        }
+    } else {
+        if (a.use_mfma) {
+            hipLaunchKernelGGL(k_decode_mfma<64>, grid_q, blk, 0, ctx->stream, a);
+            hipLaunchKernelGGL(k_decode_generic<64>, grid_16, blk, 0, ctx->stream, a);
+        } else {
+            hipLaunchKernelGGL(k_decode_generic<64>, grid_q, blk, 0, ctx->stream, a);
+        }
+    }
+    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

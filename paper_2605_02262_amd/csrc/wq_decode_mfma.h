@@ -1,4 +1,5 @@
 // a4, matrix-core path: decode attention over the packed cache for hd/group == 2 (Alg. 2 decode half).
+// (included by wq_decode.hip, after DecodeArgs and load_q)
 //
 // One wavefront walks 32-token blocks of a class on its own (no workgroup barrier inside the loop):
 //
@@ -19,9 +20,9 @@
 // folded into the other operand (q or P'), the common 2^-24 into constants applied after the contraction.
 //
 // The storage layout (wq.h) is exactly the per-lane operand order, so every load is one contiguous piece per
-// lane, a whole tile per wavefront.  The 16-bit segment is handled by extra workgroups of the generic kernel.
+// lane, a whole tile per wavefront.  Scales and minima travel as one coalesced word per lane and block and are
+// redistributed through LDS.  The query operands of all three classes are built once per workgroup in LDS.
 #pragma once
-// (included by wq_decode.hip, after DecodeArgs and load_q)
 
 namespace {
 
@@ -52,17 +53,16 @@ __device__ __forceinline__ float ror8(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xF, 0xF, false));
 }
 
-// ---- where the matrix instruction's contraction slot e (0..7) of k-step r finds its channel and bit shift ----
-// Returns the channel inside the lane's quarter (hd/4 channels) and the left shift the code keeps in its f16 half.
-template <int BITS>
-__device__ __forceinline__ void k_slot(int r, int e, int& ch, int& sh)
+// ---- where contraction slot e (0..7) of k-step r finds its channel (inside the lane's quarter of hd/4
+// channels) and the left shift its code keeps inside the f16 half; c = class index (0,1,2 = 2,4,8 bits) ----
+__device__ __forceinline__ void k_slot(int c, int r, int e, int& ch, int& sh)
 {
     const int v = e >> 1, hi = e & 1;
-    if (BITS == 2) {            // dword d = r/2 holds 16 fields; pair p = 4*(r%2)+v is (field p, field p+8)
+    if (c == 0) {               // dword d = r/2 holds 16 fields; pair p = 4*(r%2)+v is (field p, field p+8)
         const int d = r >> 1, p = 4 * (r & 1) + v;
         ch = 16 * d + p + 8 * hi;
         sh = p <= 4 ? 2 * p : 2 * (p - 5);
-    } else if (BITS == 4) {     // dword r holds 8 fields; pair v is (field v, field v+4)
+    } else if (c == 1) {        // dword r holds 8 fields; pair v is (field v, field v+4)
         ch = 8 * r + v + 4 * hi;
         sh = 4 * (v & 1);
     } else {                    // dwords 2r, 2r+1; register v = (dword v/2, bytes (v%2, v%2+2))
@@ -129,23 +129,59 @@ struct WaveState {
 
 template <int HD>
 struct MfmaSmem {
-    _Float16 q[WQ_MAX_REP][HD];       // query, per head scaled by a power of two into [-1, 1]
-    float qexp[WQ_MAX_REP];           // that power of two
-    float O[4][WQ_MAX_REP][HD];       // per-wave numerators for the merge
+    union {
+        struct {
+            _Float16 bq[3][HD / 32][64][8];   // B operands of the logit product: [class][k-step][lane][slot]
+            _Float16 q[WQ_MAX_REP][HD];       // query, per head scaled by a power of two into [-1, 1]
+            uint32_t meta[4][2][64];          // per wave: K and V metadata words of the current block
+        } run;
+        float O[4][WQ_MAX_REP][HD];           // per-wave numerators for the merge (after the loops)
+    };
+    float qexp[WQ_MAX_REP];                   // the heads' powers of two
+    float qsum[WQ_MAX_REP][2];                // sum of the scaled query over each group
     float ml[4][WQ_MAX_REP][2];
 };
 
-// One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
 template <int HD, int BITS>
-__device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, int b, int kvh, int share, int nshare, float c_log2,
-                                WaveState<HD>& st)
+struct Frag {
+    static constexpr int KDW = (HD / 4) * BITS / 32;        // dwords of K codes per lane per 16-token tile
+    static constexpr int VDW = (HD / 16) * 8 * BITS / 32;   // dwords of V codes per lane per 32-token block
+    uint32_t k[2][KDW];
+    uint32_t v[VDW];
+    uint32_t km, vm;                                        // one metadata word per lane and plane
+};
+
+template <int N>
+__device__ __forceinline__ void load_dwords(const uint32_t* __restrict__ p, uint32_t* dst)
+{
+    if constexpr (N == 1) {
+        dst[0] = p[0];
+    } else if constexpr (N == 2) {
+        uint2 u = *reinterpret_cast<const uint2*>(p);
+        dst[0] = u.x;
+        dst[1] = u.y;
+    } else {
+#pragma unroll
+        for (int d = 0; d < N; d += 4) {
+            uint4 u = *reinterpret_cast<const uint4*>(p + d);
+            dst[d] = u.x;
+            dst[d + 1] = u.y;
+            dst[d + 2] = u.z;
+            dst[d + 3] = u.w;
+        }
+    }
+}
+
+// One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
+template <int HD, int BITS, int DEPTH>
+__device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int share, int nshare,
+                                                float c_log2, WaveState<HD>& st)
 {
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
     constexpr int NK = HD / 32;                    // k-steps of the logit product per 16-token tile
     constexpr int CT = HD / 16;                    // channel tiles of the value product
-    constexpr int KDW = (HD / 4) * BITS / 32;      // dwords of K codes per lane per tile
-    constexpr int VDW = (HD / 16) * 8 * BITS / 32; // dwords of V codes per lane per block
-    const int lane = threadIdx.x & 63;
+    using F = Frag<HD, BITS>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
 
     const int len = kv.cls_len[C][b];
@@ -153,92 +189,49 @@ __device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, 
     const int blk_lo = (int)((int64_t)share * nblk / nshare), blk_hi = (int)((int64_t)(share + 1) * nblk / nshare);
     if (blk_lo >= blk_hi) return;
 
-    // ---- B operand of the logit product for this class: q (scaled into [-1,1]) times 2^-shift of its slot ----
     half8 Bq[NK];
-    float qsum = 0.f;                              // sum of q' over this lane's group (all four quarters' worth)
-    {
-        const bool mine = (j >> 1) == g;           // slots 8j.. belong to channel quarter j, group j/2
 #pragma unroll
-        for (int r = 0; r < NK; r++) {
-            half8 v;
-#pragma unroll
-            for (int e = 0; e < 8; e++) {
-                int ch, sh;
-                k_slot<BITS>(r, e, ch, sh);
-                float qv = (mine && h < WQ_MAX_REP) ? (float)sm.q[h][j * (HD / 4) + ch] : 0.f;
-                v[e] = (_Float16)(qv * __builtin_ldexpf(1.0f, -sh));
-            }
-            Bq[r] = v;
-        }
-        for (int ch = 0; ch < HD / 2; ch++) qsum += (float)sm.q[h][g * (HD / 2) + ch];
-    }
+    for (int r = 0; r < NK; r++) Bq[r] = *reinterpret_cast<const half8*>(&sm.run.bq[C][r][lane][0]);
     // logits come out of the matrix cores as 2^-24 * sum q' code; fold 2^24, the head's power of two and
     // sm_scale*log2(e) into one constant, and pre-divide the m-term by 2^24 so both terms share it.
     const float cexp = c_log2 * sm.qexp[h] * 16777216.0f;
-    const float qs = qsum * (1.0f / 16777216.0f);
+    const float qs = sm.qsum[h][g] * (1.0f / 16777216.0f);
 
     const int64_t cap = kv.cap[C];
     const int64_t tok_base = kv.cls_off[C][b];
-    const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok_base) * HD * BITS / 8;
-    const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * HD * BITS / 8;
-    const uint32_t* kmeta = static_cast<const uint32_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok_base) * 2;
-    const uint32_t* vmeta = static_cast<const uint32_t*>(kv.meta[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * 2;
-    const int moff = g * 16 + 4 * j;               // word offset of (group g, tokens 4j..4j+3) inside a metadata tile
+    const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok_base) * HD * BITS / 8 + lane * (F::KDW * 4);
+    const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * HD * BITS / 8 + lane * (F::VDW * 4);
+    const uint32_t* kmeta = static_cast<const uint32_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok_base) * 2 + lane;
+    const uint32_t* vmeta = static_cast<const uint32_t*>(kv.meta[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * 2 + lane;
+    uint32_t* smeta = &sm.run.meta[wave][0][0];
+    const int moff = g * 16 + 4 * j;               // (group g, tokens 4j..4j+3) inside a metadata tile of 32 words
 
-    struct Frag {
-        uint32_t k[2][KDW];
-        uint32_t v[VDW];
-        uint4 km[2], vm[2];
-    };
-    auto load = [&](int blk, Frag& f) {
-        const uint8_t* kp = kbase + (int64_t)blk * (32 * HD * BITS / 8) + lane * (KDW * 4);
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            const uint32_t* p = reinterpret_cast<const uint32_t*>(kp + t * (16 * HD * BITS / 8));
-            if constexpr (KDW == 1) {
-                f.k[t][0] = p[0];
-            } else if constexpr (KDW == 2) {
-                uint2 u = *reinterpret_cast<const uint2*>(p);
-                f.k[t][0] = u.x;
-                f.k[t][1] = u.y;
-            } else {
-#pragma unroll
-                for (int d = 0; d < KDW; d += 4) {
-                    uint4 u = *reinterpret_cast<const uint4*>(p + d);
-                    f.k[t][d] = u.x;
-                    f.k[t][d + 1] = u.y;
-                    f.k[t][d + 2] = u.z;
-                    f.k[t][d + 3] = u.w;
-                }
-            }
-        }
-        const uint32_t* vp = reinterpret_cast<const uint32_t*>(vbase + (int64_t)blk * (32 * HD * BITS / 8) + lane * (VDW * 4));
-        if constexpr (VDW == 2) {
-            uint2 u = *reinterpret_cast<const uint2*>(vp);
-            f.v[0] = u.x;
-            f.v[1] = u.y;
-        } else {
-#pragma unroll
-            for (int d = 0; d < VDW; d += 4) {
-                uint4 u = *reinterpret_cast<const uint4*>(vp + d);
-                f.v[d] = u.x;
-                f.v[d + 1] = u.y;
-                f.v[d + 2] = u.z;
-                f.v[d + 3] = u.w;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            f.km[t] = *reinterpret_cast<const uint4*>(kmeta + ((int64_t)blk * 2 + t) * 32 + moff);
-            f.vm[t] = *reinterpret_cast<const uint4*>(vmeta + ((int64_t)blk * 2 + t) * 32 + moff);
-        }
+    auto load = [&](int blk, F& f) {
+        const int64_t o = (int64_t)blk * (32 * HD * BITS / 8);
+        load_dwords<F::KDW>(reinterpret_cast<const uint32_t*>(kbase + o), f.k[0]);
+        load_dwords<F::KDW>(reinterpret_cast<const uint32_t*>(kbase + o + 16 * HD * BITS / 8), f.k[1]);
+        load_dwords<F::VDW>(reinterpret_cast<const uint32_t*>(vbase + o), f.v);
+        f.km = kmeta[(int64_t)blk * 64];
+        f.vm = vmeta[(int64_t)blk * 64];
     };
 
-    Frag cur;
-    load(blk_lo, cur);
-    for (int blk = blk_lo; blk < blk_hi; blk++) {
-        Frag nxt;
-        if (blk + 1 < blk_hi) load(blk + 1, nxt);
+    auto compute = [&](int blk, const F& f) {
+        // ---- scales and minima: one word per lane in, the lane's 4 tokens x 2 tiles x {K,V} out ----
+        smeta[lane] = f.km;
+        smeta[64 + lane] = f.vm;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t kw[8], vw[8];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            const uint4 a = *reinterpret_cast<const uint4*>(smeta + t * 32 + moff);
+            const uint4 c = *reinterpret_cast<const uint4*>(smeta + 64 + t * 32 + moff);
+            kw[4 * t] = a.x, kw[4 * t + 1] = a.y, kw[4 * t + 2] = a.z, kw[4 * t + 3] = a.w;
+            vw[4 * t] = c.x, vw[4 * t + 1] = c.y, vw[4 * t + 2] = c.z, vw[4 * t + 3] = c.w;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the next block's words may overwrite the buffer after this point
 
         // ---- logits of the two 16-token tiles ----
         float x[8];
@@ -246,11 +239,10 @@ __device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, 
         for (int t = 0; t < 2; t++) {
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < NK; r++) acc = mfma(k_operand<BITS>(cur.k[t], r), Bq[r], acc);
-            const uint32_t mw[4] = {cur.km[t].x, cur.km[t].y, cur.km[t].z, cur.km[t].w};
+            for (int r = 0; r < NK; r++) acc = mfma(k_operand<BITS>(f.k[t], r), Bq[r], acc);
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                float y = fmaf(f16lo(mw[i]), acc[i], f16hi(mw[i]) * qs);
+                const float y = fmaf(f16lo(kw[4 * t + i]), acc[i], f16hi(kw[4 * t + i]) * qs);
                 x[4 * t + i] = y + ror8(y);
             }
         }
@@ -269,7 +261,7 @@ __device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, 
             lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
             lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
             const float mn = fmaxf(st.m, lm);
-            const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);  // 0 on the first block
+            const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);   // 0 on the first block
             st.m = mn;
             st.l *= alpha;
             st.accM *= alpha;
@@ -277,8 +269,6 @@ __device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, 
             for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
         }
         // ---- weights, P' = p * s_v * slot scale, and the m_v part ----
-        const uint32_t vw[8] = {cur.vm[0].x, cur.vm[0].y, cur.vm[0].z, cur.vm[0].w,
-                                cur.vm[1].x, cur.vm[1].y, cur.vm[1].z, cur.vm[1].w};
         _Float16 pp[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
@@ -295,8 +285,22 @@ __device__ void walk_class_mfma(const wq_packed_kv& kv, const MfmaSmem<HD>& sm, 
         }
         // ---- values ----
 #pragma unroll
-        for (int ct = 0; ct < CT; ct++) st.O[ct] = mfma(v_operand<BITS>(cur.v, ct), Bp, st.O[ct]);
-        cur = nxt;
+        for (int ct = 0; ct < CT; ct++) st.O[ct] = mfma(v_operand<BITS>(f.v, ct), Bp, st.O[ct]);
+    };
+
+    // software pipeline: DEPTH blocks in flight per wavefront
+    F f[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++)
+        if (blk_lo + d < blk_hi) load(blk_lo + d, f[d]);
+    for (int blk = blk_lo; blk < blk_hi; blk += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; d++) {
+            if (blk + d < blk_hi) {
+                compute(blk + d, f[d]);
+                if (blk + d + DEPTH < blk_hi) load(blk + d + DEPTH, f[d]);
+            }
+        }
     }
 }
 
@@ -307,27 +311,43 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
-    constexpr int CT = HD / 16;
+    constexpr int CT = HD / 16, NK = HD / 32, QC = HD / 4;
 
-    // ---- query: per head, scale by a power of two so that max |q| is in [0.5, 1]; keep it as f16 ----
-    if (wave < 2) {
-        for (int r = wave * 4; r < wave * 4 + 4; r++) {
-            float v0 = 0.f, v1 = 0.f;
-            if (r < a.rep) {
-                const int64_t base = ((int64_t)b * a.Hq + kvh * a.rep + r) * HD;
-                v0 = load_q(a.q, a.q_dtype, base + lane);
-                if (HD == 128) v1 = load_q(a.q, a.q_dtype, base + 64 + lane);
-            }
-            float mx = fmaxf(fabsf(v0), fabsf(v1));
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-            int ex = 0;
-            if (mx > 0.f && mx < INFINITY) (void)frexpf(mx, &ex);      // mx = f * 2^ex, f in [0.5, 1)
-            const float dn = __builtin_ldexpf(1.0f, -ex);
-            sm.q[r][lane] = (_Float16)(v0 * dn);
-            if (HD == 128) sm.q[r][64 + lane] = (_Float16)(v1 * dn);
-            if (lane == 0) sm.qexp[r] = __builtin_ldexpf(1.0f, ex);
+    // ---- query: per head, scale by a power of two so that max |q| lands in [0.5, 1); keep it as f16 ----
+    for (int r = wave; r < WQ_MAX_REP; r += 4) {
+        float v0 = 0.f, v1 = 0.f;
+        if (r < a.rep) {
+            const int64_t base = ((int64_t)b * a.Hq + kvh * a.rep + r) * HD;
+            v0 = load_q(a.q, a.q_dtype, base + lane);
+            if (HD == 128) v1 = load_q(a.q, a.q_dtype, base + 64 + lane);
         }
+        float mx = fmaxf(fabsf(v0), fabsf(v1));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        const int eb = (int)((__float_as_uint(mx) >> 23) & 0xFFu);            // biased exponent of the largest |q|
+        const bool ok = eb > 0 && eb < 253;                                     // zero, denormal or non-finite: leave as is
+        const float dn = ok ? __uint_as_float((uint32_t)(253 - eb) << 23) : 1.0f;   // 2^-(eb-126)
+        const float up = ok ? __uint_as_float((uint32_t)(eb + 1) << 23) : 1.0f;     // 2^(eb-126)
+        sm.run.q[r][lane] = (_Float16)(v0 * dn);
+        if (HD == 128) sm.run.q[r][64 + lane] = (_Float16)(v1 * dn);
+        if (lane == 0) sm.qexp[r] = up;
+    }
+    __syncthreads();
+    // ---- B operands of the logit product for all three classes, and the per-group sums of q' ----
+    for (int idx = tid; idx < 3 * NK * 512; idx += 256) {
+        const int e = idx & 7, ln = (idx >> 3) & 63, r = (idx >> 9) % NK, c = idx / (NK * 512);
+        const int lj = ln >> 4, lcol = ln & 15, lg = lcol >> 3, lh = lcol & 7;
+        int ch, sh;
+        k_slot(c, r, e, ch, sh);
+        float qv = 0.f;
+        if ((lj >> 1) == lg) qv = (float)sm.run.q[lh][lj * QC + ch] * __uint_as_float((uint32_t)(127 - sh) << 23);
+        sm.run.bq[c][r][ln][e] = (_Float16)qv;
+    }
+    if (tid < 2 * WQ_MAX_REP) {
+        const int hh = tid >> 1, gg = tid & 1;
+        float s = 0.f;
+        for (int ch = 0; ch < HD / 2; ch++) s += (float)sm.run.q[hh][gg * (HD / 2) + ch];
+        sm.qsum[hh][gg] = s;
     }
     __syncthreads();
 
@@ -339,9 +359,9 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     st.accM = 0.f;
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
     const int share = split * 4 + wave, nshare = a.splits * 4;
-    walk_class_mfma<HD, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
-    walk_class_mfma<HD, 4>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
-    walk_class_mfma<HD, 8>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    walk_class_mfma<HD, 2, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    walk_class_mfma<HD, 4, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    walk_class_mfma<HD, 8, 1>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
 
     // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
     float l = st.l, am = st.accM;
@@ -349,34 +369,31 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     l += __shfl_xor(l, 32, 64);
     am += __shfl_xor(am, 16, 64);
     am += __shfl_xor(am, 32, 64);
-    if (h < WQ_MAX_REP) {
+    __syncthreads();                               // every wave is done with the run-time part of LDS
 #pragma unroll
-        for (int ct = 0; ct < CT; ct++) {
-            if ((ct >= CT / 2) == (g == 1)) {      // this column's group owns channel tile ct
+    for (int ct = 0; ct < CT; ct++) {
+        if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
 #pragma unroll
-                for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
-            }
+            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
         }
-        if (j == 0 && g == 0) {
-            sm.ml[wave][h][0] = st.m;
-            sm.ml[wave][h][1] = l;
-        }
+    }
+    if (j == 0 && g == 0) {
+        sm.ml[wave][h][0] = st.m;
+        sm.ml[wave][h][1] = l;
     }
     __syncthreads();
     // ---- merge the four waves, write the partial (m in natural-log units) ----
     float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts + split) * a.rep * (HD + 2);
     for (int idx = tid; idx < a.rep * HD; idx += 256) {
         const int r = idx / HD, ch = idx - r * HD;
-        float M = fmaxf(fmaxf(sm.ml[0][r][0], sm.ml[1][r][0]), fmaxf(sm.ml[2][r][0], sm.ml[3][r][0]));
+        const float M = fmaxf(fmaxf(sm.ml[0][r][0], sm.ml[1][r][0]), fmaxf(sm.ml[2][r][0], sm.ml[3][r][0]));
         float num = 0.f, L = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; w++) {
             const float mw = sm.ml[w][r][0];
-            if (mw != -INFINITY) {
-                const float s = exp2f(mw - M);
-                num = fmaf(sm.O[w][r][ch], s, num);
-                L = fmaf(sm.ml[w][r][1], s, L);
-            }
+            const float s = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+            num = fmaf(sm.O[w][r][ch], s, num);
+            L = fmaf(sm.ml[w][r][1], s, L);
         }
         out[r * (HD + 2) + ch] = num;
         if (ch == 0) {
