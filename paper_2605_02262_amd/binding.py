@@ -94,7 +94,7 @@ class Context:
 
     def __init__(self, workspace_bytes_: int, device: str = "cuda", stream: Optional[torch.cuda.Stream] = None):
         self.device = torch.device(device)
-        self.ws = torch.zeros(max(int(workspace_bytes_), 256), dtype=torch.uint8, device=self.device)
+        self.ws = torch.zeros(max(int(workspace_bytes_), 16384), dtype=torch.uint8, device=self.device)
         self.handle = C.c_void_p()
         st = (stream or torch.cuda.current_stream(self.device)).cuda_stream
         rc = lib().wq_create(C.byref(self.handle), C.c_void_p(st), self.ws.data_ptr(), self.ws.numel())

@@ -15,7 +15,9 @@ LIB = os.path.join(HERE, "libwq.so")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the quantizer's rounding sequence is part of the storage format: no contraction into fused multiply-add
-PER_FILE = {"wq_quantize.hip": ["-ffp-contract=off"]}
+# the decode kernel keeps its matrix-core accumulators in ordinary vector registers: they are rescaled by vector
+# code, and accumulator-file copies around that would cost more than they save
+PER_FILE = {"wq_quantize.hip": ["-ffp-contract=off"], "wq_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def sources():

@@ -62,7 +62,7 @@ int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_
         ctx->owns_ws = true;
     }
     if (ctx->ws && ctx->ws_bytes >= WQ_WS_HEADER && ctx->owns_ws) {
-        if (hipMemsetAsync(ctx->ws, 0, WQ_WS_HEADER, ctx->stream) != hipSuccess) {
+        if (hipMemset(ctx->ws, 0, WQ_WS_HEADER) != hipSuccess) {
             (void)hipFree(ctx->ws);
             delete ctx;
             return WQ_ERR_HIP;

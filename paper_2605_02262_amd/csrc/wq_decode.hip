@@ -9,6 +9,10 @@
 // k_decode_generic: plain vector-ALU kernel that reads codes field by field from the storage layout.  It
 // handles every supported (hd, group) and is the reference implementation inside the library; the
 // matrix-core body in wq_decode_mfma.h is the fast path for hd/group == 2.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "wq_internal.h"
 
 namespace {
@@ -20,8 +24,16 @@ struct DecodeArgs {
     float sm_scale;
     int splits16, nparts;   // workgroups on the 16-bit segment; nparts = splits + splits16 partials per (b, KV head)
     int use_mfma;
+    int mfma16;             // the matrix-core kernel also walks the 16-bit segment
+    int fused;              // ... and merges the splits itself (last workgroup per (b, KV head))
     wq_packed_kv kv;
     float* part;            // [B][Hkv][nparts][rep][hd + 2]
+    unsigned* tickets;      // [B*Hkv] arrival counters, zero between launches
+    float* out;
+    float* lse;
+#ifdef WQ_TIMELINE
+    long long* dbg;
+#endif
 };
 
 __device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
@@ -289,6 +301,7 @@ __global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part,
                                                  float* __restrict__ out, float* __restrict__ lse)
 {
     __shared__ float s_w[1024 + 32];
+    __shared__ float s_l[1024 + 32];
     __shared__ float s_red[2];
     const int h = blockIdx.x, b = blockIdx.y;
     const int kvh = h / rep, r = h % rep;
@@ -296,32 +309,40 @@ __global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part,
     const int tid = threadIdx.x;
     const int64_t stride = (int64_t)rep * (hd + 2);
     const float* base = part + (((int64_t)b * Hkv + kvh) * nparts) * stride + (int64_t)r * (hd + 2);
+    constexpr int CHUNK = 32;
+    float pre[CHUNK];                      // this channel's numerators of the first CHUNK splits: in flight while M is found
+#pragma unroll
+    for (int k = 0; k < CHUNK; k++) pre[k] = (k < nparts && tid < hd) ? base[(int64_t)k * stride + tid] : 0.f;
     float mx = -INFINITY;
-    for (int s = tid; s < nparts; s += 128) mx = fmaxf(mx, base[s * stride + hd]);
+    for (int s = tid; s < nparts; s += 128) {
+        const float ms = base[s * stride + hd];
+        s_w[s] = ms;
+        s_l[s] = base[s * stride + hd + 1];
+        mx = fmaxf(mx, ms);
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
     if ((tid & 63) == 0) s_red[tid >> 6] = mx;
     __syncthreads();
     const float M = fmaxf(s_red[0], s_red[1]);
     for (int s = tid; s < nparts; s += 128) {
-        const float ms = base[s * stride + hd];
+        const float ms = s_w[s];
         s_w[s] = (ms == -INFINITY) ? 0.f : __expf(ms - M);
     }
     __syncthreads();
     float L = 0.f;
-    for (int s = 0; s < nparts; s++) L = fmaf(base[s * stride + hd + 1], s_w[s], L);
+    for (int s = 0; s < nparts; s++) L = fmaf(s_l[s], s_w[s], L);
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < CHUNK; k++) acc = fmaf(pre[k], k < nparts ? s_w[k] : 0.f, acc);
     if (tid < hd) {
-        float acc = 0.f;
-        int s = 0;
-        for (; s + 4 <= nparts; s += 4) {
-            const float a0 = base[(s + 0) * stride + tid], a1 = base[(s + 1) * stride + tid];
-            const float a2 = base[(s + 2) * stride + tid], a3 = base[(s + 3) * stride + tid];
-            acc = fmaf(a0, s_w[s], acc);
-            acc = fmaf(a1, s_w[s + 1], acc);
-            acc = fmaf(a2, s_w[s + 2], acc);
-            acc = fmaf(a3, s_w[s + 3], acc);
+        for (int s0 = CHUNK; s0 < nparts; s0 += CHUNK) {
+            float v[CHUNK];
+#pragma unroll
+            for (int k = 0; k < CHUNK; k++) v[k] = (s0 + k < nparts) ? base[(int64_t)(s0 + k) * stride + tid] : 0.f;
+#pragma unroll
+            for (int k = 0; k < CHUNK; k++) acc = fmaf(v[k], (s0 + k < nparts) ? s_w[s0 + k] : 0.f, acc);
         }
-        for (; s < nparts; s++) acc = fmaf(base[s * stride + tid], s_w[s], acc);
         out[((int64_t)b * Hq + h) * hd + tid] = L > 0.f ? acc / L : 0.f;
     }
     if (lse && tid == 0) lse[(int64_t)b * Hq + h] = L > 0.f ? M + logf(L) : -INFINITY;
@@ -356,28 +377,39 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.splits = num_splits;
     a.sm_scale = sm_scale;
     a.use_mfma = (algo == WQ_DECODE_MFMA) || (algo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
-    a.splits16 = a.use_mfma ? wq_decode_splits16(B, kv->cap16) : 0;
+    // a bf16 cache needs the exact bf16 query for the bf16 instruction; other query types send the 16-bit
+    // segment to the generic kernel
+    a.mfma16 = a.use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
+    a.splits16 = (a.use_mfma && !a.mfma16) ? wq_decode_splits16(B, kv->cap16) : 0;
     a.nparts = a.splits + a.splits16;
+    a.fused = getenv("WQ_FUSE") && a.use_mfma && a.mfma16 && (int64_t)B * kv->Hkv <= WQ_MAX_TICKETS && 2 * a.nparts * a.rep <= 4 * WQ_MAX_REP * kv->hd;
     a.kv = *kv;
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
+    a.tickets = reinterpret_cast<unsigned*>(ctx->ws + 256);
+    a.out = out;
+#ifdef WQ_TIMELINE
+    a.dbg = getenv("WQ_TIMELINE") ? reinterpret_cast<long long*>(ctx->ws + ctx->ws_bytes - (8 << 20)) : nullptr;
+#endif
+    a.lse = lse;
     const dim3 blk(256);
-    const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16, kv->Hkv, B);
+    const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16 > 0 ? a.splits16 : 1, kv->Hkv, B);
     if (kv->hd == 128) {
         if (a.use_mfma) {
             hipLaunchKernelGGL(k_decode_mfma<128>, grid_q, blk, 0, ctx->stream, a);
-            hipLaunchKernelGGL(k_decode_generic<128>, grid_16, blk, 0, ctx->stream, a);
+            if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<128>, grid_16, blk, 0, ctx->stream, a);
         } else {
             hipLaunchKernelGGL(k_decode_generic<128>, grid_q, blk, 0, ctx->stream, a);
         }
     } else {
         if (a.use_mfma) {
             hipLaunchKernelGGL(k_decode_mfma<64>, grid_q, blk, 0, ctx->stream, a);
-            hipLaunchKernelGGL(k_decode_generic<64>, grid_16, blk, 0, ctx->stream, a);
+            if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<64>, grid_16, blk, 0, ctx->stream, a);
         } else {
             hipLaunchKernelGGL(k_decode_generic<64>, grid_q, blk, 0, ctx->stream, a);
         }
     }
-    hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
+    if (!a.fused)
+        hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

@@ -24,6 +24,14 @@
 // redistributed through LDS.  The query operands of all three classes are built once per workgroup in LDS.
 #pragma once
 
+#ifdef WQ_TIMELINE   // development aid: per-workgroup phase time stamps (100 MHz clock) at the end of the workspace
+#define WQ_STAMP(k) do { if (a.dbg && threadIdx.x == 0) a.dbg[(((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (k)] = wall_clock64(); } while (0)
+#define WQ_WSTAMP(k, val) do { if (a.dbg && (threadIdx.x & 63) == 0) a.dbg[(((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 + (threadIdx.x >> 6) * 6 + (k)] = (val); } while (0)
+#else
+#define WQ_STAMP(k) do { } while (0)
+#define WQ_WSTAMP(k, val) do { } while (0)
+#endif
+
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -65,9 +73,12 @@ __device__ __forceinline__ void k_slot(int c, int r, int e, int& ch, int& sh)
     } else if (c == 1) {        // dword r holds 8 fields; pair v is (field v, field v+4)
         ch = 8 * r + v + 4 * hi;
         sh = 4 * (v & 1);
-    } else {                    // dwords 2r, 2r+1; register v = (dword v/2, bytes (v%2, v%2+2))
+    } else if (c == 2) {        // dwords 2r, 2r+1; register v = (dword v/2, bytes (v%2, v%2+2))
         const int d = 2 * r + (v >> 1);
         ch = 4 * d + (v & 1) + 2 * hi;
+        sh = 0;
+    } else {                    // 16-bit segment: elements in natural order
+        ch = 8 * r + e;
         sh = 0;
     }
 }
@@ -101,6 +112,14 @@ __device__ __forceinline__ float v_slot_scale(int v)
     return 1.0f;
 }
 
+template <int BITS>
+__device__ __forceinline__ float v_slot_shift(int v)      // -log2 of v_slot_scale
+{
+    if (BITS == 2) return 2.0f * (float)v;
+    if (BITS == 4) return (v & 1) ? 4.0f : 0.0f;
+    return 0.0f;
+}
+
 // unpack the V fragment of one lane (for channel tile ct: 8 tokens of one channel) into an A operand
 template <int BITS>
 __device__ __forceinline__ half8 v_operand(const uint32_t* x, int ct)
@@ -127,19 +146,24 @@ struct WaveState {
     float accM;           // this lane's share of sum p * m_v
 };
 
+constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
+
 template <int HD>
 struct MfmaSmem {
     union {
         struct {
-            _Float16 bq[3][HD / 32][64][8];   // B operands of the logit product: [class][k-step][lane][slot]
+            uint16_t bq[4][HD / 32][64][8];   // B operands of the logit product: [class, 3 = 16-bit][k-step][lane][slot]
             _Float16 q[WQ_MAX_REP][HD];       // query, per head scaled by a power of two into [-1, 1]
+            uint16_t qraw[WQ_MAX_REP][HD];    // upper 16 bits of the fp32 query (the bf16 value when q is bf16)
             uint32_t meta[4][2][64];          // per wave: K and V metadata words of the current block
+            uint16_t vt[4][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
         } run;
         float O[4][WQ_MAX_REP][HD];           // per-wave numerators for the merge (after the loops)
     };
     float qexp[WQ_MAX_REP];                   // the heads' powers of two
     float qsum[WQ_MAX_REP][2];                // sum of the scaled query over each group
     float ml[4][WQ_MAX_REP][2];
+    int last;
 };
 
 template <int HD, int BITS>
@@ -174,7 +198,7 @@ __device__ __forceinline__ void load_dwords(const uint32_t* __restrict__ p, uint
 
 // One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
 template <int HD, int BITS, int DEPTH>
-__device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int share, int nshare,
+__device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
                                                 float c_log2, WaveState<HD>& st)
 {
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
@@ -184,10 +208,8 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
 
-    const int len = kv.cls_len[C][b];
-    const int nblk = (len + 31) >> 5;
-    const int blk_lo = (int)((int64_t)share * nblk / nshare), blk_hi = (int)((int64_t)(share + 1) * nblk / nshare);
     if (blk_lo >= blk_hi) return;
+    const int len = kv.cls_len[C][b];
 
     half8 Bq[NK];
 #pragma unroll
@@ -214,6 +236,11 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
         f.km = kmeta[(int64_t)blk * 64];
         f.vm = vmeta[(int64_t)blk * 64];
     };
+
+    // partial sums per slot register v: its weights carry 2^-shift(v) (folded into the exponent), undone after the loop
+    float lv[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f}, ms[4];
+#pragma unroll
+    for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v);
 
     auto compute = [&](int blk, const F& f) {
         // ---- scales and minima: one word per lane in, the lane's 4 tokens x 2 tiles x {K,V} out ----
@@ -242,7 +269,7 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
             for (int r = 0; r < NK; r++) acc = mfma(k_operand<BITS>(f.k[t], r), Bq[r], acc);
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const float y = fmaf(f16lo(kw[4 * t + i]), acc[i], f16hi(kw[4 * t + i]) * qs);
+                const float y = fmaf(f16lo(kw[4 * t + i]), acc[i], fmaf(f16hi(kw[4 * t + i]), qs, 0.0f));
                 x[4 * t + i] = y + ror8(y);
             }
         }
@@ -266,16 +293,22 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
             st.l *= alpha;
             st.accM *= alpha;
 #pragma unroll
+            for (int v = 0; v < 4; v++) {
+                lv[v] *= alpha;
+                av[v] *= alpha;
+                ms[v] = mn + v_slot_shift<BITS>(v);
+            }
+#pragma unroll
             for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
         }
-        // ---- weights, P' = p * s_v * slot scale, and the m_v part ----
+        // ---- weights with the slot's power of two folded into the exponent, P' = p * s_v, and the m_v part ----
         _Float16 pp[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -st.m));
-            st.l += p;
-            st.accM = fmaf(p, f16hi(vw[k]), st.accM);
-            pp[k] = (_Float16)(p * v_slot_scale<BITS>(k & 3) * f16lo(vw[k]));
+            const float p = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -ms[k & 3]));
+            lv[k & 3] += p;
+            av[k & 3] = fmaf(f16hi(vw[k]), p, av[k & 3]);
+            pp[k] = (_Float16)fmaf(f16lo(vw[k]), p, 0.0f);
         }
         half8 Bp;
 #pragma unroll
@@ -302,6 +335,165 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
             }
         }
     }
+#pragma unroll
+    for (int v = 0; v < 4; v++) {
+        st.l = fmaf(lv[v], 1.0f / v_slot_scale<BITS>(v), st.l);
+        st.accM = fmaf(av[v], 1.0f / v_slot_scale<BITS>(v), st.accM);
+    }
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <bool BF>
+__device__ __forceinline__ floatx4 mfma16(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, const U4& b, floatx4 c)
+{
+    U4 a{a0, a1, a2, a3};
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+}
+
+// The 16-bit segment (text, generated tokens, video tail, 16-bit windows) of one (sequence, KV head): rows are
+// plain [token][Hkv][hd] so the K side feeds the matrix cores straight from global memory (one token row
+// quarter per lane); V rows go through LDS and are read back one channel x 8 tokens per lane.  bf16 caches use
+// the bf16 instruction with the exact bf16 query and the weights split into two bf16 terms (p = hi + lo);
+// fp16 caches use the f16 instruction.  Accumulators are in true units here (no 2^-24).
+template <int HD, bool BF>
+__device__ __forceinline__ void walk_seg16_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
+                                                float c_log2, WaveState<HD>& st)
+{
+    constexpr int NK = HD / 32, CT = HD / 16, PITCH = HD / 2 + VT_PAD, KDW = HD / 8;
+    if (blk_lo >= blk_hi) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = lane >> 4, col = lane & 15, h = col & 7;
+    const int len = kv.len16[b];
+    const int64_t row0 = kv.off16[b];
+    const int64_t rstride = (int64_t)kv.Hkv * HD;
+    const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16) + (int64_t)kvh * HD;
+    const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16) + (int64_t)kvh * HD;
+    U4 Bq[NK];
+#pragma unroll
+    for (int r = 0; r < NK; r++) Bq[r] = *reinterpret_cast<const U4*>(&sm.run.bq[3][r][lane][0]);
+    const float cexp = BF ? c_log2 : c_log2 * sm.qexp[h];
+    uint16_t* vt = &sm.run.vt[wave][0][0];
+
+    for (int blk = blk_lo; blk < blk_hi; blk++) {
+        const int nv = len - blk * 32;
+        // ---- all loads of the block up front: one memory round trip per block ----
+        uint32_t kd[2][KDW];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            const int tok = min(blk * 32 + 16 * t + col, len - 1);      // rows past the end re-read the last row, masked below
+            load_dwords<KDW>(reinterpret_cast<const uint32_t*>(k16 + (row0 + tok) * rstride + j * (HD / 4)), kd[t]);
+        }
+        constexpr int VIT = (32 * (HD / 2) * 2) / (16 * 64);          // 16-byte pieces per lane and channel half
+        uint4 vd[2][VIT];
+#pragma unroll
+        for (int half = 0; half < 2; half++)
+#pragma unroll
+            for (int it = 0; it < VIT; it++) {
+                const int chunk = it * 64 + lane;
+                const int row = chunk / (HD / 16), c16 = chunk % (HD / 16);
+                const int tok = min(blk * 32 + row, len - 1);
+                vd[half][it] = *reinterpret_cast<const uint4*>(v16 + (row0 + tok) * rstride + half * (HD / 2) + c16 * 8);
+            }
+        // ---- logits ----
+        float x[8];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < NK; r++) acc = mfma16<BF>(kd[t][4 * r], kd[t][4 * r + 1], kd[t][4 * r + 2], kd[t][4 * r + 3], Bq[r], acc);
+#pragma unroll
+            for (int i = 0; i < 4; i++) x[4 * t + i] = acc[i] + ror8(acc[i]);
+        }
+        if (nv < 32) {
+#pragma unroll
+            for (int t = 0; t < 2; t++)
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    if (16 * t + 4 * j + i >= nv) x[4 * t + i] = -INFINITY;
+        }
+        float lm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        lm *= cexp;
+        if (__builtin_amdgcn_ballot_w64(lm > st.m) != 0) {
+            lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
+            lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
+            const float mn = fmaxf(st.m, lm);
+            const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);
+            st.m = mn;
+            st.l *= alpha;
+            st.accM *= alpha;
+#pragma unroll
+            for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
+        }
+        float p[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            p[k] = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -st.m));
+            st.l += p[k];
+        }
+        // ---- weights as B operands: slots (2v, 2v+1) = (tile 0 token 4j+v, tile 1 token 4j+v) ----
+        U4 Ph, Pl;
+        {
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+                if constexpr (BF) {
+                    const uint32_t u0 = __float_as_uint(p[v]), u1 = __float_as_uint(p[4 + v]);
+                    const float r0 = p[v] - __uint_as_float(u0 & 0xFFFF0000u), r1 = p[4 + v] - __uint_as_float(u1 & 0xFFFF0000u);
+                    hi[v] = (u0 >> 16) | (u1 & 0xFFFF0000u);
+                    lo[v] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+                } else {
+                    const _Float16 h0 = (_Float16)p[v], h1 = (_Float16)p[4 + v];
+                    hi[v] = (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+                    lo[v] = 0;
+                }
+            }
+            Ph = U4{hi[0], hi[1], hi[2], hi[3]};
+            Pl = U4{lo[0], lo[1], lo[2], lo[3]};
+        }
+        // ---- V rows -> LDS -> one channel x 8 tokens per lane, half of the channels at a time ----
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+#pragma unroll
+            for (int it = 0; it < VIT; it++) {
+                const int chunk = it * 64 + lane;
+                const int row = chunk / (HD / 16), c16 = chunk % (HD / 16);
+                const uint4 v = vd[half][it];
+                uint2* dst = reinterpret_cast<uint2*>(vt + row * PITCH + c16 * 8);   // the padded pitch is only 8-byte aligned
+                dst[0] = uint2{v.x, v.y};
+                dst[1] = uint2{v.z, v.w};
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int c2 = 0; c2 < CT / 2; c2++) {
+                const int ct = half * (CT / 2) + c2;
+                uint32_t a[4];
+#pragma unroll
+                for (int v = 0; v < 4; v++) {
+                    const uint32_t e0 = vt[(4 * j + v) * PITCH + 16 * c2 + col];
+                    const uint32_t e1 = vt[(16 + 4 * j + v) * PITCH + 16 * c2 + col];
+                    a[v] = e0 | (e1 << 16);
+                }
+                st.O[ct] = mfma16<BF>(a[0], a[1], a[2], a[3], Ph, st.O[ct]);
+                if constexpr (BF) st.O[ct] = mfma16<BF>(a[0], a[1], a[2], a[3], Pl, st.O[ct]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();          // the buffer is overwritten next
+        }
+    }
+}
+
+// ceil((x - base) / w) clamped to [0, n]
+__device__ __forceinline__ int range_edge(int64_t x, int64_t base, int w, int n)
+{
+    if (x <= base) return 0;
+    const int64_t k = (x - base + w - 1) / w;
+    return k > n ? n : (int)k;
 }
 
 template <int HD>
@@ -312,7 +504,36 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
     constexpr int CT = HD / 16, NK = HD / 32, QC = HD / 4;
+    const bool bf16seg = a.kv.dtype16 == WQ_BF16;
+    WQ_STAMP(0);
 
+    // ---- this wavefront's cost-balanced share of the stream [16-bit | 2-bit | 4-bit | 8-bit] of (b, kvh) ----
+    int lo[4], hi[4];
+    {
+        // cost of one 32-token block of each class relative to the others, as measured on MI355X: the loop is
+        // bound by issue and latency per block more than by bytes, so the shares are balanced by block cost
+        const int wgt[4] = {108, 115, 137, 600};
+        int nb[4];
+#pragma unroll
+        for (int c = 0; c < 3; c++) nb[c] = (a.kv.cls_len[c][b] + 31) >> 5;
+        nb[3] = a.mfma16 ? (a.kv.len16[b] + 31) >> 5 : 0;
+        const int order[4] = {3, 0, 1, 2};
+        int64_t total = 0;
+#pragma unroll
+        for (int c = 0; c < 4; c++) total += (int64_t)nb[c] * wgt[c];
+        const int ns = a.splits * 4, s = split * 4 + wave;
+        const int64_t x0 = total * s / ns, x1 = total * (s + 1) / ns;
+        int64_t base = 0;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const int c = order[k];
+            lo[c] = range_edge(x0, base, wgt[c], nb[c]);
+            hi[c] = range_edge(x1, base, wgt[c], nb[c]);
+            base += (int64_t)nb[c] * wgt[c];
+        }
+    }
+
+    WQ_STAMP(1);
     // ---- query: per head, scale by a power of two so that max |q| lands in [0.5, 1); keep it as f16 ----
     for (int r = wave; r < WQ_MAX_REP; r += 4) {
         float v0 = 0.f, v1 = 0.f;
@@ -329,27 +550,76 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         const float dn = ok ? __uint_as_float((uint32_t)(253 - eb) << 23) : 1.0f;   // 2^-(eb-126)
         const float up = ok ? __uint_as_float((uint32_t)(eb + 1) << 23) : 1.0f;     // 2^(eb-126)
         sm.run.q[r][lane] = (_Float16)(v0 * dn);
-        if (HD == 128) sm.run.q[r][64 + lane] = (_Float16)(v1 * dn);
+        sm.run.qraw[r][lane] = (uint16_t)(__float_as_uint(v0) >> 16);
+        if (HD == 128) {
+            sm.run.q[r][64 + lane] = (_Float16)(v1 * dn);
+            sm.run.qraw[r][64 + lane] = (uint16_t)(__float_as_uint(v1) >> 16);
+        }
         if (lane == 0) sm.qexp[r] = up;
     }
     __syncthreads();
-    // ---- B operands of the logit product for all three classes, and the per-group sums of q' ----
-    for (int idx = tid; idx < 3 * NK * 512; idx += 256) {
-        const int e = idx & 7, ln = (idx >> 3) & 63, r = (idx >> 9) % NK, c = idx / (NK * 512);
-        const int lj = ln >> 4, lcol = ln & 15, lg = lcol >> 3, lh = lcol & 7;
-        int ch, sh;
-        k_slot(c, r, e, ch, sh);
-        float qv = 0.f;
-        if ((lj >> 1) == lg) qv = (float)sm.run.q[lh][lj * QC + ch] * __uint_as_float((uint32_t)(127 - sh) << 23);
-        sm.run.bq[c][r][ln][e] = (_Float16)qv;
+    WQ_STAMP(2);
+    // ---- B operands of the logit product for the three classes and the 16-bit segment; group sums of q' ----
+    // Wave r builds k-step r (the wave index is uniform, so the parity of r is a uniform branch); every slot of
+    // (class, r) draws on the same 16 consecutive channels of the lane's quarter: two 16-byte LDS reads.
+    if (wave < NK) {
+        const int r = wave, lj = lane >> 4, lg = (lane & 15) >> 3, lh = lane & 7;
+        const bool mine = (lj >> 1) == lg;
+        const int c0 = lj * QC + 16 * (r >> 1);
+        _Float16 hq[16];
+        uint16_t hr[16];
+        {
+            const U4 u0 = *reinterpret_cast<const U4*>(&sm.run.q[lh][c0]), u1 = *reinterpret_cast<const U4*>(&sm.run.q[lh][c0 + 8]);
+            const U4 w0 = *reinterpret_cast<const U4*>(&sm.run.qraw[lh][c0]), w1 = *reinterpret_cast<const U4*>(&sm.run.qraw[lh][c0 + 8]);
+            const uint32_t uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+            const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                hq[2 * k] = __builtin_bit_cast(_Float16, (uint16_t)(uu[k] & 0xFFFFu));
+                hq[2 * k + 1] = __builtin_bit_cast(_Float16, (uint16_t)(uu[k] >> 16));
+                hr[2 * k] = (uint16_t)(ww[k] & 0xFFFFu);
+                hr[2 * k + 1] = (uint16_t)(ww[k] >> 16);
+            }
+        }
+        auto build = [&](auto odd_tag) {
+            constexpr int ODD = decltype(odd_tag)::value;
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                uint16_t row[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    int ch, sh;
+                    k_slot(c, ODD, e, ch, sh);          // r = ODD has the same parity and r/2 == 0: ch is local to the 16 channels
+                    if (c == 3 && bf16seg) {
+                        row[e] = hr[ch];
+                    } else {
+                        const _Float16 qv = hq[ch] * (_Float16)__uint_as_float((uint32_t)(127 - sh) << 23);
+                        row[e] = __builtin_bit_cast(uint16_t, qv);
+                    }
+                    if (!mine) row[e] = 0;
+                }
+                U4 o{(uint32_t)row[0] | ((uint32_t)row[1] << 16), (uint32_t)row[2] | ((uint32_t)row[3] << 16),
+                     (uint32_t)row[4] | ((uint32_t)row[5] << 16), (uint32_t)row[6] | ((uint32_t)row[7] << 16)};
+                *reinterpret_cast<U4*>(&sm.run.bq[c][r][lane][0]) = o;
+            }
+        };
+        if (r & 1)
+            build(std::integral_constant<int, 1>{});
+        else
+            build(std::integral_constant<int, 0>{});
     }
-    if (tid < 2 * WQ_MAX_REP) {
-        const int hh = tid >> 1, gg = tid & 1;
+    {
+        // 16 sums (head, group) of HD/2 values: 16 lanes each
+        const int sidx = tid >> 4, part = tid & 15, hh = sidx >> 1, gg = sidx & 1;
         float s = 0.f;
-        for (int ch = 0; ch < HD / 2; ch++) s += (float)sm.run.q[hh][gg * (HD / 2) + ch];
-        sm.qsum[hh][gg] = s;
+#pragma unroll
+        for (int k = 0; k < HD / 32; k++) s += (float)sm.run.q[hh][gg * (HD / 2) + part + 16 * k];
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        if (part == 0) sm.qsum[hh][gg] = s;
     }
     __syncthreads();
+    WQ_STAMP(3);
 
     WaveState<HD> st;
 #pragma unroll
@@ -358,11 +628,24 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     st.l = 0.f;
     st.accM = 0.f;
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
-    const int share = split * 4 + wave, nshare = a.splits * 4;
-    walk_class_mfma<HD, 2, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
-    walk_class_mfma<HD, 4, 2>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
-    walk_class_mfma<HD, 8, 1>(a.kv, sm, b, kvh, share, nshare, c_log2, st);
+    WQ_WSTAMP(0, wall_clock64());
+    WQ_WSTAMP(5, ((long long)(hi[3] - lo[3]) << 48) | ((long long)(hi[0] - lo[0]) << 32) | ((long long)(hi[1] - lo[1]) << 16) | (long long)(hi[2] - lo[2]));
+    if (bf16seg)
+        walk_seg16_mfma<HD, true>(a.kv, sm, b, kvh, lo[3], hi[3], c_log2, st);
+    else
+        walk_seg16_mfma<HD, false>(a.kv, sm, b, kvh, lo[3], hi[3], c_log2, st);
+    // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
+#pragma unroll
+    for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
+    WQ_WSTAMP(1, wall_clock64());
+    walk_class_mfma<HD, 2, 2>(a.kv, sm, b, kvh, lo[0], hi[0], c_log2, st);
+    WQ_WSTAMP(2, wall_clock64());
+    walk_class_mfma<HD, 4, 2>(a.kv, sm, b, kvh, lo[1], hi[1], c_log2, st);
+    WQ_WSTAMP(3, wall_clock64());
+    walk_class_mfma<HD, 8, 1>(a.kv, sm, b, kvh, lo[2], hi[2], c_log2, st);
+    WQ_WSTAMP(4, wall_clock64());
 
+    WQ_STAMP(4);
     // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
     float l = st.l, am = st.accM;
     l += __shfl_xor(l, 16, 64);
@@ -383,7 +666,11 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     __syncthreads();
     // ---- merge the four waves, write the partial (m in natural-log units) ----
-    float* out = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts + split) * a.rep * (HD + 2);
+    // Partials are written and read with device-scope accesses that go through to memory (every XCD has its own
+    // L2), so that no cache write-back is needed to hand them to the workgroup that merges the splits.
+    const int64_t pstride = (int64_t)a.rep * (HD + 2);
+    float* pbase = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts) * pstride;
+    float* out = pbase + split * pstride;
     for (int idx = tid; idx < a.rep * HD; idx += 256) {
         const int r = idx / HD, ch = idx - r * HD;
         const float M = fmaxf(fmaxf(sm.ml[0][r][0], sm.ml[1][r][0]), fmaxf(sm.ml[2][r][0], sm.ml[3][r][0]));
@@ -395,11 +682,70 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             num = fmaf(sm.O[w][r][ch], s, num);
             L = fmaf(sm.ml[w][r][1], s, L);
         }
-        out[r * (HD + 2) + ch] = num;
+        __hip_atomic_store(out + r * (HD + 2) + ch, num, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ch == 0) {
-            out[r * (HD + 2) + HD] = M * 0.6931471805599453f;
-            out[r * (HD + 2) + HD + 1] = L;
+            __hip_atomic_store(out + r * (HD + 2) + HD, M * 0.6931471805599453f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(out + r * (HD + 2) + HD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+    WQ_STAMP(5);
+    if (!a.fused) return;
+
+    // ---- the last workgroup of (b, kvh) to arrive merges all splits in split order ----
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // this lane's stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned old = __hip_atomic_fetch_add(a.tickets + b * a.kv.Hkv + kvh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.last = (old == (unsigned)a.nparts - 1u);
+    }
+    __syncthreads();
+    if (!sm.last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");    // drop stale lines: the partials below come from memory
+    if (tid == 0) __hip_atomic_store(a.tickets + b * a.kv.Hkv + kvh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    float* wts = &sm.O[0][0][0];                   // [rep][nparts] m_s, then the weights e^{m_s - M}
+    float* lsum = wts + a.rep * a.nparts;          // [rep][nparts] l_s
+    for (int idx = tid; idx < a.rep * a.nparts; idx += 256) {
+        const int r = idx / a.nparts, s = idx - r * a.nparts;
+        const float* src = pbase + s * pstride + r * (HD + 2) + HD;
+        wts[idx] = src[0];
+        lsum[idx] = src[1];
+    }
+    __syncthreads();
+    if (tid < a.rep) {                             // per head: max, then weights, then the denominator (split order)
+        float M = -INFINITY;
+        for (int s = 0; s < a.nparts; s++) M = fmaxf(M, wts[tid * a.nparts + s]);
+        float L = 0.f;
+        for (int s = 0; s < a.nparts; s++) {
+            const float ms = wts[tid * a.nparts + s];
+            const float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
+            wts[tid * a.nparts + s] = w;
+            L = fmaf(lsum[tid * a.nparts + s], w, L);
+        }
+        sm.ml[0][tid][0] = M;
+        sm.ml[0][tid][1] = L;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < a.rep * HD; idx += 256) {
+        const int r = idx / HD, ch = idx - r * HD;
+        const float* src = pbase + r * (HD + 2) + ch;
+        float acc = 0.f;
+        int s = 0;
+        for (; s + 4 <= a.nparts; s += 4) {
+            const float a0 = *(src + (s + 0) * pstride);
+            const float a1 = *(src + (s + 1) * pstride);
+            const float a2 = *(src + (s + 2) * pstride);
+            const float a3 = *(src + (s + 3) * pstride);
+            acc = fmaf(a0, wts[r * a.nparts + s], acc);
+            acc = fmaf(a1, wts[r * a.nparts + s + 1], acc);
+            acc = fmaf(a2, wts[r * a.nparts + s + 2], acc);
+            acc = fmaf(a3, wts[r * a.nparts + s + 3], acc);
+        }
+        for (; s < a.nparts; s++)
+            acc = fmaf(*(src + s * pstride), wts[r * a.nparts + s], acc);
+        const float L = sm.ml[0][r][1];
+        const int hq = kvh * a.rep + r;
+        a.out[((int64_t)b * a.Hq + hq) * HD + ch] = L > 0.f ? acc / L : 0.f;
+        if (a.lse && ch == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? sm.ml[0][r][0] + logf(L) : -INFINITY;
     }
 }
 

@@ -17,7 +17,8 @@ struct wq_ctx {
     char err[256];
 };
 
-constexpr size_t WQ_WS_HEADER = 256;   // status word lives in the first bytes of the workspace
+constexpr size_t WQ_WS_HEADER = 16384; // zero-initialised: status word (first 256 bytes), then arrival tickets
+constexpr int WQ_MAX_TICKETS = (16384 - 256) / 4;
 constexpr int WQ_MAX_REP = 8;          // query heads per KV head
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 
