@@ -25,13 +25,13 @@ int check_packed(wq_ctx* ctx, const wq_packed_kv* kv, int B, bool need_tables)
     for (int c = 0; c < 3; c++) {
         if (kv->cap[c] < 0 || kv->cap[c] % 32 != 0)
             return wq_fail(ctx, WQ_ERR_ARG, "cap[%d]=%lld is not a non-negative multiple of 32", c, (long long)kv->cap[c]);
-        if (kv->cap[c] > (int64_t)1 << 30) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "cap[%d] too large", c);
+        if (kv->cap[c] > (int64_t)1 << 26) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "cap[%d] above 2^26 tokens", c);
         if (kv->cap[c] > 0 && (!kv->codes[c] || !kv->meta[c]))
             return wq_fail(ctx, WQ_ERR_ARG, "class %d has capacity but NULL codes/meta", c);
         if (need_tables && (!kv->cls_off[c] || !kv->cls_len[c]))
             return wq_fail(ctx, WQ_ERR_ARG, "class %d offset/length tables are NULL", c);
     }
-    if (kv->cap16 < 0 || kv->cap16 > (int64_t)1 << 30) return wq_fail(ctx, WQ_ERR_ARG, "bad cap16");
+    if (kv->cap16 < 0 || kv->cap16 > (int64_t)1 << 26) return wq_fail(ctx, WQ_ERR_ARG, "bad cap16");
     if (kv->cap16 > 0 && (!kv->k16 || !kv->v16)) return wq_fail(ctx, WQ_ERR_ARG, "16-bit segment has capacity but NULL k16/v16");
     if (!kv->off16 || !kv->len16) return wq_fail(ctx, WQ_ERR_ARG, "off16/len16 tables are NULL");
     return WQ_OK;
@@ -121,9 +121,10 @@ size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group,
 int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens)
 {
     if (B <= 0 || Hkv <= 0) return 1;
-    // aim at ~4 workgroups per compute unit (256 CUs), but keep at least 256 tokens per split
-    int64_t want = (1024 + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
-    int64_t most = max_seq_tokens > 0 ? (max_seq_tokens + 255) / 256 : 1;
+    // two resident workgroups per compute unit (256 CUs) is what the decode kernel's registers and LDS allow;
+    // more splits only add per-workgroup set-up.  Keep at least 1024 tokens per workgroup (256 per wavefront).
+    int64_t want = (512 + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
+    int64_t most = max_seq_tokens > 0 ? (max_seq_tokens + 1023) / 1024 : 1;
     if (want > most) want = most;
     if (want < 1) want = 1;
     if (want > 256) want = 256;

@@ -163,6 +163,7 @@ struct MfmaSmem {
     float qexp[WQ_MAX_REP];                   // the heads' powers of two
     float qsum[WQ_MAX_REP][2];                // sum of the scaled query over each group
     float ml[4][WQ_MAX_REP][2];
+    uint32_t warm[256];
     int last;
 };
 
@@ -488,12 +489,49 @@ __device__ __forceinline__ void walk_seg16_mfma(const wq_packed_kv& kv, MfmaSmem
     }
 }
 
+// Start fetching the first blocks of a class range towards this XCD's L2 while the prologue runs: one dword per
+// 128-byte line.  Branch-free, so that the loads go out back to back and nothing waits for them: offsets are
+// clamped into the range (extra lanes re-touch its last line) and an empty range touches `dummy` instead.  The
+// values are folded together and stored to LDS after the prologue, which is where the wait for them lands.
+constexpr int WQ_WARM_BLOCKS = 4;   // blocks per class range requested ahead of the prologue (about what the L2s hold)
+
+template <int HD, int BITS>
+__device__ __forceinline__ uint32_t warm_class(const wq_packed_kv& kv, int b, int kvh, int blk_lo, int blk_hi, int lane, const void* dummy)
+{
+    constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
+    constexpr int BLKB = 32 * HD * BITS / 8;
+    constexpr int NIT = (WQ_WARM_BLOCKS * BLKB + 8191) / 8192;
+    const int n = min(blk_hi - blk_lo, WQ_WARM_BLOCKS);
+    const bool any = n > 0;
+    const int64_t cap = kv.cap[C];
+    const int64_t tok = any ? kv.cls_off[C][b] + (int64_t)blk_lo * 32 : 0;
+    const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok) * HD * BITS / 8;
+    const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok) * HD * BITS / 8;
+    const uint8_t* kmeta = static_cast<const uint8_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok) * 8;
+    const uint8_t* vmeta = static_cast<const uint8_t*>(kv.meta[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok) * 8;
+    const uint8_t* dm = static_cast<const uint8_t*>(dummy);
+    uint32_t v[2 * NIT + 2];
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+        const int off = min(it * 8192 + lane * 128, n * BLKB - 128);      // n >= 1 whenever the address is used
+        v[2 * it] = *reinterpret_cast<const uint32_t*>(any ? kbase + off : dm);
+        v[2 * it + 1] = *reinterpret_cast<const uint32_t*>(any ? vbase + off : dm);
+    }
+    const int moff = min(lane * 128, n * 256 - 128);
+    v[2 * NIT] = *reinterpret_cast<const uint32_t*>(any ? kmeta + moff : dm);
+    v[2 * NIT + 1] = *reinterpret_cast<const uint32_t*>(any ? vmeta + moff : dm);
+    uint32_t x = 0;
+#pragma unroll
+    for (int k = 0; k < 2 * NIT + 2; k++) x ^= v[k];
+    return x;
+}
+
 // ceil((x - base) / w) clamped to [0, n]
-__device__ __forceinline__ int range_edge(int64_t x, int64_t base, int w, int n)
+__device__ __forceinline__ int range_edge(uint32_t x, uint32_t base, uint32_t w, int n)
 {
     if (x <= base) return 0;
-    const int64_t k = (x - base + w - 1) / w;
-    return k > n ? n : (int)k;
+    const uint32_t k = (x - base + w - 1) / w;
+    return k > (uint32_t)n ? n : (int)k;
 }
 
 template <int HD>
@@ -501,47 +539,76 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 {
     MfmaSmem<HD>& sm = *reinterpret_cast<MfmaSmem<HD>*>(smem_raw);
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
     constexpr int CT = HD / 16, NK = HD / 32, QC = HD / 4;
     const bool bf16seg = a.kv.dtype16 == WQ_BF16;
     WQ_STAMP(0);
+
+    // ---- the query loads go out first (heads wave and wave+4 of this KV head) ----
+    // (raw bits first, one uniform branch on the element type, so that all four loads are in flight together)
+    uint32_t qraw[2][2];
+    const bool qh0 = wave < a.rep, qh1 = wave + 4 < a.rep;      // heads past rep re-read head 0 and are zeroed later
+    {
+        const int64_t hb = ((int64_t)b * a.Hq + kvh * a.rep) * HD + lane;
+        const int64_t b0 = hb + (qh0 ? wave : 0) * HD, b1 = hb + (qh1 ? wave + 4 : 0) * HD;
+        if (a.q_dtype == WQ_F32) {
+            const uint32_t* p = static_cast<const uint32_t*>(a.q);
+            qraw[0][0] = p[b0], qraw[1][0] = p[b1];
+            qraw[0][1] = HD == 128 ? p[b0 + 64] : 0u, qraw[1][1] = HD == 128 ? p[b1 + 64] : 0u;
+        } else {
+            const uint16_t* p = static_cast<const uint16_t*>(a.q);
+            qraw[0][0] = p[b0], qraw[1][0] = p[b1];
+            qraw[0][1] = HD == 128 ? p[b0 + 64] : 0u, qraw[1][1] = HD == 128 ? p[b1 + 64] : 0u;
+        }
+    }
 
     // ---- this wavefront's cost-balanced share of the stream [16-bit | 2-bit | 4-bit | 8-bit] of (b, kvh) ----
     int lo[4], hi[4];
     {
         // cost of one 32-token block of each class relative to the others, as measured on MI355X: the loop is
         // bound by issue and latency per block more than by bytes, so the shares are balanced by block cost
-        const int wgt[4] = {108, 115, 137, 600};
+        const int wgt[4] = {113, 118, 158, 372};
         int nb[4];
 #pragma unroll
         for (int c = 0; c < 3; c++) nb[c] = (a.kv.cls_len[c][b] + 31) >> 5;
         nb[3] = a.mfma16 ? (a.kv.len16[b] + 31) >> 5 : 0;
         const int order[4] = {3, 0, 1, 2};
-        int64_t total = 0;
+        // 32-bit arithmetic: class capacities are limited to 2^26 tokens, so the total stays below 2^32
+        uint32_t total = 0;
 #pragma unroll
-        for (int c = 0; c < 4; c++) total += (int64_t)nb[c] * wgt[c];
-        const int ns = a.splits * 4, s = split * 4 + wave;
-        const int64_t x0 = total * s / ns, x1 = total * (s + 1) / ns;
-        int64_t base = 0;
+        for (int c = 0; c < 4; c++) total += (uint32_t)nb[c] * (uint32_t)wgt[c];
+        const uint32_t ns = (uint32_t)a.splits * 4u, s = (uint32_t)split * 4u + (uint32_t)wave;
+        const uint32_t qd = total / ns, rm = total - qd * ns;          // total*s/ns without a wide product
+        const uint32_t x0 = qd * s + rm * s / ns, x1 = qd * (s + 1) + rm * (s + 1) / ns;
+        uint32_t base = 0;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const int c = order[k];
-            lo[c] = range_edge(x0, base, wgt[c], nb[c]);
-            hi[c] = range_edge(x1, base, wgt[c], nb[c]);
-            base += (int64_t)nb[c] * wgt[c];
+            lo[c] = range_edge(x0, base, (uint32_t)wgt[c], nb[c]);
+            hi[c] = range_edge(x1, base, (uint32_t)wgt[c], nb[c]);
+            base += (uint32_t)nb[c] * (uint32_t)wgt[c];
         }
     }
 
+    // ---- and the first blocks of every class this wavefront will walk start moving towards L2 ----
+    const uint32_t sink = warm_class<HD, 2>(a.kv, b, kvh, lo[0], hi[0], lane, a.q) ^ warm_class<HD, 4>(a.kv, b, kvh, lo[1], hi[1], lane, a.q) ^
+                          warm_class<HD, 8>(a.kv, b, kvh, lo[2], hi[2], lane, a.q);
+
     WQ_STAMP(1);
     // ---- query: per head, scale by a power of two so that max |q| lands in [0.5, 1); keep it as f16 ----
-    for (int r = wave; r < WQ_MAX_REP; r += 4) {
-        float v0 = 0.f, v1 = 0.f;
-        if (r < a.rep) {
-            const int64_t base = ((int64_t)b * a.Hq + kvh * a.rep + r) * HD;
-            v0 = load_q(a.q, a.q_dtype, base + lane);
-            if (HD == 128) v1 = load_q(a.q, a.q_dtype, base + 64 + lane);
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+        const int r = wave + 4 * k;
+        float v0, v1;
+        if (a.q_dtype == WQ_F32) {
+            v0 = __uint_as_float(qraw[k][0]), v1 = __uint_as_float(qraw[k][1]);
+        } else if (a.q_dtype == WQ_BF16) {
+            v0 = wq_bf16_bits_to_float(qraw[k][0]), v1 = wq_bf16_bits_to_float(qraw[k][1]);
+        } else {
+            v0 = wq_f16_bits_to_float(qraw[k][0]), v1 = wq_f16_bits_to_float(qraw[k][1]);
         }
+        if (!(k == 0 ? qh0 : qh1)) v0 = v1 = 0.f;
         float mx = fmaxf(fabsf(v0), fabsf(v1));
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
@@ -558,6 +625,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         if (lane == 0) sm.qexp[r] = up;
     }
     __syncthreads();
+    *reinterpret_cast<volatile uint32_t*>(&sm.warm[tid]) = sink;   // nobody reads it: it only anchors the warm-up loads
     WQ_STAMP(2);
     // ---- B operands of the logit product for the three classes and the 16-bit segment; group sums of q' ----
     // Wave r builds k-step r (the wave index is uniform, so the parity of r is a uniform branch); every slot of
