@@ -35,6 +35,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic():
+    """HBM bytes per launch of the decode kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the same counter reads for the plain copy probe), or None."""
+    path = os.path.join(ROOT, "profiles", "decode_attention_cfg3_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,7 +56,6 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload id (3 = long-video 7B-shaped layer)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--decode-only", action="store_true", help="skip scoring/quantization inside the timed steps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -119,79 +131,79 @@ def main():
     assert ctx.device_status() == 0
     alg_bytes = copies[0].bytes_algorithmic()
 
-    def step(i, ev=None):
+    def step(i):
         pk_w, pk_r = copies[i % N_COPIES], copies[(i + 1) % N_COPIES]
-        if ev: ev[0].record()
-        if not args.decode_only:
-            W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
-        if ev: ev[1].record()
-        if not args.decode_only:
-            bits_, perm_, seg_ = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
-        if ev: ev[2].record()
-        if not args.decode_only:
-            W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm_, seg_, total_rows, pk_w)
-        if ev: ev[3].record()
+        W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
+        bits_, perm_, seg_ = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
+        W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm_, seg_, total_rows, pk_w)
         W.wq_decode_attention(ctx, q, pk_r, sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)
-        if ev: ev[4].record()
 
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n):
+        """mean microseconds of fn(i) over n back-to-back calls: one HIP event before the first, one after the last"""
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    # ---- the timed region: K passes of the whole hot path --------------------------------------------------
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     t_start = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, events[i])
-    torch.cuda.synchronize()
+    step_us = timed(lambda i: step(args.warmup + i), args.steps)
     wall = time.perf_counter() - t_start
-    stage = np.array([[e[k].elapsed_time(e[k + 1]) * 1e3 for k in range(4)] for e in events])   # us
-    st_mean = stage.mean(axis=0)
-    dec_us = float(st_mean[3])
-    gbs = alg_bytes / (dec_us * 1e-6) / 1e9
 
-    # ---- decode alone, back to back over the rotating copies (launch gaps included) -------------------------
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 25 * N_COPIES
+    # ---- its stages, each over the same number of back-to-back calls (a pair of events per call would add
+    #      several microseconds of marker overhead to a 30 us kernel) ---------------------------------------
+    n = max(args.steps, 2 * N_COPIES)
+    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, nsplit, max_tok, algo, out=out, lse=lse))
     for i in range(N_COPIES):
-        W.wq_decode_attention(ctx, q, copies[i], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out)
-    e0.record()
-    for i in range(reps):
-        W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out)
-    e1.record()
-    torch.cuda.synchronize()
-    b2b_us = e0.elapsed_time(e1) * 1e3 / reps
+        dec(W.DECODE_AUTO)(i)
+    dec_us = timed(dec(W.DECODE_AUTO), n)                                     # streaming kernel + split merge
+    kern_mean_us = timed(dec(W.DECODE_AUTO | W.DECODE_PARTIALS_ONLY), n)     # the streaming kernel alone
+    sc_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
+                                               total_win, scores=scores), n)
+    as_us = timed(lambda i: W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first), n)
+    rq_us = timed(lambda i: W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, copies[i % N_COPIES]), n)
+    st_mean = [sc_us, as_us, rq_us, dec_us]
+    gbs = alg_bytes / (dec_us * 1e-6) / 1e9
+    kern_gbs = alg_bytes / (kern_mean_us * 1e-6) / 1e9
+    b2b_us = dec_us
 
     # ---- achievable stream-read rate of this GPU (plain 16-byte loads over 2 GiB) ------------------------------
     big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
     big.zero_()
     W.wq_probe_stream(ctx, big)
+    read_gbs = big.numel() / (timed(lambda i: W.wq_probe_stream(ctx, big), 5) * 1e-6) / 1e9
+    half = big.numel() // 2
+    W.wq_probe_stream(ctx, big[:half], big[half:])      # plain copy of 1 GiB: the reference for byte counters
     torch.cuda.synchronize()
-    e0.record()
-    for _ in range(5):
-        W.wq_probe_stream(ctx, big)
-    e1.record()
-    torch.cuda.synchronize()
-    read_gbs = 5 * big.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del big
 
     res = {
         "metric": "mixed-precision KV decode-attention GB/s (% HBM peak) + us/step at 50K ctx",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(step_us * 1e-3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 cache in, 2/4/8-bit codes, f16 MFMA, fp32 accumulate",
         "data": "synthetic (seeded, LLaVA-OneVision-shaped; stands in for the paper's video workloads)",
         "config": {"workload": w.name, "B": B, "Hq": w.Hq, "Hkv": w.Hkv, "head_dim": w.hd, "group": w.group,
                    "visual_tokens_per_seq": w.seqs[0].n_vis, "text_tokens_per_seq": w.seqs[0].n_text,
                    "window": w.seqs[0].win_size, "bit_mix_windows_8_4_2": list(map(int, w.seqs[0].quota)),
-                   "splits": nsplit, "kv_copies_rotated": N_COPIES, "decode_only_steps": bool(args.decode_only)},
+                   "splits": nsplit, "kv_copies_rotated": N_COPIES, "calls_per_stage_timing": n},
         "decode_us_per_step": round(dec_us, 2),
         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
         "stage_us": {"window_scores": round(float(st_mean[0]), 1), "assign_bits": round(float(st_mean[1]), 1),
                      "reorder_quantize": round(float(st_mean[2]), 1), "decode_attention": round(dec_us, 2)},
-        "decode_back_to_back_us": round(b2b_us, 2),
         "stream_read_GBs": round(read_gbs, 0),
-        "roofline": {"kernel": "k_decode<128> (+ split combine)", "bound": "hbm", "achieved": round(gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "algorithmic_bytes_per_launch": alg_bytes},
+        "roofline": {"kernel": "k_decode_mfma<128>", "bound": "hbm", "achieved": round(kern_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kern_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic() if args.config == 3 else None, "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel_us": round(kern_mean_us, 2)},
         "roofline_other": {
             "reorder_quantize": {"bound": "hbm", "unit": "GB/s",
                                  "achieved": round((total_rows * w.Hkv * w.hd * 2 * 2 + alg_bytes) / (st_mean[2] * 1e-6) / 1e9, 1)
@@ -210,15 +222,20 @@ def main():
         rows0 = int(t.kv_off[1])
         pk0 = O.reorder_quantize(k0_host, v0_host, [0, rows0], [s0.win_size], [0, nw], perm_h, seg_h, w.group)
         tc = time.perf_counter()
-        ref = O.decode_attention(q_host[:1], pk0, sm_scale)
-        dt = time.perf_counter() - tc
+        reps = 0
+        while True:                         # about 10 s of CPU work on the sample
+            ref = O.decode_attention(q_host[:1], pk0, sm_scale)
+            reps += 1
+            if time.perf_counter() - tc >= 10.0:
+                break
+        dt = (time.perf_counter() - tc) / reps
         bytes0 = alg_bytes / B
         W.wq_decode_attention(ctx, q, copies[0], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out)
         torch.cuda.synchronize()
         got = out[0].cpu().numpy().astype(np.float64)
         err = float((np.abs(got - ref[0]).max(axis=-1) / np.abs(ref[0]).max(axis=-1)).max())
         res["cpu_baseline"] = {"value": round(bytes0 / dt / 1e9, 4), "unit": "GB/s", "cores": O.num_threads(),
-                               "kind": "oracle", "seconds": round(dt, 2),
+                               "kind": "oracle", "seconds_per_pass": round(dt, 3), "passes": reps,
                                "sample": f"decode attention of sequence 0 of {B} (all {w.Hq} heads, {rows0} tokens), fp64"}
         res["parity_max_rel_err_seq0"] = err
     print(json.dumps(res), flush=True)

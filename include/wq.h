@@ -74,6 +74,9 @@ typedef enum { WQ_OK = 0, WQ_ERR_ARG = -1, WQ_ERR_UNSUPPORTED = -2, WQ_ERR_HIP =
 typedef enum { WQ_SCORE_AUTO = 0, WQ_SCORE_PAIRWISE_MFMA = 1, WQ_SCORE_POOLED = 2 } wq_score_algo;
 typedef enum { WQ_MODE_QUOTA = 0, WQ_MODE_THRESHOLD = 1 } wq_assign_mode;
 typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } wq_decode_algo;
+/* or-ed into algo: run only the kernel that streams the cache and leave its per-split partials in the workspace
+ * (out and lse are not written).  A measurement aid: it lets that kernel be timed without the merge kernel.   */
+#define WQ_DECODE_PARTIALS_ONLY 0x100
 
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
@@ -169,6 +172,15 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * matrix-core kernel when hd/group == 2, else the generic one.                                               */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
+
+/* ---- timing of the dominant kernel (measurement aid) ---------------------------------------------------------
+ * With timing enabled every wq_decode_attention records a HIP event right before and right after its main
+ * kernel (the one that streams the cache) on the context's stream, in a ring of 64 event pairs created once by
+ * wq_decode_timing(ctx, 1); the decode call itself still allocates nothing and does not synchronise.
+ * wq_decode_times_us waits for the last timed call and returns the durations of the last n (<= 64) timed calls,
+ * oldest first, in microseconds.  Enabling or disabling restarts the count.                                   */
+int wq_decode_timing(wq_ctx* ctx, int enable);
+int wq_decode_times_us(wq_ctx* ctx, float* us, int n);
 
 /* ---- measurement probe (not part of the method; for callers that cannot time a plain kernel themselves) ----
  * Streams `bytes` (multiple of 16) of device memory with 16-byte loads from `blocks` workgroups of 256 lanes:

@@ -16,6 +16,7 @@ F32, BF16, F16 = 0, 1, 2
 SCORE_AUTO, SCORE_PAIRWISE_MFMA, SCORE_POOLED = 0, 1, 2
 MODE_QUOTA, MODE_THRESHOLD = 0, 1
 DECODE_AUTO, DECODE_GENERIC, DECODE_MFMA = 0, 1, 2
+DECODE_PARTIALS_ONLY = 0x100
 CLASS_BITS = (2, 4, 8)
 DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW = 1, 2
 
@@ -61,6 +62,8 @@ def lib() -> C.CDLL:
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
+        L.wq_decode_timing.argtypes = [vp, i32]
+        L.wq_decode_times_us.argtypes = [vp, C.POINTER(C.c_float), i32]
         _lib = L
     return _lib
 
@@ -107,6 +110,14 @@ class Context:
     def check(self, rc: int):
         if rc != 0:
             raise WQError(rc, lib().wq_last_error(self.handle).decode())
+
+    def decode_timing(self, enable: bool = True):
+        self.check(lib().wq_decode_timing(self.handle, 1 if enable else 0))
+
+    def decode_times_us(self, n: int):
+        buf = (C.c_float * n)()
+        self.check(lib().wq_decode_times_us(self.handle, buf, n))
+        return [float(x) for x in buf]
 
     def device_status(self) -> int:
         bits = C.c_uint32(0)

@@ -51,6 +51,9 @@ int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_
     ctx->ws = static_cast<char*>(workspace);
     ctx->ws_bytes = workspace_bytes;
     ctx->owns_ws = false;
+    ctx->timing = false;
+    for (int i = 0; i < 2 * WQ_TIMING_RING; i++) ctx->ev[i] = nullptr;
+    ctx->ev_calls = 0;
     ctx->err[0] = 0;
     if (!workspace && workspace_bytes > 0) {
         void* p = nullptr;
@@ -76,6 +79,8 @@ int wq_destroy(wq_ctx* ctx)
 {
     if (!ctx) return WQ_OK;
     if (ctx->owns_ws && ctx->ws) (void)hipFree(ctx->ws);
+    for (int i = 0; i < 2 * WQ_TIMING_RING; i++)
+        if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     delete ctx;
     return WQ_OK;
 }
@@ -84,6 +89,32 @@ int wq_set_stream(wq_ctx* ctx, void* hip_stream)
 {
     if (!ctx) return WQ_ERR_ARG;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
+    return WQ_OK;
+}
+
+int wq_decode_timing(wq_ctx* ctx, int enable)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (enable && !ctx->ev[0])
+        for (int i = 0; i < 2 * WQ_TIMING_RING; i++) WQ_HIP_CHECK(ctx, hipEventCreate(&ctx->ev[i]));
+    ctx->timing = enable != 0;
+    ctx->ev_calls = 0;
+    return WQ_OK;
+}
+
+int wq_decode_times_us(wq_ctx* ctx, float* us, int n)
+{
+    if (!ctx || !us || n < 0 || !ctx->ev[0]) return WQ_ERR_ARG;
+    if ((uint64_t)n > ctx->ev_calls || n > WQ_TIMING_RING) return wq_fail(ctx, WQ_ERR_ARG, "only %llu timed calls, ring of %d",
+                                                                          (unsigned long long)ctx->ev_calls, WQ_TIMING_RING);
+    for (int k = 0; k < n; k++) {                    // oldest of the last n first
+        const uint64_t call = ctx->ev_calls - (uint64_t)n + (uint64_t)k;
+        const int slot = (int)(call % WQ_TIMING_RING);
+        float ms = 0.f;
+        WQ_HIP_CHECK(ctx, hipEventSynchronize(ctx->ev[2 * slot + 1]));
+        WQ_HIP_CHECK(ctx, hipEventElapsedTime(&ms, ctx->ev[2 * slot], ctx->ev[2 * slot + 1]));
+        us[k] = ms * 1000.0f;
+    }
     return WQ_OK;
 }
 
@@ -205,9 +236,10 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
                        Hq, kv->Hkv, WQ_MAX_REP);
-    if (algo != WQ_DECODE_AUTO && algo != WQ_DECODE_GENERIC && algo != WQ_DECODE_MFMA)
+    const int balgo = algo & ~WQ_DECODE_PARTIALS_ONLY;
+    if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
         return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
-    if (algo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
+    if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
     if (num_splits < 0 || num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
     if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");

@@ -368,6 +368,8 @@ size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
                      int num_splits, int algo, float* out, float* lse)
 {
+    const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
+    algo &= ~WQ_DECODE_PARTIALS_ONLY;
     DecodeArgs a;
     a.q = q;
     a.q_dtype = q_dtype;
@@ -393,23 +395,30 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.lse = lse;
     const dim3 blk(256);
     const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16 > 0 ? a.splits16 : 1, kv->Hkv, B);
+    const int tslot = (int)(ctx->ev_calls % WQ_TIMING_RING);
+    if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot], ctx->stream);
     if (kv->hd == 128) {
         if (a.use_mfma) {
             hipLaunchKernelGGL(k_decode_mfma<128>, grid_q, blk, 0, ctx->stream, a);
+            if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
             if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<128>, grid_16, blk, 0, ctx->stream, a);
         } else {
             hipLaunchKernelGGL(k_decode_generic<128>, grid_q, blk, 0, ctx->stream, a);
+            if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
         }
     } else {
         if (a.use_mfma) {
             hipLaunchKernelGGL(k_decode_mfma<64>, grid_q, blk, 0, ctx->stream, a);
+            if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
             if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<64>, grid_16, blk, 0, ctx->stream, a);
         } else {
             hipLaunchKernelGGL(k_decode_generic<64>, grid_q, blk, 0, ctx->stream, a);
+            if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
         }
     }
-    if (!a.fused)
+    if (!a.fused && !partials_only)
         hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
+    if (ctx->timing) ctx->ev_calls++;
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

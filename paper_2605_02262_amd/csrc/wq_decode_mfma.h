@@ -163,7 +163,6 @@ struct MfmaSmem {
     float qexp[WQ_MAX_REP];                   // the heads' powers of two
     float qsum[WQ_MAX_REP][2];                // sum of the scaled query over each group
     float ml[4][WQ_MAX_REP][2];
-    uint32_t warm[256];
     int last;
 };
 
@@ -489,43 +488,6 @@ __device__ __forceinline__ void walk_seg16_mfma(const wq_packed_kv& kv, MfmaSmem
     }
 }
 
-// Start fetching the first blocks of a class range towards this XCD's L2 while the prologue runs: one dword per
-// 128-byte line.  Branch-free, so that the loads go out back to back and nothing waits for them: offsets are
-// clamped into the range (extra lanes re-touch its last line) and an empty range touches `dummy` instead.  The
-// values are folded together and stored to LDS after the prologue, which is where the wait for them lands.
-constexpr int WQ_WARM_BLOCKS = 4;   // blocks per class range requested ahead of the prologue (about what the L2s hold)
-
-template <int HD, int BITS>
-__device__ __forceinline__ uint32_t warm_class(const wq_packed_kv& kv, int b, int kvh, int blk_lo, int blk_hi, int lane, const void* dummy)
-{
-    constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
-    constexpr int BLKB = 32 * HD * BITS / 8;
-    constexpr int NIT = (WQ_WARM_BLOCKS * BLKB + 8191) / 8192;
-    const int n = min(blk_hi - blk_lo, WQ_WARM_BLOCKS);
-    const bool any = n > 0;
-    const int64_t cap = kv.cap[C];
-    const int64_t tok = any ? kv.cls_off[C][b] + (int64_t)blk_lo * 32 : 0;
-    const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok) * HD * BITS / 8;
-    const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok) * HD * BITS / 8;
-    const uint8_t* kmeta = static_cast<const uint8_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok) * 8;
-    const uint8_t* vmeta = static_cast<const uint8_t*>(kv.meta[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok) * 8;
-    const uint8_t* dm = static_cast<const uint8_t*>(dummy);
-    uint32_t v[2 * NIT + 2];
-#pragma unroll
-    for (int it = 0; it < NIT; it++) {
-        const int off = min(it * 8192 + lane * 128, n * BLKB - 128);      // n >= 1 whenever the address is used
-        v[2 * it] = *reinterpret_cast<const uint32_t*>(any ? kbase + off : dm);
-        v[2 * it + 1] = *reinterpret_cast<const uint32_t*>(any ? vbase + off : dm);
-    }
-    const int moff = min(lane * 128, n * 256 - 128);
-    v[2 * NIT] = *reinterpret_cast<const uint32_t*>(any ? kmeta + moff : dm);
-    v[2 * NIT + 1] = *reinterpret_cast<const uint32_t*>(any ? vmeta + moff : dm);
-    uint32_t x = 0;
-#pragma unroll
-    for (int k = 0; k < 2 * NIT + 2; k++) x ^= v[k];
-    return x;
-}
-
 // ceil((x - base) / w) clamped to [0, n]
 __device__ __forceinline__ int range_edge(uint32_t x, uint32_t base, uint32_t w, int n)
 {
@@ -591,10 +553,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         }
     }
 
-    // ---- and the first blocks of every class this wavefront will walk start moving towards L2 ----
-    const uint32_t sink = warm_class<HD, 2>(a.kv, b, kvh, lo[0], hi[0], lane, a.q) ^ warm_class<HD, 4>(a.kv, b, kvh, lo[1], hi[1], lane, a.q) ^
-                          warm_class<HD, 8>(a.kv, b, kvh, lo[2], hi[2], lane, a.q);
-
     WQ_STAMP(1);
     // ---- query: per head, scale by a power of two so that max |q| lands in [0.5, 1); keep it as f16 ----
 #pragma unroll
@@ -625,7 +583,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         if (lane == 0) sm.qexp[r] = up;
     }
     __syncthreads();
-    *reinterpret_cast<volatile uint32_t*>(&sm.warm[tid]) = sink;   // nobody reads it: it only anchors the warm-up loads
     WQ_STAMP(2);
     // ---- B operands of the logit product for the three classes and the 16-bit segment; group sums of q' ----
     // Wave r builds k-step r (the wave index is uniform, so the parity of r is a uniform branch); every slot of

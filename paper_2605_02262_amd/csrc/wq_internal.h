@@ -14,11 +14,15 @@ struct wq_ctx {
     char* ws;            // device workspace
     size_t ws_bytes;
     bool owns_ws;
+    bool timing;                 // record an event pair around the main decode kernel of every call
+    hipEvent_t ev[2 * 64];       // ring of WQ_TIMING_RING pairs (created by wq_decode_timing)
+    uint64_t ev_calls;           // decode calls timed so far
     char err[256];
 };
 
 constexpr size_t WQ_WS_HEADER = 16384; // zero-initialised: status word (first 256 bytes), then arrival tickets
 constexpr int WQ_MAX_TICKETS = (16384 - 256) / 4;
+constexpr int WQ_TIMING_RING = 64;
 constexpr int WQ_MAX_REP = 8;          // query heads per KV head
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 

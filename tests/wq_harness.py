@@ -69,7 +69,7 @@ def run_oracle(bt: synth.Batch, scores_override: Optional[np.ndarray] = None, mo
     sc = None
     if with_scores:
         sc = O.window_scores(bt.E_v, bt.E_t, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pooled")
-    use = scores_override if scores_override is not None else sc.astype(np.float32)
+    use = np.asarray(scores_override, np.float32) if scores_override is not None else sc.astype(np.float32)
     bits, perm, seg = O.assign_bits(use, t.win_off, mode, quota=t.quota, thresholds=thresholds, top_bits=w.top_bits,
                                     pin_first=w.pin_first)
     pk = O.reorder_quantize(bt.K, bt.V, t.kv_off, t.win_size, t.win_off, perm, seg, w.group,
