@@ -220,6 +220,8 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
     if (B == 0) return WQ_OK;
     if (!kv_off || !win_size || !win_off || !seg_windows) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
     if (total_rows > 0 && (!K || !V || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL K, V or perm");
+    if ((reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V)) % 16 != 0)
+        return wq_fail(ctx, WQ_ERR_ARG, "K and V must be 16-byte aligned");
     if (ctx->ws_bytes < WQ_WS_HEADER + wq_align256(sizeof(int32_t) * (size_t)(B + 1)))
         return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for reorder_quantize");
     return wq_launch_quantize(ctx, K, V, dtype, B, kv_off, win_size, win_off, perm, seg_windows, total_rows, out);

@@ -60,6 +60,33 @@ __device__ __forceinline__ float wq_f16_bits_to_float(uint32_t h)
     return __half2float(__ushort_as_half(static_cast<unsigned short>(h)));
 }
 
+// 8 consecutive elements of a row as floats (16-byte loads for the 16-bit types, 2 x 16 for fp32)
+__device__ __forceinline__ void wq_ld8(const float* p, float* x)
+{
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    x[0] = a.x, x[1] = a.y, x[2] = a.z, x[3] = a.w, x[4] = b.x, x[5] = b.y, x[6] = b.z, x[7] = b.w;
+}
+__device__ __forceinline__ void wq_ld8(const __hip_bfloat16* p, float* x)
+{
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        x[2 * k] = __uint_as_float(w[k] << 16);
+        x[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ void wq_ld8(const __half* p, float* x)
+{
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        x[2 * k] = wq_f16_bits_to_float(w[k] & 0xFFFFu);
+        x[2 * k + 1] = wq_f16_bits_to_float(w[k] >> 16);
+    }
+}
+
 // first b in [0,B) with off[b+1] > x  (off ascending, off[0] <= x < off[B] assumed)
 __device__ __forceinline__ int wq_find_seq(const int32_t* off, int B, int64_t x)
 {

@@ -114,8 +114,9 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
         if (valid) {
             const int64_t base = (src * Hkv + kvh) * HD + p * CPT;
 #pragma unroll
+            for (int i = 0; i < CPT; i += 8) wq_ld8(X + base + i, x + i);     // 16-byte pieces (rows are 16-byte aligned)
+#pragma unroll
             for (int i = 0; i < CPT; i++) {
-                x[i] = wq_ld(X, base + i);
                 lo = fminf(lo, x[i]);
                 hi = fmaxf(hi, x[i]);
             }
@@ -257,7 +258,7 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
         hipLaunchKernelGGL((k_quantize<T, HD, 8>), dim3((unsigned)(pk->cap[2] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
                            kv_off, win_size, win_off, perm, seg_windows, *pk);
     if (total_rows > 0 && pk->cap16 > 0)
-        hipLaunchKernelGGL(k_copy16<T>, dim3((unsigned)total_rows), blk, 0, st, K, V, B, pk->Hkv * HD, kv_off, win_size,
+        hipLaunchKernelGGL(k_copy16<T>, dim3((unsigned)(total_rows < pk->cap16 ? total_rows : pk->cap16)), blk, 0, st, K, V, B, pk->Hkv * HD, kv_off, win_size,
                            win_off, perm, seg_windows, pre16, *pk);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
