@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
     constexpr int QMAX = (1 << BITS) - 1;
     constexpr int CPT = HD / 8;                 // channels per thread: 8 threads share one token row
     constexpr int PER_DW = 32 / BITS;           // codes per output dword
-    __shared__ __align__(16) uint8_t s_code[2][32][HD];
+    __shared__ uint32_t s_v[32][HD / 4 + 1];    // V codes, 4 per word, rows padded by one word (conflict-free column reads)
     __shared__ uint32_t s_meta[2][4][32];       // [plane][group][token]
     const int tid = threadIdx.x;
     const int blk = blockIdx.x;
@@ -141,13 +141,40 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
             sh = __float2half_rn(1.0f);
         }
         const float inv = 1.0f / s;
-        uint8_t* dst = &s_code[plane][u][p * CPT];
+        uint32_t cw[CPT / 4];                   // this thread's codes, 4 per word (8 bits each)
+#pragma unroll
+        for (int i = 0; i < CPT / 4; i++) cw[i] = 0;
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
             float t = (x[i] - m) * inv;         // contraction is off: subtract, round, multiply, round
             float q = rintf(t);
             q = fminf(fmaxf(q, 0.0f), (float)QMAX);
-            dst[i] = valid ? (uint8_t)(int)q : (uint8_t)0;
+            cw[i >> 2] |= (valid ? (uint32_t)(int)q : 0u) << (8 * (i & 3));
+        }
+        if (plane == 0) {
+            // K plane: the thread's CPT codes are consecutive fields of its token's row quarter: pack and store
+            constexpr int Q = HD / 4;
+            constexpr int NB = CPT * BITS / 8;  // bytes: 2..16
+            const int j = (p * CPT) / Q, e0 = (p * CPT) % Q;
+            uint8_t* out = static_cast<uint8_t*>(pk.codes[C]) + ((int64_t)kvh * pk.cap[C] + tok0) * HD * BITS / 8 +
+                           (u >> 4) * (16 * HD * BITS / 8) + ((j * 16 + (u & 15)) * Q + e0) * BITS / 8;
+            uint32_t pw[(NB + 3) / 4];
+#pragma unroll
+            for (int i = 0; i < (NB + 3) / 4; i++) pw[i] = 0;
+#pragma unroll
+            for (int i = 0; i < CPT; i++) pw[(i * BITS) >> 5] |= ((cw[i >> 2] >> (8 * (i & 3))) & 0xFFu) << ((i * BITS) & 31);
+            if constexpr (NB == 2) {
+                *reinterpret_cast<uint16_t*>(out) = (uint16_t)pw[0];
+            } else if constexpr (NB == 4) {
+                *reinterpret_cast<uint32_t*>(out) = pw[0];
+            } else if constexpr (NB == 8) {
+                *reinterpret_cast<uint2*>(out) = uint2{pw[0], pw[1]};
+            } else {
+                *reinterpret_cast<uint4*>(out) = uint4{pw[0], pw[1], pw[2], pw[3]};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CPT / 4; i++) s_v[u][p * (CPT / 4) + i] = cw[i];
         }
         if ((p * CPT) % group == 0) {
             uint32_t word = valid ? ((uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(mh) << 16)) : 0u;
@@ -156,22 +183,6 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
     }
     __syncthreads();
 
-    // ---- K plane: two tiles of 16 tokens, field n = (j*16 + m)*(HD/4) + e ----------------------------------
-    {
-        constexpr int Q = HD / 4;
-        constexpr int TILE_DW = 16 * HD * BITS / 32;
-        uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(pk.codes[C]) +
-                                                   ((int64_t)kvh * pk.cap[C] + tok0) * HD * BITS / 8);
-        for (int w = tid; w < 2 * TILE_DW; w += 256) {
-            int tile = w / TILE_DW, n0 = (w - tile * TILE_DW) * PER_DW;
-            int j = n0 / (16 * Q), mrow = (n0 / Q) % 16, e0 = n0 % Q;
-            const uint8_t* srcp = &s_code[0][tile * 16 + mrow][j * Q + e0];
-            uint32_t word = 0;
-#pragma unroll
-            for (int k = 0; k < PER_DW; k++) word |= (uint32_t)srcp[k] << (k * BITS);
-            out[w] = word;
-        }
-    }
     // ---- V plane: block of 32 tokens, field n = ((jj*16 + mm)*(HD/16) + ct)*8 + tau ----------------------
     {
         constexpr int CT = HD / 16;
@@ -186,7 +197,8 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
                 int tau = n & 7, ct = (n >> 3) % CT, lane = (n >> 3) / CT;
                 int jj = lane >> 4, mm = lane & 15;
                 int tok = 16 * (tau >> 2) + 4 * jj + (tau & 3);
-                word |= (uint32_t)s_code[1][tok][16 * ct + mm] << (k * BITS);
+                const int ch = 16 * ct + mm;
+                word |= ((s_v[tok][ch >> 2] >> (8 * (ch & 3))) & 0xFFu) << (k * BITS);
             }
             out[w] = word;
         }
