@@ -21,7 +21,7 @@
 //
 // The storage layout (wq.h) is exactly the per-lane operand order, so every load is one contiguous piece per
 // lane, a whole tile per wavefront.  Scales and minima travel as one coalesced word per lane and block and are
-// redistributed through LDS.  The query operands of all three classes are built once per workgroup in LDS.
+// redistributed through LDS.  Each wavefront builds the query operands of the class it walks from global memory.
 #pragma once
 
 #ifdef WQ_TIMELINE   // development aid: per-workgroup phase time stamps (100 MHz clock) at the end of the workspace
@@ -152,19 +152,83 @@ template <int HD>
 struct MfmaSmem {
     union {
         struct {
-            uint16_t bq[4][HD / 32][64][8];   // B operands of the logit product: [class, 3 = 16-bit][k-step][lane][slot]
-            _Float16 q[WQ_MAX_REP][HD];       // query, per head scaled by a power of two into [-1, 1]
-            uint16_t qraw[WQ_MAX_REP][HD];    // upper 16 bits of the fp32 query (the bf16 value when q is bf16)
-            uint32_t meta[4][2][64];          // per wave: K and V metadata words of the current block
+            uint32_t meta[4][2][64];              // per wave: K and V metadata words of the current block
             uint16_t vt[4][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
         } run;
-        float O[4][WQ_MAX_REP][HD];           // per-wave numerators for the merge (after the loops)
+        float O[4][WQ_MAX_REP][HD];               // per-wave numerators for the merge (after the loops)
     };
-    float qexp[WQ_MAX_REP];                   // the heads' powers of two
-    float qsum[WQ_MAX_REP][2];                // sum of the scaled query over each group
     float ml[4][WQ_MAX_REP][2];
     int last;
 };
+
+
+// ---- the query operands of one class, built by the wavefront itself -------------------------------------------
+// Lane (j, (g,h)) loads its quarter j of head h's query straight from global memory (hd/4 values), the head's
+// largest magnitude is found with two cross-lane exchanges, the query is scaled by a power of two into [-1, 1)
+// and laid out as the B operands of the k-steps: slot e of k-step r takes channel k_slot(c, r, e) of the quarter,
+// times 2^-shift of that slot; lanes whose quarter is not in their column's group hold zeros (block-diagonal B).
+// Returns the head's power of two (1 for the raw-bf16 operands of a bf16 16-bit segment) and the sum of the scaled
+// query over the lane's group.
+template <int HD, int CLS>
+__device__ __forceinline__ void build_q_operands(const DecodeArgs& a, int b, int kvh, bool raw_bf16, U4* Bq, float& qexp, float& qsum)
+{
+    constexpr int QC = HD / 4, NK = HD / 32;
+    const int lane = threadIdx.x & 63;
+    const int j = lane >> 4, g = (lane & 15) >> 3, h = lane & 7;
+    const bool live = h < a.rep;
+    const int64_t base = ((int64_t)b * a.Hq + kvh * a.rep + (live ? h : 0)) * HD + j * QC;
+    float v[QC];
+    if (a.q_dtype == WQ_F32) {
+        const float* p = static_cast<const float*>(a.q) + base;
+#pragma unroll
+        for (int k = 0; k < QC; k += 8) wq_ld8(p + k, v + k);
+    } else if (a.q_dtype == WQ_BF16) {
+        const __hip_bfloat16* p = static_cast<const __hip_bfloat16*>(a.q) + base;
+#pragma unroll
+        for (int k = 0; k < QC; k += 8) wq_ld8(p + k, v + k);
+    } else {
+        const __half* p = static_cast<const __half*>(a.q) + base;
+#pragma unroll
+        for (int k = 0; k < QC; k += 8) wq_ld8(p + k, v + k);
+    }
+    float mx = 0.f;
+#pragma unroll
+    for (int k = 0; k < QC; k++) {
+        if (!live) v[k] = 0.f;
+        mx = fmaxf(mx, fabsf(v[k]));
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const int eb = (int)((__float_as_uint(mx) >> 23) & 0xFFu);              // biased exponent of the largest |q|
+    const bool ok = eb > 0 && eb < 253;                                       // zero, denormal or non-finite: leave as is
+    const float dn = ok ? __uint_as_float((uint32_t)(253 - eb) << 23) : 1.0f;     // 2^-(eb-126): max |q| lands in [0.5, 1)
+    const float up = ok ? __uint_as_float((uint32_t)(eb + 1) << 23) : 1.0f;       // 2^(eb-126)
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < QC; k++) s += (float)(_Float16)(v[k] * dn);
+    const float pair = s + __shfl_xor(s, 16, 64);                            // both quarters of group j/2
+    const float other = __shfl_xor(pair, 32, 64);
+    const bool mine = (j >> 1) == g;
+    qsum = mine ? pair : other;
+    qexp = raw_bf16 ? 1.0f : up;
+#pragma unroll
+    for (int r = 0; r < NK; r++) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; e2++) {
+            uint32_t half[2];
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                int ch, sh;
+                k_slot(CLS, r, 2 * e2 + t, ch, sh);
+                const _Float16 f = (_Float16)(v[ch] * dn * __uint_as_float((uint32_t)(127 - sh) << 23));
+                half[t] = raw_bf16 ? (__float_as_uint(v[ch]) >> 16) : (uint32_t)__builtin_bit_cast(uint16_t, f);
+            }
+            w[e2] = mine ? (half[0] | (half[1] << 16)) : 0u;
+        }
+        Bq[r] = U4{w[0], w[1], w[2], w[3]};
+    }
+}
 
 template <int HD, int BITS>
 struct Frag {
@@ -198,7 +262,7 @@ __device__ __forceinline__ void load_dwords(const uint32_t* __restrict__ p, uint
 
 // One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
 template <int HD, int BITS, int DEPTH>
-__device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
+__device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
                                                 float c_log2, WaveState<HD>& st)
 {
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
@@ -209,15 +273,19 @@ __device__ __forceinline__ void walk_class_mfma(const wq_packed_kv& kv, MfmaSmem
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
 
     if (blk_lo >= blk_hi) return;
+    const wq_packed_kv& kv = a.kv;
     const int len = kv.cls_len[C][b];
 
+    U4 Bqw[NK];
+    float qexp, qsum;
+    build_q_operands<HD, C>(a, b, kvh, false, Bqw, qexp, qsum);
     half8 Bq[NK];
 #pragma unroll
-    for (int r = 0; r < NK; r++) Bq[r] = *reinterpret_cast<const half8*>(&sm.run.bq[C][r][lane][0]);
+    for (int r = 0; r < NK; r++) Bq[r] = __builtin_bit_cast(half8, Bqw[r]);
     // logits come out of the matrix cores as 2^-24 * sum q' code; fold 2^24, the head's power of two and
     // sm_scale*log2(e) into one constant, and pre-divide the m-term by 2^24 so both terms share it.
-    const float cexp = c_log2 * sm.qexp[h] * 16777216.0f;
-    const float qs = sm.qsum[h][g] * (1.0f / 16777216.0f);
+    const float cexp = c_log2 * qexp * 16777216.0f;
+    const float qs = qsum * (1.0f / 16777216.0f);
 
     const int64_t cap = kv.cap[C];
     const int64_t tok_base = kv.cls_off[C][b];
@@ -360,22 +428,23 @@ __device__ __forceinline__ floatx4 mfma16(uint32_t a0, uint32_t a1, uint32_t a2,
 // the bf16 instruction with the exact bf16 query and the weights split into two bf16 terms (p = hi + lo);
 // fp16 caches use the f16 instruction.  Accumulators are in true units here (no 2^-24).
 template <int HD, bool BF>
-__device__ __forceinline__ void walk_seg16_mfma(const wq_packed_kv& kv, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
+__device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
                                                 float c_log2, WaveState<HD>& st)
 {
     constexpr int NK = HD / 32, CT = HD / 16, PITCH = HD / 2 + VT_PAD, KDW = HD / 8;
     if (blk_lo >= blk_hi) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane >> 4, col = lane & 15, h = col & 7;
+    const wq_packed_kv& kv = a.kv;
     const int len = kv.len16[b];
     const int64_t row0 = kv.off16[b];
     const int64_t rstride = (int64_t)kv.Hkv * HD;
     const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16) + (int64_t)kvh * HD;
     const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16) + (int64_t)kvh * HD;
     U4 Bq[NK];
-#pragma unroll
-    for (int r = 0; r < NK; r++) Bq[r] = *reinterpret_cast<const U4*>(&sm.run.bq[3][r][lane][0]);
-    const float cexp = BF ? c_log2 : c_log2 * sm.qexp[h];
+    float qexp, qsum;
+    build_q_operands<HD, 3>(a, b, kvh, BF, Bq, qexp, qsum);
+    const float cexp = c_log2 * qexp;
     uint16_t* vt = &sm.run.vt[wave][0][0];
 
     for (int blk = blk_lo; blk < blk_hi; blk++) {
@@ -503,27 +572,9 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
-    constexpr int CT = HD / 16, NK = HD / 32, QC = HD / 4;
+    constexpr int CT = HD / 16;
     const bool bf16seg = a.kv.dtype16 == WQ_BF16;
     WQ_STAMP(0);
-
-    // ---- the query loads go out first (heads wave and wave+4 of this KV head) ----
-    // (raw bits first, one uniform branch on the element type, so that all four loads are in flight together)
-    uint32_t qraw[2][2];
-    const bool qh0 = wave < a.rep, qh1 = wave + 4 < a.rep;      // heads past rep re-read head 0 and are zeroed later
-    {
-        const int64_t hb = ((int64_t)b * a.Hq + kvh * a.rep) * HD + lane;
-        const int64_t b0 = hb + (qh0 ? wave : 0) * HD, b1 = hb + (qh1 ? wave + 4 : 0) * HD;
-        if (a.q_dtype == WQ_F32) {
-            const uint32_t* p = static_cast<const uint32_t*>(a.q);
-            qraw[0][0] = p[b0], qraw[1][0] = p[b1];
-            qraw[0][1] = HD == 128 ? p[b0 + 64] : 0u, qraw[1][1] = HD == 128 ? p[b1 + 64] : 0u;
-        } else {
-            const uint16_t* p = static_cast<const uint16_t*>(a.q);
-            qraw[0][0] = p[b0], qraw[1][0] = p[b1];
-            qraw[0][1] = HD == 128 ? p[b0 + 64] : 0u, qraw[1][1] = HD == 128 ? p[b1 + 64] : 0u;
-        }
-    }
 
     // ---- this wavefront's cost-balanced share of the stream [16-bit | 2-bit | 4-bit | 8-bit] of (b, kvh) ----
     int lo[4], hi[4];
@@ -554,96 +605,14 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
 
     WQ_STAMP(1);
-    // ---- query: per head, scale by a power of two so that max |q| lands in [0.5, 1); keep it as f16 ----
-#pragma unroll
-    for (int k = 0; k < 2; k++) {
-        const int r = wave + 4 * k;
-        float v0, v1;
-        if (a.q_dtype == WQ_F32) {
-            v0 = __uint_as_float(qraw[k][0]), v1 = __uint_as_float(qraw[k][1]);
-        } else if (a.q_dtype == WQ_BF16) {
-            v0 = wq_bf16_bits_to_float(qraw[k][0]), v1 = wq_bf16_bits_to_float(qraw[k][1]);
-        } else {
-            v0 = wq_f16_bits_to_float(qraw[k][0]), v1 = wq_f16_bits_to_float(qraw[k][1]);
-        }
-        if (!(k == 0 ? qh0 : qh1)) v0 = v1 = 0.f;
-        float mx = fmaxf(fabsf(v0), fabsf(v1));
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-        const int eb = (int)((__float_as_uint(mx) >> 23) & 0xFFu);            // biased exponent of the largest |q|
-        const bool ok = eb > 0 && eb < 253;                                     // zero, denormal or non-finite: leave as is
-        const float dn = ok ? __uint_as_float((uint32_t)(253 - eb) << 23) : 1.0f;   // 2^-(eb-126)
-        const float up = ok ? __uint_as_float((uint32_t)(eb + 1) << 23) : 1.0f;     // 2^(eb-126)
-        sm.run.q[r][lane] = (_Float16)(v0 * dn);
-        sm.run.qraw[r][lane] = (uint16_t)(__float_as_uint(v0) >> 16);
-        if (HD == 128) {
-            sm.run.q[r][64 + lane] = (_Float16)(v1 * dn);
-            sm.run.qraw[r][64 + lane] = (uint16_t)(__float_as_uint(v1) >> 16);
-        }
-        if (lane == 0) sm.qexp[r] = up;
+#ifdef WQ_TIMELINE
+    if (a.dbg && threadIdx.x == 0) {
+        const int64_t wg = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        a.dbg[wg * 32 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
+        a.dbg[wg * 32 + 7] = __builtin_amdgcn_s_getreg((31 << 11) | 20);   // XCC_ID
     }
-    __syncthreads();
+#endif
     WQ_STAMP(2);
-    // ---- B operands of the logit product for the three classes and the 16-bit segment; group sums of q' ----
-    // Wave r builds k-step r (the wave index is uniform, so the parity of r is a uniform branch); every slot of
-    // (class, r) draws on the same 16 consecutive channels of the lane's quarter: two 16-byte LDS reads.
-    if (wave < NK) {
-        const int r = wave, lj = lane >> 4, lg = (lane & 15) >> 3, lh = lane & 7;
-        const bool mine = (lj >> 1) == lg;
-        const int c0 = lj * QC + 16 * (r >> 1);
-        _Float16 hq[16];
-        uint16_t hr[16];
-        {
-            const U4 u0 = *reinterpret_cast<const U4*>(&sm.run.q[lh][c0]), u1 = *reinterpret_cast<const U4*>(&sm.run.q[lh][c0 + 8]);
-            const U4 w0 = *reinterpret_cast<const U4*>(&sm.run.qraw[lh][c0]), w1 = *reinterpret_cast<const U4*>(&sm.run.qraw[lh][c0 + 8]);
-            const uint32_t uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-            const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                hq[2 * k] = __builtin_bit_cast(_Float16, (uint16_t)(uu[k] & 0xFFFFu));
-                hq[2 * k + 1] = __builtin_bit_cast(_Float16, (uint16_t)(uu[k] >> 16));
-                hr[2 * k] = (uint16_t)(ww[k] & 0xFFFFu);
-                hr[2 * k + 1] = (uint16_t)(ww[k] >> 16);
-            }
-        }
-        auto build = [&](auto odd_tag) {
-            constexpr int ODD = decltype(odd_tag)::value;
-#pragma unroll
-            for (int c = 0; c < 4; c++) {
-                uint16_t row[8];
-#pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    int ch, sh;
-                    k_slot(c, ODD, e, ch, sh);          // r = ODD has the same parity and r/2 == 0: ch is local to the 16 channels
-                    if (c == 3 && bf16seg) {
-                        row[e] = hr[ch];
-                    } else {
-                        const _Float16 qv = hq[ch] * (_Float16)__uint_as_float((uint32_t)(127 - sh) << 23);
-                        row[e] = __builtin_bit_cast(uint16_t, qv);
-                    }
-                    if (!mine) row[e] = 0;
-                }
-                U4 o{(uint32_t)row[0] | ((uint32_t)row[1] << 16), (uint32_t)row[2] | ((uint32_t)row[3] << 16),
-                     (uint32_t)row[4] | ((uint32_t)row[5] << 16), (uint32_t)row[6] | ((uint32_t)row[7] << 16)};
-                *reinterpret_cast<U4*>(&sm.run.bq[c][r][lane][0]) = o;
-            }
-        };
-        if (r & 1)
-            build(std::integral_constant<int, 1>{});
-        else
-            build(std::integral_constant<int, 0>{});
-    }
-    {
-        // 16 sums (head, group) of HD/2 values: 16 lanes each
-        const int sidx = tid >> 4, part = tid & 15, hh = sidx >> 1, gg = sidx & 1;
-        float s = 0.f;
-#pragma unroll
-        for (int k = 0; k < HD / 32; k++) s += (float)sm.run.q[hh][gg * (HD / 2) + part + 16 * k];
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        if (part == 0) sm.qsum[hh][gg] = s;
-    }
-    __syncthreads();
     WQ_STAMP(3);
 
     WaveState<HD> st;
@@ -656,18 +625,18 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     WQ_WSTAMP(0, wall_clock64());
     WQ_WSTAMP(5, ((long long)(hi[3] - lo[3]) << 48) | ((long long)(hi[0] - lo[0]) << 32) | ((long long)(hi[1] - lo[1]) << 16) | (long long)(hi[2] - lo[2]));
     if (bf16seg)
-        walk_seg16_mfma<HD, true>(a.kv, sm, b, kvh, lo[3], hi[3], c_log2, st);
+        walk_seg16_mfma<HD, true>(a, sm, b, kvh, lo[3], hi[3], c_log2, st);
     else
-        walk_seg16_mfma<HD, false>(a.kv, sm, b, kvh, lo[3], hi[3], c_log2, st);
+        walk_seg16_mfma<HD, false>(a, sm, b, kvh, lo[3], hi[3], c_log2, st);
     // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
     WQ_WSTAMP(1, wall_clock64());
-    walk_class_mfma<HD, 2, 2>(a.kv, sm, b, kvh, lo[0], hi[0], c_log2, st);
+    walk_class_mfma<HD, 2, 2>(a, sm, b, kvh, lo[0], hi[0], c_log2, st);
     WQ_WSTAMP(2, wall_clock64());
-    walk_class_mfma<HD, 4, 2>(a.kv, sm, b, kvh, lo[1], hi[1], c_log2, st);
+    walk_class_mfma<HD, 4, 2>(a, sm, b, kvh, lo[1], hi[1], c_log2, st);
     WQ_WSTAMP(3, wall_clock64());
-    walk_class_mfma<HD, 8, 1>(a.kv, sm, b, kvh, lo[2], hi[2], c_log2, st);
+    walk_class_mfma<HD, 8, 1>(a, sm, b, kvh, lo[2], hi[2], c_log2, st);
     WQ_WSTAMP(4, wall_clock64());
 
     WQ_STAMP(4);
