@@ -168,6 +168,9 @@ def main():
     kern_mean_us = timed(dec(W.DECODE_AUTO | W.DECODE_PARTIALS_ONLY), n)     # the streaming kernel alone
     sc_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
                                                total_win, scores=scores), n)
+    scm_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
+                                                total_win, algo=W.SCORE_PAIRWISE_MFMA, scores=scores), max(4, n // 8))
+    pair_flops = sum(2.0 * sq.n_win * sq.win_size * sq.n_text * w.D for sq in w.seqs)
     as_us = timed(lambda i: W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first), n)
     rq_us = timed(lambda i: W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, copies[i % N_COPIES]), n)
     st_mean = [sc_us, as_us, rq_us, dec_us]
@@ -208,6 +211,10 @@ def main():
             "reorder_quantize": {"bound": "hbm", "unit": "GB/s",
                                  "achieved": round((total_rows * w.Hkv * w.hd * 2 * 2 + alg_bytes) / (st_mean[2] * 1e-6) / 1e9, 1)
                                  if st_mean[2] > 0 else None},
+            "window_scores_pairwise_mfma": {"bound": "mfma", "unit": "TFLOP/s", "peak": 2500.0, "us": round(scm_us, 1),
+                                            "achieved": round(pair_flops / (scm_us * 1e-6) / 1e12, 1),
+                                            "frac": round(pair_flops / (scm_us * 1e-6) / 1e12 / 2500.0, 4),
+                                            "note": "literal pairwise form on the matrix cores; the default is the pooled form"},
             "window_scores": {"bound": "hbm", "unit": "GB/s",
                               "achieved": round((total_vis + total_txt) * w.D * 2 / (st_mean[0] * 1e-6) / 1e9, 1)
                               if st_mean[0] > 0 else None}},

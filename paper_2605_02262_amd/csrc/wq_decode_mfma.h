@@ -270,7 +270,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
     constexpr int CT = HD / 16;                    // channel tiles of the value product
     using F = Frag<HD, BITS>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
+    const int j = lane >> 4, col = lane & 15, g = col >> 3;
 
     if (blk_lo >= blk_hi) return;
     const wq_packed_kv& kv = a.kv;
@@ -434,7 +434,7 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
     constexpr int NK = HD / 32, CT = HD / 16, PITCH = HD / 2 + VT_PAD, KDW = HD / 8;
     if (blk_lo >= blk_hi) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = lane >> 4, col = lane & 15, h = col & 7;
+    const int j = lane >> 4, col = lane & 15;
     const wq_packed_kv& kv = a.kv;
     const int len = kv.len16[b];
     const int64_t row0 = kv.off16[b];

@@ -114,3 +114,28 @@ def test_scores_only_larger_D():
     H.assert_scores_close(s, want)
     pair = O.window_scores(Ev[:196], Et[:256], [0, 196], [0, 256], [196], [0, 1], form="pairwise")
     assert abs(pair[0] - want[0]) < 1e-12
+
+
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16])
+def test_scores_pairwise_on_matrix_cores(dtype):
+    """The literal pairwise form on the matrix cores against the fp64 oracle (pairwise form where it is affordable)."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(3, 70, 35, 150, (1, 1, 1)),             # 210 rows: tiles of 128 with a ragged tail, 150 text tokens
+             synth.SeqSpec(0, 10, 4, 5, (0, 0, 0)),                # no visual rows
+             synth.SeqSpec(2, 196, 98, 300, (1, 1, 2), tail=5),    # 397 rows, 300 text tokens: three column tiles
+             synth.SeqSpec(2, 64, 64, 0, (1, 1, 0))]               # no text at all -> scores 0
+    w = synth.Workload("pair", dtype, dtype, 28, 4, 128, 64, 896, 1.5, specs, 9)
+    t = synth.tables(w)
+    ets, evs = zip(*[synth.embeddings(w, b) for b in range(w.B)])
+    Et, Ev = np.concatenate(ets), np.concatenate(evs)
+    ctx = W.Context(W.workspace_bytes(w.B, 0, 0, 0, Ev.shape[0], Et.shape[0], w.D))
+    args = (H.to_dev(Ev, dtype), H.to_dev(Et, dtype), H.i32(t.vis_off), H.i32(t.txt_off), H.i32(t.win_size), H.i32(t.win_off),
+            Ev.shape[0], Et.shape[0], int(t.win_off[-1]))
+    s_mfma = W.wq_window_scores(ctx, *args, algo=W.SCORE_PAIRWISE_MFMA)
+    s_pool = W.wq_window_scores(ctx, *args, algo=W.SCORE_POOLED)
+    torch.cuda.synchronize()
+    want = O.window_scores(Ev, Et, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pairwise")
+    H.assert_scores_close(s_mfma, want)
+    H.assert_scores_close(s_pool, want)
