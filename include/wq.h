@@ -88,7 +88,7 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
  *                wq_create allocate workspace_bytes itself (freed by wq_destroy).  Size it with
  *                wq_workspace_bytes; calls that need more return WQ_ERR_WORKSPACE.
  *                A caller-provided workspace must start with 16384 zero bytes (device status word and
- *                arrival counters; the library leaves them zero after every call).
+ *                reserved words; the library leaves them zero after every call).
  * wq_create touches no GPU when it is given a workspace (or workspace_bytes == 0).                          */
 int wq_create(wq_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes);
 int wq_destroy(wq_ctx* ctx);

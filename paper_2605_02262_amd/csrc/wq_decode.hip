@@ -25,10 +25,9 @@ struct DecodeArgs {
     int splits16, nparts;   // workgroups on the 16-bit segment; nparts = splits + splits16 partials per (b, KV head)
     int use_mfma;
     int mfma16;             // the matrix-core kernel also walks the 16-bit segment
-    int fused;              // ... and merges the splits itself (last workgroup per (b, KV head))
+    int wgt[4];             // cost of one 32-token block of the 2-, 4-, 8- and 16-bit class, relative to each other
     wq_packed_kv kv;
     float* part;            // [B][Hkv][nparts][rep][hd + 2]
-    unsigned* tickets;      // [B*Hkv] arrival counters, zero between launches
     float* out;
     float* lse;
 #ifdef WQ_TIMELINE
@@ -384,10 +383,12 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.mfma16 = a.use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
     a.splits16 = (a.use_mfma && !a.mfma16) ? wq_decode_splits16(B, kv->cap16) : 0;
     a.nparts = a.splits + a.splits16;
-    a.fused = getenv("WQ_FUSE") && a.use_mfma && a.mfma16 && (int64_t)B * kv->Hkv <= WQ_MAX_TICKETS && 2 * a.nparts * a.rep <= 4 * WQ_MAX_REP * kv->hd;
     a.kv = *kv;
+    for (int c = 0; c < 4; c++) a.wgt[c] = WQ_BLOCK_COST[c];
+#ifdef WQ_TUNE
+    if (getenv("WQ_WGT")) sscanf(getenv("WQ_WGT"), "%d,%d,%d,%d", &a.wgt[0], &a.wgt[1], &a.wgt[2], &a.wgt[3]);
+#endif
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
-    a.tickets = reinterpret_cast<unsigned*>(ctx->ws + 256);
     a.out = out;
 #ifdef WQ_TIMELINE
     a.dbg = getenv("WQ_TIMELINE") ? reinterpret_cast<long long*>(ctx->ws + ctx->ws_bytes - (8 << 20)) : nullptr;
@@ -416,7 +417,7 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
             if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
         }
     }
-    if (!a.fused && !partials_only)
+    if (!partials_only)
         hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
     if (ctx->timing) ctx->ev_calls++;
     WQ_HIP_CHECK(ctx, hipGetLastError());

@@ -10,8 +10,11 @@
 //                            dot products and every lane of the softmax has real work (7 of 8 columns per half).
 //   dequant                  logit = s0*D0 + m0*sum(q over group 0) + s1*D1 + m1*sum(q over group 1): each lane
 //                            applies its own group's (s, m), the two halves meet with one DPP row rotate.
-//   online softmax           running max shared by the wavefront's four lane groups; it is re-synchronised (and
-//                            the output accumulators rescaled) only when some logit exceeds it.
+//   online softmax           reference exponent per column, shared by the wavefront's four lane groups.  It starts
+//                            as the first block's largest logit and moves (with a rescale of the output
+//                            accumulators) only when a logit exceeds it by more than 2^8: weights stay below
+//                            2^8, far inside what f32 sums and the f16 operand hold, and a new largest logit
+//                            (there is one in most blocks of a short walk) costs nothing.
 //   O^T += V_codes^T . P'^T  P' = p * s_v (per value group, hence the same 16 columns), raw V codes as A; the
 //                            m_v part of the dequantised values is the scalar sum  p * m_v  kept per lane.
 //
@@ -54,6 +57,27 @@ __device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c)
 
 __device__ __forceinline__ float f16lo(uint32_t w) { return wq_f16_bits_to_float(w & 0xFFFFu); }
 __device__ __forceinline__ float f16hi(uint32_t w) { return wq_f16_bits_to_float(w >> 16); }
+
+// largest of three without the quieting moves that fmaxf brings along (inputs here are never signalling NaNs)
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// (f16 in the low half of w) * p, rounded to f16, into the low / the high half of a register
+__device__ __forceinline__ uint32_t mul_f16lo_to_lo(uint32_t w, float p)
+{
+    uint32_t r;
+    asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(p));
+    return r;
+}
+__device__ __forceinline__ uint32_t mul_f16lo_to_hi(uint32_t acc, uint32_t w, float p)
+{
+    asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(w), "v"(p));
+    return acc;
+}
 
 // rotate by 8 lanes inside each row of 16 lanes: lane (g,h) <-> lane (1-g,h)
 __device__ __forceinline__ float ror8(float v)
@@ -141,11 +165,15 @@ __device__ __forceinline__ half8 v_operand(const uint32_t* x, int ct)
 template <int HD>
 struct WaveState {
     floatx4 O[HD / 16];   // O^T tiles: row = channel 16ct + 4j + i, column = (g,h)
-    float m;              // running max of this column's logits, log2 domain, shared by the four lane groups
+    float m;              // reference exponent of this column (a recent largest logit), log2 domain, shared by the four lane groups
     float l;              // this lane's share of sum p
     float accM;           // this lane's share of sum p * m_v
 };
 
+// 32-token blocks in flight per wavefront and class: enough bytes to keep the memory system busy while a block
+// is being worked on (a 2-bit block is 2.5 KB, an 8-bit block 8.5 KB)
+constexpr int WQ_D2 = 4, WQ_D4 = 3, WQ_D8 = 2;
+constexpr float WQ_MAX_SLACK = 8.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
 constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
 
 template <int HD>
@@ -158,7 +186,6 @@ struct MfmaSmem {
         float O[4][WQ_MAX_REP][HD];               // per-wave numerators for the merge (after the loops)
     };
     float ml[4][WQ_MAX_REP][2];
-    int last;
 };
 
 
@@ -265,6 +292,7 @@ template <int HD, int BITS, int DEPTH>
 __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
                                                 float c_log2, WaveState<HD>& st)
 {
+    static_assert(DEPTH >= 1 && DEPTH <= 4, "pipeline slots of the short block");
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
     constexpr int NK = HD / 32;                    // k-steps of the logit product per 16-token tile
     constexpr int CT = HD / 16;                    // channel tiles of the value product
@@ -310,7 +338,9 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
 #pragma unroll
     for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v);
 
-    auto compute = [&](int blk, const F& f) {
+    // one 32-token block; PARTIAL: the sequence's last block of the class, tokens past its end are masked out
+    auto compute = [&](int blk, const F& f, auto partial) {
+        constexpr bool PARTIAL = decltype(partial)::value;
         // ---- scales and minima: one word per lane in, the lane's 4 tokens x 2 tiles x {K,V} out ----
         smeta[lane] = f.km;
         smeta[64 + lane] = f.vm;
@@ -341,18 +371,18 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
                 x[4 * t + i] = y + ror8(y);
             }
         }
-        const int nv = len - blk * 32;             // valid tokens in this block (only the last one is short)
-        if (nv < 32) {
+        if constexpr (PARTIAL) {
+            const int nv = len - blk * 32;         // valid tokens in this block
 #pragma unroll
             for (int t = 0; t < 2; t++)
 #pragma unroll
                 for (int i = 0; i < 4; i++)
                     if (16 * t + 4 * j + i >= nv) x[4 * t + i] = -INFINITY;
         }
-        // ---- running max: touch the other lane groups only when some logit beats it ----
-        float lm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        // ---- reference exponent: touch the other lane groups only when some logit is far above it ----
+        float lm = max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
         lm *= cexp;                                // cexp > 0
-        if (__builtin_amdgcn_ballot_w64(lm > st.m) != 0) {
+        if (__builtin_amdgcn_ballot_w64(lm > st.m + WQ_MAX_SLACK) != 0) {
             lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
             lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
             const float mn = fmaxf(st.m, lm);
@@ -370,20 +400,18 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
             for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
         }
         // ---- weights with the slot's power of two folded into the exponent, P' = p * s_v, and the m_v part ----
-        _Float16 pp[8];
+        float p[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -ms[k & 3]));
-            lv[k & 3] += p;
-            av[k & 3] = fmaf(f16hi(vw[k]), p, av[k & 3]);
-            pp[k] = (_Float16)fmaf(f16lo(vw[k]), p, 0.0f);
+            p[k] = __builtin_amdgcn_exp2f(fmaf(x[k], cexp, -ms[k & 3]));
+            lv[k & 3] += p[k];
+            av[k & 3] = fmaf(f16hi(vw[k]), p[k], av[k & 3]);
         }
-        half8 Bp;
+        uint32_t bp[4];
 #pragma unroll
-        for (int v = 0; v < 4; v++) {
-            Bp[2 * v] = pp[v];                     // tile 0, token 4j+v
-            Bp[2 * v + 1] = pp[4 + v];             // tile 1, token 4j+v
-        }
+        for (int v = 0; v < 4; v++)                // slots (2v, 2v+1) = (tile 0, tile 1) token 4j+v
+            bp[v] = mul_f16lo_to_hi(mul_f16lo_to_lo(vw[v], p[v]), vw[4 + v], p[4 + v]);
+        const half8 Bp = as_half8(bp[0], bp[1], bp[2], bp[3]);
         // ---- values ----
 #pragma unroll
         for (int ct = 0; ct < CT; ct++) st.O[ct] = mfma(v_operand<BITS>(f.v, ct), Bp, st.O[ct]);
@@ -394,14 +422,24 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
 #pragma unroll
     for (int d = 0; d < DEPTH; d++)
         if (blk_lo + d < blk_hi) load(blk_lo + d, f[d]);
-    for (int blk = blk_lo; blk < blk_hi; blk += DEPTH) {
+    // only the sequence's last block of the class can be short; it gets an instance of its own after the loop,
+    // so that the loop carries no masking
+    const int full_hi = blk_hi * 32 > len ? blk_hi - 1 : blk_hi;
+    for (int blk = blk_lo; blk < full_hi; blk += DEPTH) {
 #pragma unroll
         for (int d = 0; d < DEPTH; d++) {
-            if (blk + d < blk_hi) {
-                compute(blk + d, f[d]);
+            if (blk + d < full_hi) {
+                compute(blk + d, f[d], std::false_type{});
                 if (blk + d + DEPTH < blk_hi) load(blk + d + DEPTH, f[d]);
             }
         }
+    }
+    if (full_hi < blk_hi) {
+        const int slot = (full_hi - blk_lo) % DEPTH;       // the short block's data sits in its pipeline slot
+        if (DEPTH > 1 && slot == 1) f[0] = f[DEPTH > 1 ? 1 : 0];
+        if (DEPTH > 2 && slot == 2) f[0] = f[DEPTH > 2 ? 2 : 0];
+        if (DEPTH > 3 && slot == 3) f[0] = f[DEPTH > 3 ? 3 : 0];
+        compute(full_hi, f[0], std::true_type{});
     }
 #pragma unroll
     for (int v = 0; v < 4; v++) {
@@ -486,7 +524,7 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
         }
         float lm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         lm *= cexp;
-        if (__builtin_amdgcn_ballot_w64(lm > st.m) != 0) {
+        if (__builtin_amdgcn_ballot_w64(lm > st.m + WQ_MAX_SLACK) != 0) {
             lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
             lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
             const float mn = fmaxf(st.m, lm);
@@ -581,7 +619,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     {
         // cost of one 32-token block of each class relative to the others, as measured on MI355X: the loop is
         // bound by issue and latency per block more than by bytes, so the shares are balanced by block cost
-        const int wgt[4] = {113, 118, 158, 372};
+        const int wgt[4] = {a.wgt[0], a.wgt[1], a.wgt[2], a.wgt[3]};
         int nb[4];
 #pragma unroll
         for (int c = 0; c < 3; c++) nb[c] = (a.kv.cls_len[c][b] + 31) >> 5;
@@ -632,11 +670,11 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
     WQ_WSTAMP(1, wall_clock64());
-    walk_class_mfma<HD, 2, 2>(a, sm, b, kvh, lo[0], hi[0], c_log2, st);
+    walk_class_mfma<HD, 2, WQ_D2>(a, sm, b, kvh, lo[0], hi[0], c_log2, st);
     WQ_WSTAMP(2, wall_clock64());
-    walk_class_mfma<HD, 4, 2>(a, sm, b, kvh, lo[1], hi[1], c_log2, st);
+    walk_class_mfma<HD, 4, WQ_D4>(a, sm, b, kvh, lo[1], hi[1], c_log2, st);
     WQ_WSTAMP(3, wall_clock64());
-    walk_class_mfma<HD, 8, 1>(a, sm, b, kvh, lo[2], hi[2], c_log2, st);
+    walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, lo[2], hi[2], c_log2, st);
     WQ_WSTAMP(4, wall_clock64());
 
     WQ_STAMP(4);
@@ -660,8 +698,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     __syncthreads();
     // ---- merge the four waves, write the partial (m in natural-log units) ----
-    // Partials are written and read with device-scope accesses that go through to memory (every XCD has its own
-    // L2), so that no cache write-back is needed to hand them to the workgroup that merges the splits.
     const int64_t pstride = (int64_t)a.rep * (HD + 2);
     float* pbase = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts) * pstride;
     float* out = pbase + split * pstride;
@@ -676,71 +712,13 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             num = fmaf(sm.O[w][r][ch], s, num);
             L = fmaf(sm.ml[w][r][1], s, L);
         }
-        __hip_atomic_store(out + r * (HD + 2) + ch, num, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        out[r * (HD + 2) + ch] = num;
         if (ch == 0) {
-            __hip_atomic_store(out + r * (HD + 2) + HD, M * 0.6931471805599453f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(out + r * (HD + 2) + HD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            out[r * (HD + 2) + HD] = M * 0.6931471805599453f;
+            out[r * (HD + 2) + HD + 1] = L;
         }
     }
     WQ_STAMP(5);
-    if (!a.fused) return;
-
-    // ---- the last workgroup of (b, kvh) to arrive merges all splits in split order ----
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // this lane's stores have completed
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned old = __hip_atomic_fetch_add(a.tickets + b * a.kv.Hkv + kvh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm.last = (old == (unsigned)a.nparts - 1u);
-    }
-    __syncthreads();
-    if (!sm.last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");    // drop stale lines: the partials below come from memory
-    if (tid == 0) __hip_atomic_store(a.tickets + b * a.kv.Hkv + kvh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-    float* wts = &sm.O[0][0][0];                   // [rep][nparts] m_s, then the weights e^{m_s - M}
-    float* lsum = wts + a.rep * a.nparts;          // [rep][nparts] l_s
-    for (int idx = tid; idx < a.rep * a.nparts; idx += 256) {
-        const int r = idx / a.nparts, s = idx - r * a.nparts;
-        const float* src = pbase + s * pstride + r * (HD + 2) + HD;
-        wts[idx] = src[0];
-        lsum[idx] = src[1];
-    }
-    __syncthreads();
-    if (tid < a.rep) {                             // per head: max, then weights, then the denominator (split order)
-        float M = -INFINITY;
-        for (int s = 0; s < a.nparts; s++) M = fmaxf(M, wts[tid * a.nparts + s]);
-        float L = 0.f;
-        for (int s = 0; s < a.nparts; s++) {
-            const float ms = wts[tid * a.nparts + s];
-            const float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
-            wts[tid * a.nparts + s] = w;
-            L = fmaf(lsum[tid * a.nparts + s], w, L);
-        }
-        sm.ml[0][tid][0] = M;
-        sm.ml[0][tid][1] = L;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < a.rep * HD; idx += 256) {
-        const int r = idx / HD, ch = idx - r * HD;
-        const float* src = pbase + r * (HD + 2) + ch;
-        float acc = 0.f;
-        int s = 0;
-        for (; s + 4 <= a.nparts; s += 4) {
-            const float a0 = *(src + (s + 0) * pstride);
-            const float a1 = *(src + (s + 1) * pstride);
-            const float a2 = *(src + (s + 2) * pstride);
-            const float a3 = *(src + (s + 3) * pstride);
-            acc = fmaf(a0, wts[r * a.nparts + s], acc);
-            acc = fmaf(a1, wts[r * a.nparts + s + 1], acc);
-            acc = fmaf(a2, wts[r * a.nparts + s + 2], acc);
-            acc = fmaf(a3, wts[r * a.nparts + s + 3], acc);
-        }
-        for (; s < a.nparts; s++)
-            acc = fmaf(*(src + s * pstride), wts[r * a.nparts + s], acc);
-        const float L = sm.ml[0][r][1];
-        const int hq = kvh * a.rep + r;
-        a.out[((int64_t)b * a.Hq + hq) * HD + ch] = L > 0.f ? acc / L : 0.f;
-        if (a.lse && ch == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? sm.ml[0][r][0] + logf(L) : -INFINITY;
-    }
 }
 
 }  // namespace

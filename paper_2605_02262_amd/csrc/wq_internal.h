@@ -20,10 +20,12 @@ struct wq_ctx {
     char err[256];
 };
 
-constexpr size_t WQ_WS_HEADER = 16384; // zero-initialised: status word (first 256 bytes), then arrival tickets
-constexpr int WQ_MAX_TICKETS = (16384 - 256) / 4;
+constexpr size_t WQ_WS_HEADER = 16384; // zero-initialised: status word (first 256 bytes)
 constexpr int WQ_TIMING_RING = 64;
 constexpr int WQ_MAX_REP = 8;          // query heads per KV head
+// wall time of one 32-token block of the 2-, 4-, 8- and 16-bit class in the decode kernel, relative to each other
+// (measured on MI355X with the whole chip streaming): the fixed shares of the token axis are balanced by it
+constexpr int WQ_BLOCK_COST[4] = {100, 130, 230, 500};
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 
 inline int wq_fail(wq_ctx* ctx, int code, const char* fmt, ...)
