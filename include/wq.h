@@ -77,6 +77,11 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
 /* or-ed into algo: run only the kernel that streams the cache and leave its per-split partials in the workspace
  * (out and lse are not written).  A measurement aid: it lets that kernel be timed without the merge kernel.   */
 #define WQ_DECODE_PARTIALS_ONLY 0x100
+/* or-ed into algo: every wavefront of the matrix-core kernel gets a fixed share of the token axis, so that the
+ * summation order, and with it every bit of the result, is the same on every run.  Without it the wavefronts of a
+ * workgroup take the blocks of the workgroup's share one by one as they get free (faster; results agree to
+ * rounding).                                                                                                   */
+#define WQ_DECODE_FIXED_SHARES 0x200
 
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
@@ -165,7 +170,8 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * out[b,h,:] = sum_t softmax_t(sm_scale * q[b,h].k^_t) v^_t over the 2-, 4-, 8- and 16-bit segments of
  * sequence b, one softmax over all of them, no mask (Sec. 2.1); head h reads KV head h/(Hq/Hkv).
  * Codes are expanded in registers; the token axis is split over num_splits workgroups per (b, KV head)
- * and merged by log-sum-exp in a fixed order (deterministic, no float atomics).
+ * and merged by log-sum-exp in a fixed order (no float atomics).  Which wavefront sums which tokens is fixed
+ * only under WQ_DECODE_FIXED_SHARES.
  * q [B,Hq,hd] device, element type q_dtype; out [B,Hq,hd] device fp32; lse [B,Hq] device fp32 or NULL
  * (natural-log sum of exp of the scaled logits).  num_splits 0 = automatic.  max_seq_tokens: host bound on
  * tokens of any one sequence (used only to size the automatic split).  algo: WQ_DECODE_AUTO picks the

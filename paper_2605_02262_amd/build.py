@@ -16,8 +16,9 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the quantizer's rounding sequence is part of the storage format: no contraction into fused multiply-add
 # the decode kernel keeps its matrix-core accumulators in ordinary vector registers: they are rescaled by vector
-# code, and accumulator-file copies around that would cost more than they save
-PER_FILE = {"wq_quantize.hip": ["-ffp-contract=off"], "wq_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+# code, and accumulator-file copies around that would cost more than they save; its single-lane ticket draws stay
+# as written (the wave-reduction rewrite of uniform atomics would read the result right away)
+PER_FILE = {"wq_quantize.hip": ["-ffp-contract=off"], "wq_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
 
 
 def sources():

@@ -152,9 +152,9 @@ size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group,
 int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens)
 {
     if (B <= 0 || Hkv <= 0) return 1;
-    // two resident workgroups per compute unit (256 CUs) is what the decode kernel's registers and LDS allow;
-    // more splits only add per-workgroup set-up.  Keep at least 1024 tokens per workgroup (256 per wavefront).
-    int64_t want = (512 + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
+    // one workgroup of eight wavefronts per compute unit (256 CUs) is what the decode kernel's registers allow;
+    // more splits only add per-workgroup set-up.  Keep at least 1024 tokens per workgroup.
+    int64_t want = (256 + (int64_t)B * Hkv - 1) / ((int64_t)B * Hkv);
     int64_t most = max_seq_tokens > 0 ? (max_seq_tokens + 1023) / 1024 : 1;
     if (want > most) want = most;
     if (want < 1) want = 1;
@@ -238,7 +238,7 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
                        Hq, kv->Hkv, WQ_MAX_REP);
-    const int balgo = algo & ~WQ_DECODE_PARTIALS_ONLY;
+    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
     if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
         return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
     if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)

@@ -25,7 +25,8 @@ struct DecodeArgs {
     int splits16, nparts;   // workgroups on the 16-bit segment; nparts = splits + splits16 partials per (b, KV head)
     int use_mfma;
     int mfma16;             // the matrix-core kernel also walks the 16-bit segment
-    int wgt[4];             // cost of one 32-token block of the 2-, 4-, 8- and 16-bit class, relative to each other
+    int fixed_shares;       // every wavefront of the matrix-core kernel gets a fixed share of its workgroup's range
+    float wgt[4], inv_wgt[4];   // cost of one 32-token block of the 2-, 4-, 8- and 16-bit class, relative to each other
     wq_packed_kv kv;
     float* part;            // [B][Hkv][nparts][rep][hd + 2]
     float* out;
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(256) void k_decode_generic(DecodeArgs a)
 
 // Matrix-core kernel: the quantized classes of one (split, KV head, sequence).
 template <int HD>
-__global__ __launch_bounds__(256) void k_decode_mfma(DecodeArgs a)
+__global__ __launch_bounds__(64 * WQ_WAVES) void k_decode_mfma(DecodeArgs a)
 {
     __shared__ __align__(16) unsigned char smem[sizeof(MfmaSmem<HD>)];
     wq_decode_mfma_body<HD>(a, smem);
@@ -368,7 +369,8 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
                      int num_splits, int algo, float* out, float* lse)
 {
     const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
-    algo &= ~WQ_DECODE_PARTIALS_ONLY;
+    const bool fixed_shares = (algo & WQ_DECODE_FIXED_SHARES) != 0;
+    algo &= ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
     DecodeArgs a;
     a.q = q;
     a.q_dtype = q_dtype;
@@ -384,10 +386,13 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.splits16 = (a.use_mfma && !a.mfma16) ? wq_decode_splits16(B, kv->cap16) : 0;
     a.nparts = a.splits + a.splits16;
     a.kv = *kv;
-    for (int c = 0; c < 4; c++) a.wgt[c] = WQ_BLOCK_COST[c];
+    a.fixed_shares = fixed_shares;
+    for (int c = 0; c < 4; c++) a.wgt[c] = (float)WQ_BLOCK_COST[c];
 #ifdef WQ_TUNE
-    if (getenv("WQ_WGT")) sscanf(getenv("WQ_WGT"), "%d,%d,%d,%d", &a.wgt[0], &a.wgt[1], &a.wgt[2], &a.wgt[3]);
+    if (getenv("WQ_WGT")) sscanf(getenv("WQ_WGT"), "%f,%f,%f,%f", &a.wgt[0], &a.wgt[1], &a.wgt[2], &a.wgt[3]);
+    if (getenv("WQ_FIXED")) a.fixed_shares = atoi(getenv("WQ_FIXED"));
 #endif
+    for (int c = 0; c < 4; c++) a.inv_wgt[c] = 1.0f / a.wgt[c];
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
     a.out = out;
 #ifdef WQ_TIMELINE
@@ -396,11 +401,13 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.lse = lse;
     const dim3 blk(256);
     const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16 > 0 ? a.splits16 : 1, kv->Hkv, B);
+    // the matrix-core kernel maps workgroups (of WQ_WAVES wavefronts) to units itself
+    const dim3 grid_m((unsigned)a.splits * (unsigned)kv->Hkv * (unsigned)B), blk_m(64 * WQ_WAVES);
     const int tslot = (int)(ctx->ev_calls % WQ_TIMING_RING);
     if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot], ctx->stream);
     if (kv->hd == 128) {
         if (a.use_mfma) {
-            hipLaunchKernelGGL(k_decode_mfma<128>, grid_q, blk, 0, ctx->stream, a);
+            hipLaunchKernelGGL(k_decode_mfma<128>, grid_m, blk_m, 0, ctx->stream, a);
             if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
             if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<128>, grid_16, blk, 0, ctx->stream, a);
         } else {
@@ -409,7 +416,7 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
         }
     } else {
         if (a.use_mfma) {
-            hipLaunchKernelGGL(k_decode_mfma<64>, grid_q, blk, 0, ctx->stream, a);
+            hipLaunchKernelGGL(k_decode_mfma<64>, grid_m, blk_m, 0, ctx->stream, a);
             if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
             if (a.splits16 > 0) hipLaunchKernelGGL(k_decode_generic<64>, grid_16, blk, 0, ctx->stream, a);
         } else {

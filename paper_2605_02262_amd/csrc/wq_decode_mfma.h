@@ -28,8 +28,8 @@
 #pragma once
 
 #ifdef WQ_TIMELINE   // development aid: per-workgroup phase time stamps (100 MHz clock) at the end of the workspace
-#define WQ_STAMP(k) do { if (a.dbg && threadIdx.x == 0) a.dbg[(((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (k)] = wall_clock64(); } while (0)
-#define WQ_WSTAMP(k, val) do { if (a.dbg && (threadIdx.x & 63) == 0) a.dbg[(((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 + (threadIdx.x >> 6) * 6 + (k)] = (val); } while (0)
+#define WQ_STAMP(k) do { if (a.dbg && threadIdx.x == 0) a.dbg[(int64_t)blockIdx.x * 64 + (k)] = wall_clock64(); } while (0)
+#define WQ_WSTAMP(k, val) do { if (a.dbg && (threadIdx.x & 63) == 0) a.dbg[(int64_t)blockIdx.x * 64 + 8 + (threadIdx.x >> 6) * 6 + (k)] = (val); } while (0)
 #else
 #define WQ_STAMP(k) do { } while (0)
 #define WQ_WSTAMP(k, val) do { } while (0)
@@ -173,6 +173,7 @@ struct WaveState {
 // 32-token blocks in flight per wavefront and class: enough bytes to keep the memory system busy while a block
 // is being worked on (a 2-bit block is 2.5 KB, an 8-bit block 8.5 KB)
 constexpr int WQ_D2 = 4, WQ_D4 = 3, WQ_D8 = 2;
+constexpr int WQ_WAVES = 8;            // wavefronts per workgroup: one workgroup per compute unit, two wavefronts per SIMD
 constexpr float WQ_MAX_SLACK = 8.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
 constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
 
@@ -180,12 +181,15 @@ template <int HD>
 struct MfmaSmem {
     union {
         struct {
-            uint32_t meta[4][2][64];              // per wave: K and V metadata words of the current block
-            uint16_t vt[4][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
+            uint32_t meta[WQ_WAVES][2][64];              // per wave: K and V metadata words of the current block
+            uint16_t vt[WQ_WAVES][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
         } run;
-        float O[4][WQ_MAX_REP][HD];               // per-wave numerators for the merge (after the loops)
+        float O[WQ_WAVES][WQ_MAX_REP][HD];               // per-wave numerators for the merge (after the loops)
     };
-    float ml[4][WQ_MAX_REP][2];
+    U4 bq[4][HD / 32][64];                               // query operands of the four classes (index 3 = 16-bit segment), per lane
+    float qx[4][2][64];                                  // ... with the head's power of two and the group's query sum
+    float ml[WQ_WAVES][WQ_MAX_REP][2];
+    unsigned next_ticket;                                // the workgroup's block counter
 };
 
 
@@ -257,6 +261,98 @@ __device__ __forceinline__ void build_q_operands(const DecodeArgs& a, int b, int
     }
 }
 
+// The wavefronts of a workgroup walk the same classes, so the workgroup builds the operands of all four once, one
+// class per wavefront (the first four), and keeps them in LDS.
+template <int HD>
+__device__ __forceinline__ void stage_q_operands(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int wave, bool bf16seg)
+{
+    constexpr int NK = HD / 32;
+    const int lane = threadIdx.x & 63;
+    U4 Bq[NK];
+    float qexp, qsum;
+    if (wave >= 4) return;
+    if (wave == 0) build_q_operands<HD, 0>(a, b, kvh, false, Bq, qexp, qsum);
+    else if (wave == 1) build_q_operands<HD, 1>(a, b, kvh, false, Bq, qexp, qsum);
+    else if (wave == 2) build_q_operands<HD, 2>(a, b, kvh, false, Bq, qexp, qsum);
+    else build_q_operands<HD, 3>(a, b, kvh, bf16seg, Bq, qexp, qsum);
+#pragma unroll
+    for (int r = 0; r < NK; r++) sm.bq[wave][r][lane] = Bq[r];
+    sm.qx[wave][0][lane] = qexp;
+    sm.qx[wave][1][lane] = qsum;
+}
+
+template <int HD>
+__device__ __forceinline__ void fetch_q_operands(const MfmaSmem<HD>& sm, int c, U4* Bq, float& qexp, float& qsum)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int r = 0; r < HD / 32; r++) Bq[r] = sm.bq[c][r][lane];
+    qexp = sm.qx[c][0][lane];
+    qsum = sm.qx[c][1][lane];
+}
+
+// ---- shares of the token axis ---------------------------------------------------------------------------------
+// A workgroup owns a contiguous cost range of the stream [16-bit | 8-bit | 4-bit | 2-bit] of its (sequence, KV
+// head).  Its wavefronts do not run at the same speed (of the two that share a SIMD the older one gets more issue
+// slots and more of the memory system, and the classes differ), and one that is done early cannot be replaced: the
+// launch is over when the slowest wavefront is.  So the 32-token blocks of the range are handed out in stream
+// order through a counter in LDS (a ticket = one block): whoever is free takes the next one.  A wavefront holds a
+// range of tickets (normally one) and keeps tickets that stand for blocks of a later class until it gets there.
+// The ticket that replaces a spent one is drawn at the start of a block's arithmetic and read at its end; LDS
+// operations have a counter of their own, so the draw never waits for the block loads that are in flight.
+// With WQ_DECODE_FIXED_SHARES the range is divided among the wavefronts by cost instead and no tickets are drawn.
+struct Tickets {
+    unsigned* ctr;      // the workgroup's counter (LDS)
+    unsigned held, end; // tickets held: [held, end)
+    bool spent;         // none left: another one is due
+};
+
+// lane 0 draws n tickets; the first one's value is valid in lane 0 once the LDS operation has returned
+__device__ __forceinline__ unsigned draw_tickets(unsigned* ctr, unsigned n)
+{
+    unsigned v = 0;
+    if ((threadIdx.x & 63) == 0) v = __hip_atomic_fetch_add(ctr, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return v;
+}
+
+__device__ __forceinline__ unsigned ticket_value(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+
+struct BlockSrc {
+    int cur, end;            // this wavefront's own blocks of the class
+    int pool_first;          // first block of the class's part of the workgroup's pool
+    unsigned tk_lo, tk_hi;   // tickets that stand for those pool blocks
+};
+
+// draws n tickets and waits for them (filling the pipeline at the start of a class)
+__device__ __forceinline__ void settle_tickets(Tickets& t, unsigned n)
+{
+    if (t.spent) {
+        t.held = ticket_value(draw_tickets(t.ctr, n));
+        t.end = t.held + n;
+        t.spent = false;
+    }
+}
+
+__device__ __forceinline__ bool has_blocks(const BlockSrc& s, Tickets& t, unsigned fill)
+{
+    if (s.cur < s.end) return true;
+    if (s.tk_lo >= s.tk_hi) return false;
+    settle_tickets(t, fill);
+    return t.held < s.tk_hi;
+}
+
+// next block of the class for this wavefront, or -1 (and then -1 on every later call for the class)
+__device__ __forceinline__ int next_block(BlockSrc& s, Tickets& t, unsigned fill)
+{
+    if (s.cur < s.end) return s.cur++;
+    if (s.tk_lo >= s.tk_hi) return -1;
+    settle_tickets(t, fill);
+    if (t.held >= s.tk_hi) return -1;        // a block of a later class, or none: keep the tickets
+    const unsigned v = t.held++;
+    t.spent = t.held == t.end;
+    return s.pool_first + (int)(v - s.tk_lo);
+}
+
 template <int HD, int BITS>
 struct Frag {
     static constexpr int KDW = (HD / 4) * BITS / 32;        // dwords of K codes per lane per 16-token tile
@@ -287,12 +383,12 @@ __device__ __forceinline__ void load_dwords(const uint32_t* __restrict__ p, uint
     }
 }
 
-// One class of one (sequence, KV head): this wavefront's share of its 32-token blocks.
+// One class of one (sequence, KV head): this wavefront's share of its 32-token blocks (len tokens from token slot
+// tok_base of the class buffers).
 template <int HD, int BITS, int DEPTH>
-__device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
-                                                float c_log2, WaveState<HD>& st)
+__device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int len, int tok_base, BlockSrc& src,
+                                                Tickets& tk, float c_log2, WaveState<HD>& st)
 {
-    static_assert(DEPTH >= 1 && DEPTH <= 4, "pipeline slots of the short block");
     constexpr int C = BITS == 2 ? 0 : (BITS == 4 ? 1 : 2);
     constexpr int NK = HD / 32;                    // k-steps of the logit product per 16-token tile
     constexpr int CT = HD / 16;                    // channel tiles of the value product
@@ -300,23 +396,9 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane >> 4, col = lane & 15, g = col >> 3;
 
-    if (blk_lo >= blk_hi) return;
+    if (!has_blocks(src, tk, DEPTH)) return;
     const wq_packed_kv& kv = a.kv;
-    const int len = kv.cls_len[C][b];
-
-    U4 Bqw[NK];
-    float qexp, qsum;
-    build_q_operands<HD, C>(a, b, kvh, false, Bqw, qexp, qsum);
-    half8 Bq[NK];
-#pragma unroll
-    for (int r = 0; r < NK; r++) Bq[r] = __builtin_bit_cast(half8, Bqw[r]);
-    // logits come out of the matrix cores as 2^-24 * sum q' code; fold 2^24, the head's power of two and
-    // sm_scale*log2(e) into one constant, and pre-divide the m-term by 2^24 so both terms share it.
-    const float cexp = c_log2 * qexp * 16777216.0f;
-    const float qs = qsum * (1.0f / 16777216.0f);
-
     const int64_t cap = kv.cap[C];
-    const int64_t tok_base = kv.cls_off[C][b];
     const uint8_t* kbase = static_cast<const uint8_t*>(kv.codes[C]) + ((int64_t)kvh * cap + tok_base) * HD * BITS / 8 + lane * (F::KDW * 4);
     const uint8_t* vbase = static_cast<const uint8_t*>(kv.codes[C]) + (((int64_t)kv.Hkv + kvh) * cap + tok_base) * HD * BITS / 8 + lane * (F::VDW * 4);
     const uint32_t* kmeta = static_cast<const uint32_t*>(kv.meta[C]) + ((int64_t)kvh * cap + tok_base) * 2 + lane;
@@ -333,14 +415,44 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
         f.vm = vmeta[(int64_t)blk * 64];
     };
 
+    // software pipeline: DEPTH blocks in flight per wavefront; the first loads go out before anything else
+    F f[DEPTH];
+    int bi[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) {
+        bi[d] = next_block(src, tk, DEPTH - d);
+        if (bi[d] >= 0) load(bi[d], f[d]);
+    }
+    U4 Bqw[NK];
+    float qexp, qsum;
+    fetch_q_operands<HD>(sm, C, Bqw, qexp, qsum);
+    half8 Bq[NK];
+#pragma unroll
+    for (int r = 0; r < NK; r++) Bq[r] = __builtin_bit_cast(half8, Bqw[r]);
+    // logits come out of the matrix cores as 2^-24 * sum q' code; fold 2^24, the head's power of two and
+    // sm_scale*log2(e) into one constant, and pre-divide the m-term by 2^24 so both terms share it.
+    const float cexp = c_log2 * qexp * 16777216.0f;
+    const float qs = qsum * (1.0f / 16777216.0f);
+
+    // added to the logits: zero, except for the tokens past the end of the sequence's last block of the class
+    // (the last block this wavefront gets: shares and tickets go up the stream), which get -inf
+    float pen[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // partial sums per slot register v: its weights carry 2^-shift(v) (folded into the exponent), undone after the loop
     float lv[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f}, ms[4];
 #pragma unroll
     for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v);
 
-    // one 32-token block; PARTIAL: the sequence's last block of the class, tokens past its end are masked out
-    auto compute = [&](int blk, const F& f, auto partial) {
-        constexpr bool PARTIAL = decltype(partial)::value;
+    auto compute = [&](int blk, const F& f) {
+        const bool redraw = tk.spent;
+        unsigned drawn = 0;
+        if (redraw) drawn = draw_tickets(tk.ctr, 1u);
+        if (blk * 32 + 32 > len) {
+            const int nv = len - blk * 32;         // valid tokens in this block
+#pragma unroll
+            for (int t = 0; t < 2; t++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) pen[4 * t + i] = (16 * t + 4 * j + i >= nv) ? -INFINITY : 0.f;
+        }
         // ---- scales and minima: one word per lane in, the lane's 4 tokens x 2 tiles x {K,V} out ----
         smeta[lane] = f.km;
         smeta[64 + lane] = f.vm;
@@ -367,17 +479,9 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
             for (int r = 0; r < NK; r++) acc = mfma(k_operand<BITS>(f.k[t], r), Bq[r], acc);
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const float y = fmaf(f16lo(kw[4 * t + i]), acc[i], fmaf(f16hi(kw[4 * t + i]), qs, 0.0f));
+                const float y = fmaf(f16lo(kw[4 * t + i]), acc[i], fmaf(f16hi(kw[4 * t + i]), qs, pen[4 * t + i]));
                 x[4 * t + i] = y + ror8(y);
             }
-        }
-        if constexpr (PARTIAL) {
-            const int nv = len - blk * 32;         // valid tokens in this block
-#pragma unroll
-            for (int t = 0; t < 2; t++)
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    if (16 * t + 4 * j + i >= nv) x[4 * t + i] = -INFINITY;
         }
         // ---- reference exponent: touch the other lane groups only when some logit is far above it ----
         float lm = max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
@@ -415,31 +519,23 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
         // ---- values ----
 #pragma unroll
         for (int ct = 0; ct < CT; ct++) st.O[ct] = mfma(v_operand<BITS>(f.v, ct), Bp, st.O[ct]);
+        const unsigned got = ticket_value(drawn);      // read on every path: nothing is left pending at the loop edge
+        if (redraw) {
+            tk.held = got;
+            tk.end = got + 1u;
+            tk.spent = false;
+        }
     };
 
-    // software pipeline: DEPTH blocks in flight per wavefront
-    F f[DEPTH];
-#pragma unroll
-    for (int d = 0; d < DEPTH; d++)
-        if (blk_lo + d < blk_hi) load(blk_lo + d, f[d]);
-    // only the sequence's last block of the class can be short; it gets an instance of its own after the loop,
-    // so that the loop carries no masking
-    const int full_hi = blk_hi * 32 > len ? blk_hi - 1 : blk_hi;
-    for (int blk = blk_lo; blk < full_hi; blk += DEPTH) {
+    while (bi[0] >= 0) {
 #pragma unroll
         for (int d = 0; d < DEPTH; d++) {
-            if (blk + d < full_hi) {
-                compute(blk + d, f[d], std::false_type{});
-                if (blk + d + DEPTH < blk_hi) load(blk + d + DEPTH, f[d]);
+            if (bi[d] >= 0) {
+                compute(bi[d], f[d]);
+                bi[d] = next_block(src, tk, 1u);
+                if (bi[d] >= 0) load(bi[d], f[d]);
             }
         }
-    }
-    if (full_hi < blk_hi) {
-        const int slot = (full_hi - blk_lo) % DEPTH;       // the short block's data sits in its pipeline slot
-        if (DEPTH > 1 && slot == 1) f[0] = f[DEPTH > 1 ? 1 : 0];
-        if (DEPTH > 2 && slot == 2) f[0] = f[DEPTH > 2 ? 2 : 0];
-        if (DEPTH > 3 && slot == 3) f[0] = f[DEPTH > 3 ? 3 : 0];
-        compute(full_hi, f[0], std::true_type{});
     }
 #pragma unroll
     for (int v = 0; v < 4; v++) {
@@ -466,27 +562,29 @@ __device__ __forceinline__ floatx4 mfma16(uint32_t a0, uint32_t a1, uint32_t a2,
 // the bf16 instruction with the exact bf16 query and the weights split into two bf16 terms (p = hi + lo);
 // fp16 caches use the f16 instruction.  Accumulators are in true units here (no 2^-24).
 template <int HD, bool BF>
-__device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int blk_lo, int blk_hi,
-                                                float c_log2, WaveState<HD>& st)
+__device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int len, int first_row, BlockSrc& src,
+                                                Tickets& tk, float c_log2, WaveState<HD>& st)
 {
     constexpr int NK = HD / 32, CT = HD / 16, PITCH = HD / 2 + VT_PAD, KDW = HD / 8;
-    if (blk_lo >= blk_hi) return;
+    if (!has_blocks(src, tk, 1u)) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = lane >> 4, col = lane & 15;
     const wq_packed_kv& kv = a.kv;
-    const int len = kv.len16[b];
-    const int64_t row0 = kv.off16[b];
+    const int64_t row0 = first_row;
     const int64_t rstride = (int64_t)kv.Hkv * HD;
     const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16) + (int64_t)kvh * HD;
     const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16) + (int64_t)kvh * HD;
     U4 Bq[NK];
     float qexp, qsum;
-    build_q_operands<HD, 3>(a, b, kvh, BF, Bq, qexp, qsum);
+    fetch_q_operands<HD>(sm, 3, Bq, qexp, qsum);
     const float cexp = c_log2 * qexp;
     uint16_t* vt = &sm.run.vt[wave][0][0];
 
-    for (int blk = blk_lo; blk < blk_hi; blk++) {
+    for (int blk = next_block(src, tk, 1u); blk >= 0; blk = next_block(src, tk, 1u)) {
         const int nv = len - blk * 32;
+        const bool redraw = tk.spent;
+        unsigned drawn = 0;
+        if (redraw) drawn = draw_tickets(tk.ctr, 1u);
         // ---- all loads of the block up front: one memory round trip per block ----
         uint32_t kd[2][KDW];
 #pragma unroll
@@ -592,66 +690,100 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();          // the buffer is overwritten next
         }
+        const unsigned got = ticket_value(drawn);
+        if (redraw) {
+            tk.held = got;
+            tk.end = got + 1u;
+            tk.spent = false;
+        }
     }
 }
 
-// ceil((x - base) / w) clamped to [0, n]
-__device__ __forceinline__ int range_edge(uint32_t x, uint32_t base, uint32_t w, int n)
+// Shares are laid out on a cost axis in float arithmetic: every wavefront evaluates the same expressions for the
+// same boundary, so neighbouring shares meet exactly whatever the rounding, and a division-free float mapping is
+// monotone, which is all that the partition needs.
+// first block of a class (n blocks of cost w each, starting at cost `base`) at or after cost x
+__device__ __forceinline__ int range_edge(float x, float base, float inv_w, int n)
 {
-    if (x <= base) return 0;
-    const uint32_t k = (x - base + w - 1) / w;
-    return k > (uint32_t)n ? n : (int)k;
+    const float v = ceilf((x - base) * inv_w);
+    return v <= 0.f ? 0 : (v >= (float)n ? n : (int)v);
 }
 
 template <int HD>
 __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 {
     MfmaSmem<HD>& sm = *reinterpret_cast<MfmaSmem<HD>*>(smem_raw);
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    // consecutive workgroups go to different (sequence, KV head) units: the units' tables and queries are then
+    // read by all XCDs alike, and the workgroups of one unit do not start in a burst on neighbouring compute units
+    const int units = a.B * a.kv.Hkv;
+    const int unit = (int)(blockIdx.x % (unsigned)units), split = (int)(blockIdx.x / (unsigned)units);
+    const int kvh = unit % a.kv.Hkv, b = unit / a.kv.Hkv;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
     constexpr int CT = HD / 16;
     const bool bf16seg = a.kv.dtype16 == WQ_BF16;
     WQ_STAMP(0);
 
-    // ---- this wavefront's cost-balanced share of the stream [16-bit | 2-bit | 4-bit | 8-bit] of (b, kvh) ----
-    int lo[4], hi[4];
+    // ---- the sequence's tables first (their loads are in flight while the query operands are built) ----
+    int cls_len[4], cls_off[4];
+#pragma unroll
+    for (int c = 0; c < 3; c++) {
+        cls_len[c] = a.kv.cls_len[c][b];
+        cls_off[c] = a.kv.cls_off[c][b];
+    }
+    cls_len[3] = a.kv.len16[b];
+    cls_off[3] = a.kv.off16[b];
+    if (tid == 0) sm.next_ticket = 0u;
+    // ---- the query operands of all classes, one class per wavefront ----
+    stage_q_operands<HD>(a, sm, b, kvh, wave, bf16seg);
+
+    // ---- the workgroup's range of the stream [16-bit | 8-bit | 4-bit | 2-bit] of (b, kvh), and this wavefront's
+    //      fixed share of it (none unless the launch asks for fixed shares: then there is no pool) ----
+    Tickets tk;
+    tk.ctr = &sm.next_ticket;
+    tk.held = tk.end = 0u;
+    tk.spent = true;                       // the first tickets are drawn when the first class is entered
+    BlockSrc src[4];
     {
-        // cost of one 32-token block of each class relative to the others, as measured on MI355X: the loop is
-        // bound by issue and latency per block more than by bytes, so the shares are balanced by block cost
-        const int wgt[4] = {a.wgt[0], a.wgt[1], a.wgt[2], a.wgt[3]};
         int nb[4];
 #pragma unroll
-        for (int c = 0; c < 3; c++) nb[c] = (a.kv.cls_len[c][b] + 31) >> 5;
-        nb[3] = a.mfma16 ? (a.kv.len16[b] + 31) >> 5 : 0;
-        const int order[4] = {3, 0, 1, 2};
-        // 32-bit arithmetic: class capacities are limited to 2^26 tokens, so the total stays below 2^32
-        uint32_t total = 0;
+        for (int c = 0; c < 3; c++) nb[c] = (cls_len[c] + 31) >> 5;
+        nb[3] = a.mfma16 ? (cls_len[3] + 31) >> 5 : 0;
+        float total = 0.f;
 #pragma unroll
-        for (int c = 0; c < 4; c++) total += (uint32_t)nb[c] * (uint32_t)wgt[c];
-        const uint32_t ns = (uint32_t)a.splits * 4u, s = (uint32_t)split * 4u + (uint32_t)wave;
-        const uint32_t qd = total / ns, rm = total - qd * ns;          // total*s/ns without a wide product
-        const uint32_t x0 = qd * s + rm * s / ns, x1 = qd * (s + 1) + rm * (s + 1) / ns;
-        uint32_t base = 0;
+        for (int c = 0; c < 4; c++) total += (float)nb[c] * a.wgt[c];
+        const int S = a.splits;
+        const float rS = 1.0f / (float)S, rnw = 1.0f / (float)WQ_WAVES;
+        const float G0 = total * ((float)split * rS), G1 = total * ((float)(split + 1) * rS);     // the workgroup's range
+        const float Gs = a.fixed_shares ? G1 : G0;                                                // [Gs, G1) is its pool
+        const float x0 = G0 + (Gs - G0) * ((float)wave * rnw), x1 = G0 + (Gs - G0) * ((float)(wave + 1) * rnw);
+        float base = 0.f;
+        unsigned t = 0;
 #pragma unroll
-        for (int k = 0; k < 4; k++) {
-            const int c = order[k];
-            lo[c] = range_edge(x0, base, (uint32_t)wgt[c], nb[c]);
-            hi[c] = range_edge(x1, base, (uint32_t)wgt[c], nb[c]);
-            base += (uint32_t)nb[c] * (uint32_t)wgt[c];
+        for (int c = 3; c >= 0; c--) {
+            const float iw = a.inv_wgt[c];
+            const int e0 = split == 0 ? 0 : range_edge(G0, base, iw, nb[c]);
+            const int e1 = split == S - 1 ? nb[c] : range_edge(G1, base, iw, nb[c]);
+            const int pl = a.fixed_shares ? e1 : e0;
+            src[c].cur = wave == 0 ? e0 : range_edge(x0, base, iw, nb[c]);
+            src[c].end = wave == WQ_WAVES - 1 ? pl : range_edge(x1, base, iw, nb[c]);
+            if (!a.fixed_shares) src[c].cur = src[c].end = 0;
+            src[c].pool_first = pl;
+            src[c].tk_lo = t;
+            t += (unsigned)(e1 - pl);
+            src[c].tk_hi = t;
+            base += (float)nb[c] * a.wgt[c];
         }
     }
+    __syncthreads();                       // the operands of all classes are in LDS, the block counter is zero
 
     WQ_STAMP(1);
 #ifdef WQ_TIMELINE
     if (a.dbg && threadIdx.x == 0) {
-        const int64_t wg = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-        a.dbg[wg * 32 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
-        a.dbg[wg * 32 + 7] = __builtin_amdgcn_s_getreg((31 << 11) | 20);   // XCC_ID
+        a.dbg[(int64_t)blockIdx.x * 64 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
+        a.dbg[(int64_t)blockIdx.x * 64 + 7] = -(long long)__builtin_readcyclecounter();
     }
 #endif
-    WQ_STAMP(2);
-    WQ_STAMP(3);
 
     WaveState<HD> st;
 #pragma unroll
@@ -661,23 +793,25 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     st.accM = 0.f;
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
     WQ_WSTAMP(0, wall_clock64());
-    WQ_WSTAMP(5, ((long long)(hi[3] - lo[3]) << 48) | ((long long)(hi[0] - lo[0]) << 32) | ((long long)(hi[1] - lo[1]) << 16) | (long long)(hi[2] - lo[2]));
     if (bf16seg)
-        walk_seg16_mfma<HD, true>(a, sm, b, kvh, lo[3], hi[3], c_log2, st);
+        walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st);
     else
-        walk_seg16_mfma<HD, false>(a, sm, b, kvh, lo[3], hi[3], c_log2, st);
+        walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st);
     // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
     WQ_WSTAMP(1, wall_clock64());
-    walk_class_mfma<HD, 2, WQ_D2>(a, sm, b, kvh, lo[0], hi[0], c_log2, st);
+    walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, cls_len[2], cls_off[2], src[2], tk, c_log2, st);
     WQ_WSTAMP(2, wall_clock64());
-    walk_class_mfma<HD, 4, WQ_D4>(a, sm, b, kvh, lo[1], hi[1], c_log2, st);
+    walk_class_mfma<HD, 4, WQ_D4>(a, sm, b, kvh, cls_len[1], cls_off[1], src[1], tk, c_log2, st);
     WQ_WSTAMP(3, wall_clock64());
-    walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, lo[2], hi[2], c_log2, st);
+    walk_class_mfma<HD, 2, WQ_D2>(a, sm, b, kvh, cls_len[0], cls_off[0], src[0], tk, c_log2, st);
     WQ_WSTAMP(4, wall_clock64());
 
     WQ_STAMP(4);
+#ifdef WQ_TIMELINE
+    if (a.dbg && threadIdx.x == 0) a.dbg[(int64_t)blockIdx.x * 64 + 7] += (long long)__builtin_readcyclecounter();
+#endif
     // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
     float l = st.l, am = st.accM;
     l += __shfl_xor(l, 16, 64);
@@ -697,16 +831,18 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         sm.ml[wave][h][1] = l;
     }
     __syncthreads();
-    // ---- merge the four waves, write the partial (m in natural-log units) ----
+    // ---- merge the wavefronts, write the partial (m in natural-log units) ----
     const int64_t pstride = (int64_t)a.rep * (HD + 2);
-    float* pbase = a.part + (((int64_t)b * a.kv.Hkv + kvh) * a.nparts) * pstride;
+    float* pbase = a.part + ((int64_t)unit * a.nparts) * pstride;
     float* out = pbase + split * pstride;
-    for (int idx = tid; idx < a.rep * HD; idx += 256) {
+    for (int idx = tid; idx < a.rep * HD; idx += 64 * WQ_WAVES) {
         const int r = idx / HD, ch = idx - r * HD;
-        const float M = fmaxf(fmaxf(sm.ml[0][r][0], sm.ml[1][r][0]), fmaxf(sm.ml[2][r][0], sm.ml[3][r][0]));
+        float M = sm.ml[0][r][0];
+#pragma unroll
+        for (int w = 1; w < WQ_WAVES; w++) M = fmaxf(M, sm.ml[w][r][0]);
         float num = 0.f, L = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; w++) {
+        for (int w = 0; w < WQ_WAVES; w++) {
             const float mw = sm.ml[w][r][0];
             const float s = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
             num = fmaf(sm.O[w][r][ch], s, num);

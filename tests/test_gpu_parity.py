@@ -139,3 +139,19 @@ def test_scores_pairwise_on_matrix_cores(dtype):
     want = O.window_scores(Ev, Et, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pairwise")
     H.assert_scores_close(s_mfma, want)
     H.assert_scores_close(s_pool, want)
+
+
+def test_decode_fixed_shares_is_reproducible_and_agrees_with_block_pool():
+    """WQ_DECODE_FIXED_SHARES: the same bits on every run; the default (blocks handed out as wavefronts get free)
+    sums in a run-dependent order and agrees to rounding.  Both are checked against the oracle."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    bt = synth.batch(synth.workload(1))
+    fixed = W.DECODE_MFMA | W.DECODE_FIXED_SHARES
+    g, o, _ = _check(bt, H, splits=3, algo=fixed)
+    first = g.out.clone()
+    for _ in range(3):
+        g2 = H.run_gpu(bt, splits=3, algo=fixed)
+        assert torch.equal(g2.out, first)
+    g3, _, _ = _check(bt, H, splits=3, algo=W.DECODE_MFMA)
+    assert H.attention_error(g3.out.cpu().numpy(), first.cpu().numpy().astype(np.float64)) <= H.ATTN_TOL
