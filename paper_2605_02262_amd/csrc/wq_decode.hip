@@ -25,6 +25,8 @@ struct DecodeArgs {
     int splits16, nparts;   // workgroups on the 16-bit segment; nparts = splits + splits16 partials per (b, KV head)
     int use_mfma;
     int mfma16;             // the matrix-core kernel also walks the 16-bit segment
+    int fused;              // the matrix-core kernel merges the splits itself (last workgroup per (b, KV head))
+    unsigned* arrive;       // [B*Hkv] arrival counters, WQ_ARRIVE_STRIDE words apart, zero between launches
     int fixed_shares;       // every wavefront of the matrix-core kernel gets a fixed share of its workgroup's range
     float wgt[4], inv_wgt[4];   // cost of one 32-token block of the 2-, 4-, 8- and 16-bit class, relative to each other
     wq_packed_kv kv;
@@ -387,6 +389,14 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.nparts = a.splits + a.splits16;
     a.kv = *kv;
     a.fixed_shares = fixed_shares;
+    a.arrive = reinterpret_cast<unsigned*>(ctx->ws + 256);
+    // one launch does it all when the matrix-core kernel walks every segment, the counters fit the workspace
+    // header and the splits' weights fit the merge buffer in LDS
+    a.fused = a.use_mfma && a.mfma16 && !partials_only && (int64_t)B * kv->Hkv <= WQ_MAX_ARRIVE &&
+              2 * a.nparts * a.rep <= WQ_WAVES * WQ_MAX_REP * kv->hd;
+#ifdef WQ_TUNE
+    if (getenv("WQ_FUSE")) a.fused = a.fused && atoi(getenv("WQ_FUSE"));
+#endif
     for (int c = 0; c < 4; c++) a.wgt[c] = (float)WQ_BLOCK_COST[c];
 #ifdef WQ_TUNE
     if (getenv("WQ_WGT")) sscanf(getenv("WQ_WGT"), "%f,%f,%f,%f", &a.wgt[0], &a.wgt[1], &a.wgt[2], &a.wgt[3]);
@@ -424,7 +434,7 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
             if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot + 1], ctx->stream);
         }
     }
-    if (!partials_only)
+    if (!partials_only && !a.fused)
         hipLaunchKernelGGL(k_combine, dim3(Hq, B), dim3(128), 0, ctx->stream, a.part, Hq, a.rep, a.nparts, kv->hd, out, lse);
     if (ctx->timing) ctx->ev_calls++;
     WQ_HIP_CHECK(ctx, hipGetLastError());

@@ -190,6 +190,7 @@ struct MfmaSmem {
     float qx[4][2][64];                                  // ... with the head's power of two and the group's query sum
     float ml[WQ_WAVES][WQ_MAX_REP][2];
     unsigned next_ticket;                                // the workgroup's block counter
+    int last;                                            // this workgroup is the last of its (sequence, KV head) to finish
 };
 
 
@@ -822,8 +823,12 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
-#pragma unroll
-            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
+            float4 v;
+            v.x = fmaf(st.O[ct][0], 16777216.0f, am);
+            v.y = fmaf(st.O[ct][1], 16777216.0f, am);
+            v.z = fmaf(st.O[ct][2], 16777216.0f, am);
+            v.w = fmaf(st.O[ct][3], 16777216.0f, am);
+            *reinterpret_cast<float4*>(&sm.O[wave][h][16 * ct + 4 * j]) = v;
         }
     }
     if (j == 0 && g == 0) {
@@ -848,13 +853,81 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             num = fmaf(sm.O[w][r][ch], s, num);
             L = fmaf(sm.ml[w][r][1], s, L);
         }
-        out[r * (HD + 2) + ch] = num;
+        // device-scope stores go through to memory (every XCD has an L2 of its own), so that no cache write-back
+        // is needed to hand the partial to the workgroup that merges the splits
+        __hip_atomic_store(out + r * (HD + 2) + ch, num, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ch == 0) {
-            out[r * (HD + 2) + HD] = M * 0.6931471805599453f;
-            out[r * (HD + 2) + HD + 1] = L;
+            __hip_atomic_store(out + r * (HD + 2) + HD, M * 0.6931471805599453f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(out + r * (HD + 2) + HD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     WQ_STAMP(5);
+    if (!a.fused) return;
+
+    // ---- the last workgroup of (b, kvh) to get here merges the partials of all splits, in split order ----
+    // Every thread waits until its part of the partial has reached memory before the workgroup reports in; the
+    // last one reads the others' partials from memory as well.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned old = __hip_atomic_fetch_add(a.arrive + unit * WQ_ARRIVE_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm.last = old == (unsigned)a.splits - 1u;
+    }
+    __syncthreads();
+    if (!sm.last) return;
+    if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    const int np = a.nparts;
+    float* wts = &sm.O[0][0][0];                   // [rep][np]: m_s, then the weights e^{m_s - M}
+    float* lsum = wts + a.rep * np;                // [rep][np]: l_s
+    // all loads first (one round trip): this thread's channels of the first PRE splits, then the (m, l) pairs
+    constexpr int PRE = 16, PER = (WQ_MAX_REP * HD + 64 * WQ_WAVES - 1) / (64 * WQ_WAVES);
+    float pre[PER][PRE];
+#pragma unroll
+    for (int u = 0; u < PER; u++) {
+        const int idx = tid + u * 64 * WQ_WAVES;
+        const int r = idx / HD, ch = idx - r * HD;
+#pragma unroll
+        for (int k = 0; k < PRE; k++)
+            pre[u][k] = (idx < a.rep * HD && k < np)
+                            ? __hip_atomic_load(pbase + (int64_t)k * pstride + r * (HD + 2) + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                            : 0.f;
+    }
+    for (int idx = tid; idx < a.rep * np; idx += 64 * WQ_WAVES) {
+        const int r = idx / np, s = idx - r * np;
+        const float* src = pbase + s * pstride + r * (HD + 2) + HD;
+        wts[idx] = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lsum[idx] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (tid < a.rep) {                             // per head: max, then weights, then the denominator (split order)
+        float M = -INFINITY;
+        for (int s = 0; s < np; s++) M = fmaxf(M, wts[tid * np + s]);
+        float L = 0.f;
+        for (int s = 0; s < np; s++) {
+            const float ms = wts[tid * np + s];
+            const float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
+            wts[tid * np + s] = w;
+            L = fmaf(lsum[tid * np + s], w, L);
+        }
+        sm.ml[0][tid][0] = M;
+        sm.ml[0][tid][1] = L;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PER; u++) {
+        const int idx = tid + u * 64 * WQ_WAVES;
+        if (idx >= a.rep * HD) break;
+        const int r = idx / HD, ch = idx - r * HD;
+        const float* src = pbase + r * (HD + 2) + ch;
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < PRE; k++) acc = fmaf(pre[u][k], k < np ? wts[r * np + k] : 0.f, acc);
+        for (int s = PRE; s < np; s++) acc = fmaf(__hip_atomic_load(src + (int64_t)s * pstride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wts[r * np + s], acc);
+        const float L = sm.ml[0][r][1];
+        const int hq = kvh * a.rep + r;
+        a.out[((int64_t)b * a.Hq + hq) * HD + ch] = L > 0.f ? acc / L : 0.f;
+        if (a.lse && ch == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? sm.ml[0][r][0] + logf(L) : -INFINITY;
+    }
 }
 
 }  // namespace
