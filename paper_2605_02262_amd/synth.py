@@ -119,7 +119,7 @@ def mix_to_quota(n_win: int, p8: int, p4: int) -> tuple:
 
 
 def workload(cfg: int, seed: Optional[int] = None) -> Workload:
-    """The five configurations of the build's measurement plan."""
+    """The five configurations of the build's measurement plan, plus the paper's own operating point (5)."""
     if cfg == 0:
         s = SeqSpec(8, 16, 16, 16, mix_to_quota(8, 25, 50))
         return Workload("cfg0-tiny", F32, F16, 14, 2, 64, 32, 896, 1.0, [s], 0 if seed is None else seed)
@@ -154,6 +154,13 @@ def workload(cfg: int, seed: Optional[int] = None) -> Workload:
                 quota = mix_to_quota(n_win, p8, p4)
             seqs.append(SeqSpec(frames, 196, S, 256, quota))
         return Workload("cfg4-ragged", BF16, BF16, 28, 4, 128, 64, 3584, 1.5, seqs, sd, pin_first=0)
+    if cfg == 5:
+        # the paper's own operating point (Sec. 4.1 defaults, Sec. 4.4 token counts): batch 1, 100 frames, windows of
+        # 32 tokens, top tier kept 16-bit.  19600 visual tokens = 612 windows + a tail of 16; 2 / 217 / 393 windows at
+        # 16 / 4 / 2 bits and 135 text tokens give 215 / 6944 / 12576 tokens (the paper counts 215 / 6956 / 12564).
+        s = SeqSpec(100, 196, 32, 135, (2, 217, 393))
+        return Workload("cfg5-paper-tiers", BF16, BF16, 28, 4, 128, 64, 3584, 1.5, [s],
+                        5000 if seed is None else seed, top_bits=16)
     raise ValueError(f"unknown config {cfg}")
 
 

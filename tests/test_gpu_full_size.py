@@ -57,3 +57,13 @@ def test_ragged_batch32():
     bt = synth.batch(w)
     g, o = _full(bt)
     assert o.seg[0, 0] == bt.t.win_off[1] and o.seg[1, 2] == bt.t.win_off[2] - bt.t.win_off[1]
+
+
+def test_paper_operating_point_16bit_top_tier():
+    """The paper's own setting (Sec. 4.1 defaults, Sec. 4.4 token counts): batch 1, 100 frames, windows of 32 tokens,
+    top tier (first window and the best-scoring one) kept 16-bit, 217 / 393 windows at 4 / 2 bits, 135 text tokens."""
+    bt = synth.batch(synth.workload(5))
+    g, o = _full(bt)
+    assert o.seg[0].tolist() == [393, 217, 0, 2]
+    assert int(o.pk.len16[0]) == 2 * 32 + 16 + 135            # 215 16-bit rows, the paper's count
+    assert int(o.bits[0]) == 16                               # first window pinned (Sec. 3.2.2)
