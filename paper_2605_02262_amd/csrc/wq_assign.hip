@@ -9,29 +9,41 @@ namespace {
 
 __device__ __forceinline__ int class_of(int bits) { return bits == 2 ? 0 : (bits == 4 ? 1 : (bits == 8 ? 2 : 3)); }
 
-__global__ __launch_bounds__(256) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
-                                                const int32_t* __restrict__ quota, const float* __restrict__ thresholds,
-                                                int top_bits, int pin_first, uint8_t* __restrict__ bits,
-                                                int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
+constexpr int ASSIGN_THREADS = 1024;
+
+// matches of byte `me` among the four bytes of w
+__device__ __forceinline__ int count_eq_bytes(uint32_t w, uint32_t me)
 {
-    __shared__ float s_key[WQ_MAX_WINDOWS];
-    __shared__ uint8_t s_bits[WQ_MAX_WINDOWS];
+    return (int)((w & 0xFFu) == me) + (int)(((w >> 8) & 0xFFu) == me) + (int)(((w >> 16) & 0xFFu) == me) + (int)((w >> 24) == me);
+}
+
+__global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
+                                                           const int32_t* __restrict__ quota, const float* __restrict__ thresholds,
+                                                           int top_bits, int pin_first, uint8_t* __restrict__ bits,
+                                                           int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
+{
+    // keys and widths are read four at a time in the counting loops; both arrays are padded to a multiple of four
+    // (keys with -inf, which no key is smaller than and which never counts as an earlier equal; widths with 0)
+    __shared__ __align__(16) float s_key[WQ_MAX_WINDOWS + 4];
+    __shared__ __align__(16) uint8_t s_bits[WQ_MAX_WINDOWS + 4];
     __shared__ int s_cnt[4];
     const int b = blockIdx.x;
     const int w0 = win_off[b];
     int W = win_off[b + 1] - w0;
     if (W > WQ_MAX_WINDOWS) W = WQ_MAX_WINDOWS;   // host validated max_windows; never index past the arrays
+    const int W4 = (W + 3) & ~3;
     const int tid = threadIdx.x;
     if (tid < 4) s_cnt[tid] = 0;
-    for (int i = tid; i < W; i += 256) {
-        float s = scores[w0 + i];
+    for (int i = tid; i < W4; i += ASSIGN_THREADS) {
+        float s = i < W ? scores[w0 + i] : -INFINITY;
         s_key[i] = (s != s) ? -INFINITY : s;
+        if (i >= W) s_bits[i] = 0;
     }
     __syncthreads();
 
     if (mode == WQ_MODE_THRESHOLD) {
         float lo = thresholds[2 * b], hi = thresholds[2 * b + 1];
-        for (int i = tid; i < W; i += 256) {
+        for (int i = tid; i < W; i += ASSIGN_THREADS) {
             float s = scores[w0 + i];   // raw value: NaN compares false both ways -> 4
             int bt = s > hi ? top_bits : (s < lo ? 2 : 4);
             if (pin_first && i == 0) bt = top_bits;
@@ -48,16 +60,24 @@ __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ scores
         int n = W - first;
         n_top = min(max(n_top, 0), n);
         n4 = min(max(n4, 0), n - n_top);
-        for (int i = tid; i < W; i += 256) {
+        const float4* key4 = reinterpret_cast<const float4*>(s_key);
+        for (int i = tid; i < W; i += ASSIGN_THREADS) {
             int bt;
             if (i < first) {
                 bt = top_bits;
             } else {
-                float si = s_key[i];
+                const float si = s_key[i];
                 int r = 0;
-                for (int j = first; j < W; j++) {
-                    float sj = s_key[j];
-                    r += (sj > si || (sj == si && j < i)) ? 1 : 0;
+                for (int j = 0; j < W4; j += 4) {
+                    const float4 k = key4[j >> 2];
+                    r += (k.x > si || (k.x == si && j < i)) ? 1 : 0;
+                    r += (k.y > si || (k.y == si && j + 1 < i)) ? 1 : 0;
+                    r += (k.z > si || (k.z == si && j + 2 < i)) ? 1 : 0;
+                    r += (k.w > si || (k.w == si && j + 3 < i)) ? 1 : 0;
+                }
+                if (first) {            // the pinned window is not part of the ranking
+                    const float s0 = s_key[0];
+                    r -= (s0 > si || s0 == si) ? 1 : 0;
                 }
                 bt = r < n_top ? top_bits : (r < n_top + n4 ? 4 : 2);
             }
@@ -65,18 +85,21 @@ __global__ __launch_bounds__(256) void k_assign(const float* __restrict__ scores
         }
     }
     __syncthreads();
-    for (int i = tid; i < W; i += 256) {
+    for (int i = tid; i < W; i += ASSIGN_THREADS) {
         bits[w0 + i] = s_bits[i];
         atomicAdd(&s_cnt[class_of(s_bits[i])], 1);   // integer counts: order-independent
     }
     __syncthreads();
     if (tid < 4) seg_windows[4 * b + tid] = s_cnt[tid];
-    for (int i = tid; i < W; i += 256) {
+    const uint32_t* bits4 = reinterpret_cast<const uint32_t*>(s_bits);
+    for (int i = tid; i < W; i += ASSIGN_THREADS) {
         int c = class_of(s_bits[i]);
         int pos = 0;
         for (int k = 0; k < c; k++) pos += s_cnt[k];
-        uint8_t me = s_bits[i];
-        for (int j = 0; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
+        const uint32_t me = s_bits[i];
+        const int full = i >> 2;
+        for (int j = 0; j < full; j++) pos += count_eq_bytes(bits4[j], me);
+        for (int j = full * 4; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
         perm[w0 + pos] = i;
     }
 }
@@ -88,7 +111,7 @@ int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win
                      int32_t* perm, int32_t* seg_windows)
 {
     (void)max_windows;
-    hipLaunchKernelGGL(k_assign, dim3(B), dim3(256), 0, ctx->stream, scores, win_off, mode, quota, thresholds, top_bits,
+    hipLaunchKernelGGL(k_assign, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, scores, win_off, mode, quota, thresholds, top_bits,
                        pin_first, bits, perm, seg_windows);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
