@@ -13,6 +13,8 @@
  *                                       the build's problem statement
  *   O3  reorder + asymmetric RTN        Sec. 3.3.1, Sec. 3.3.3, Alg. 2 prefill half
  *   O4  mixed-precision decode attention  Alg. 2 decode half, Sec. 3.3.2
+ *   (wq_oracle.py adds two small host-side steps in plain Python: the per-layer threshold functions f1, f2 of
+ *   Sec. 3.2.3 and the batch-shared configuration by majority vote of the same section's last paragraph.)
  *
  * Floating point is fp64 everywhere except O3, whose integer codes are defined
  * by an explicit fp32 operation sequence (the paper fixes "round to nearest";

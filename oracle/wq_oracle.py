@@ -100,6 +100,54 @@ def rank_by_counting(scores, first: int = 0) -> np.ndarray:
     return r
 
 
+def layer_thresholds(s, alpha: float):
+    """Sec. 3.2.3 threshold functions, fp64, written out as printed:
+    T_low = f1(s) = (e^{alpha s} - 1) / (e^alpha - 1),  T_high = f2(s) = (e^{-alpha s} - 1) / (e^{-alpha} - 1).
+    alpha = 0 is the limit of both (the identity).  Pins: f(0) = 0, f(1) = 1, f1 <= f2 on [0, 1] (all stated by the
+    paper), f1(s) + f2(1 - s) = 1, and f1(1/2) = 1 / (1 + e) at the paper's default alpha = 2."""
+    s = np.asarray(s, dtype=np.float64)
+    if alpha == 0.0:
+        return s.copy(), s.copy()
+    lo = (np.exp(alpha * s) - 1.0) / (np.exp(alpha) - 1.0)
+    hi = (np.exp(-alpha * s) - 1.0) / (np.exp(-alpha) - 1.0)
+    return lo, hi
+
+
+def class_order(bits_seq) -> tuple:
+    """Stable class order of one sequence's windows (Alg. 2 prefill loop: windows are appended to their class
+    buffer in index order; classes are laid out 2-, 4-, 8-, 16-bit): (perm, counts)."""
+    bits_seq = list(int(x) for x in bits_seq)
+    perm = [i for width in (2, 4, 8, 16) for i, x in enumerate(bits_seq) if x == width]
+    return np.asarray(perm, dtype=np.int32), np.asarray([bits_seq.count(w) for w in (2, 4, 8, 16)], dtype=np.int32)
+
+
+def vote_bits(bits, win_off):
+    """Batch-shared configuration (last paragraph of Sec. 3.2.3): for every window position the width that occurs
+    most often among the requests that have that position is given to all of them.  The paper does not say what
+    happens on a tie; the higher precision wins here.  Plain loops; returns (bits, perm, seg_windows)."""
+    bits = np.asarray(bits, dtype=np.uint8)
+    win_off = np.asarray(win_off, dtype=np.int64)
+    B = len(win_off) - 1
+    out = bits.copy()
+    n_pos = int(np.diff(win_off).max()) if B else 0
+    for p in range(n_pos):
+        have = [b for b in range(B) if win_off[b + 1] - win_off[b] > p]
+        votes = {}
+        for b in have:
+            w = int(bits[win_off[b] + p])
+            votes[w] = votes.get(w, 0) + 1
+        best = max(votes.items(), key=lambda kv: (kv[1], kv[0]))[0]      # most votes, then the wider
+        for b in have:
+            out[win_off[b] + p] = best
+    perm = np.zeros(len(bits), dtype=np.int32)
+    seg = np.zeros((B, 4), dtype=np.int32)
+    for b in range(B):
+        pb, cb = class_order(out[win_off[b]:win_off[b + 1]])
+        perm[win_off[b]:win_off[b + 1]] = pb
+        seg[b] = cb
+    return out, perm, seg
+
+
 # ----------------------------------------------------------------------------- O3
 def quantize_group(x, bits: int):
     x = _f32(x)

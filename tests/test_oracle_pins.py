@@ -436,3 +436,66 @@ def test_empty_and_tail_only_sequences():
     got = O.decode_attention(q, pk, 0.125)
     want0 = O.attention_dense(q[0], K[:3], V[:3], 0.125)
     assert np.abs(got[0] - want0).max() < 1e-13
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# Sec. 3.2.3: threshold functions and the batch-shared configuration
+# ----------------------------------------------------------------------------------------------------------------
+def test_threshold_functions_closed_forms():
+    """What the paper states about f1, f2 (end points, f1 <= f2 on [0, 1]) and what follows from the formulas
+    (f1(s) + f2(1 - s) = 1; at the default alpha = 2, f1(1/2) = 1 / (1 + e) and f2(1/2) = e / (1 + e))."""
+    s = np.linspace(0.0, 1.0, 101)
+    for alpha in (0.5, 1.0, 2.0, 4.0, 8.0):
+        lo, hi = O.layer_thresholds(s, alpha)
+        assert lo[0] == 0.0 and hi[0] == 0.0
+        assert abs(lo[-1] - 1.0) < 1e-15 and abs(hi[-1] - 1.0) < 1e-15
+        assert np.all(lo <= hi + 1e-15)
+        assert np.all(np.diff(lo) > 0) and np.all(np.diff(hi) > 0)
+        lo_r, hi_r = O.layer_thresholds(1.0 - s, alpha)
+        assert np.abs(lo + hi_r - 1.0).max() < 1e-14
+    lo, hi = O.layer_thresholds([0.5], 2.0)
+    assert abs(lo[0] - 1.0 / (1.0 + np.e)) < 1e-15 and abs(hi[0] - np.e / (1.0 + np.e)) < 1e-15
+    lo, hi = O.layer_thresholds(s, 0.0)
+    assert np.array_equal(lo, s) and np.array_equal(hi, s)
+    # a dropped "-1", a swapped sign of alpha or a swapped pair would each break one of the lines above
+    lo, hi = O.layer_thresholds(s, 1e-9)
+    assert np.abs(lo - s).max() < 1e-6 and np.abs(hi - s).max() < 1e-6
+
+
+def test_vote_bits_majority_ties_and_ragged_positions():
+    # three requests with 4, 4 and 2 windows
+    bits = np.array([16, 2, 4, 2,   16, 4, 4, 4,   16, 4], dtype=np.uint8)
+    win_off = np.array([0, 4, 8, 10])
+    out, perm, seg = O.vote_bits(bits, win_off)
+    # position 0: unanimous 16; position 1: 2,4,4 -> 4; position 2: 4,4 -> 4; position 3: 2 vs 4, a tie -> 4
+    assert out.tolist() == [16, 4, 4, 4, 16, 4, 4, 4, 16, 4]
+    assert seg.tolist() == [[0, 3, 0, 1], [0, 3, 0, 1], [0, 1, 0, 1]]
+    assert perm.tolist() == [1, 2, 3, 0, 1, 2, 3, 0, 1, 0]
+    # one request: the vote changes nothing; the order is the stable class order of assign_bits
+    rng = np.random.default_rng(5)
+    sc = rng.standard_normal(37).astype(np.float32)
+    b1, p1, s1 = O.assign_bits(sc, [0, 37], 0, quota=[[5, 12, 20]], top_bits=8, pin_first=1)
+    b2, p2, s2 = O.vote_bits(b1, [0, 37])
+    assert np.array_equal(b1, b2) and np.array_equal(p1, p2) and np.array_equal(s1, s2)
+    # brute force on random small batches: every position's result is a mode, and the widest among the modes
+    for trial in range(20):
+        B = int(rng.integers(1, 6))
+        n = rng.integers(1, 9, size=B)
+        off = np.concatenate([[0], np.cumsum(n)])
+        bb = rng.choice([2, 4, 8], size=int(off[-1])).astype(np.uint8)
+        out, perm, seg = O.vote_bits(bb, off)
+        for p in range(int(n.max())):
+            col = [int(bb[off[b] + p]) for b in range(B) if n[b] > p]
+            cnt = {w: col.count(w) for w in set(col)}
+            top = max(cnt.values())
+            want = max(w for w, c in cnt.items() if c == top)
+            assert all(int(out[off[b] + p]) == want for b in range(B) if n[b] > p)
+        for b in range(B):
+            pb = perm[off[b]:off[b + 1]]
+            assert sorted(pb.tolist()) == list(range(int(n[b])))
+            widths = out[off[b]:off[b + 1]][pb].astype(int).tolist()
+            assert widths == sorted(widths)                                # classes in the order 2, 4, 8, 16 ...
+            for w in set(widths):                                          # ... and index order inside a class
+                idx = [int(i) for i in pb if out[off[b] + i] == w]
+                assert idx == sorted(idx)
+            assert seg[b].tolist() == [widths.count(w) for w in (2, 4, 8, 16)]
