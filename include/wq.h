@@ -139,6 +139,23 @@ int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_o
                    const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
                    int32_t* perm, int32_t* seg_windows);
 
+/* ---- per-layer thresholds (Sec. 3.2.3 threshold functions) --------------------------------------------------
+ * t_low[i] = f1(s[i]) = (e^{alpha s} - 1)/(e^alpha - 1),  t_high[i] = f2(s[i]) = (e^{-alpha s} - 1)/(e^{-alpha} - 1);
+ * alpha = 0 gives the limit of both, the identity.  s[i] is layer i's hidden-state similarity in [0, 1] (the
+ * caller measures it on a calibration run; the library does not).  Host-only, pure: s, t_low, t_high are host
+ * arrays of n_layers entries.  Evaluated in double, returned as the fp32 values wq_assign_bits compares with.
+ * WQ_ERR_ARG on NULL, n_layers < 0, a non-finite alpha or an s[i] outside [0, 1].                             */
+int wq_layer_thresholds(const double* s, int n_layers, double alpha, float* t_low, float* t_high);
+
+/* ---- batch-shared configuration (Sec. 3.2.3, last paragraph) ----------------------------------------------
+ * For every window position the width that occurs most often among the sequences that have that position is
+ * given to all of them; on a tie the wider one wins (the paper leaves ties open).  bits_in [total_win] uint8 as
+ * written by wq_assign_bits; win_off [B+1]; max_windows: host bound on windows per sequence (<= 8192).
+ * Outputs as in wq_assign_bits: bits_out [total_win] (may alias bits_in), perm [total_win], seg_windows [B,4].
+ * All arrays device memory.                                                                                   */
+int wq_vote_bits(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, int max_windows,
+                 uint8_t* bits_out, int32_t* perm, int32_t* seg_windows);
+
 /* ---- packed mixed-precision cache of one layer (layout: see the header comment) -------------------------- */
 typedef struct {
     int32_t B, Hkv, hd, group;

@@ -60,6 +60,8 @@ def lib() -> C.CDLL:
         L.wq_auto_splits.argtypes = [i32, i32, i64]
         L.wq_window_scores.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.wq_assign_bits.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
+        L.wq_layer_thresholds.argtypes = [C.POINTER(C.c_double), i32, C.c_double, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+        L.wq_vote_bits.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
@@ -205,6 +207,27 @@ def wq_assign_bits(ctx: Context, scores, win_off, max_windows: int, mode: int = 
     ctx.check(lib().wq_assign_bits(ctx.handle, _ptr(scores), B, _ptr(win_off), max_windows, mode, _ptr(quota),
                                    _ptr(thresholds), top_bits, pin_first, _ptr(bits), _ptr(perm), _ptr(seg)))
     return bits, perm, seg
+
+
+def wq_layer_thresholds(s, alpha: float):
+    """(T_low, T_high) per layer as fp32 lists (host-only call)."""
+    n = len(s)
+    sa = (C.c_double * n)(*[float(x) for x in s])
+    lo, hi = (C.c_float * n)(), (C.c_float * n)()
+    rc = lib().wq_layer_thresholds(sa, n, float(alpha), lo, hi)
+    if rc != 0:
+        raise WQError(rc, "wq_layer_thresholds: bad argument")
+    return [float(x) for x in lo], [float(x) for x in hi]
+
+
+def wq_vote_bits(ctx: Context, bits, win_off, max_windows: int):
+    B = win_off.numel() - 1
+    W = bits.numel()
+    out = torch.empty(W, dtype=torch.uint8, device=ctx.device)
+    perm = torch.empty(W, dtype=torch.int32, device=ctx.device)
+    seg = torch.empty(B, 4, dtype=torch.int32, device=ctx.device)
+    ctx.check(lib().wq_vote_bits(ctx.handle, _ptr(bits), B, _ptr(win_off), max_windows, _ptr(out), _ptr(perm), _ptr(seg)))
+    return out, perm, seg
 
 
 def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg_windows, total_rows: int, out: PackedKV):

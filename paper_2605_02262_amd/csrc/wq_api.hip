@@ -1,5 +1,6 @@
 // C-ABI entry points of libwq: context handling, host-side argument validation, dispatch.
 // Every check that needs only host data happens here, before anything is enqueued.
+#include <math.h>
 #include <new>
 #include <string.h>
 
@@ -203,6 +204,35 @@ int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_o
     if (mode == WQ_MODE_THRESHOLD && !thresholds) return wq_fail(ctx, WQ_ERR_ARG, "threshold mode without thresholds");
     return wq_launch_assign(ctx, scores, B, win_off, max_windows, mode, quota, thresholds, top_bits, pin_first != 0,
                             bits, perm, seg_windows);
+}
+
+int wq_layer_thresholds(const double* s, int n_layers, double alpha, float* t_low, float* t_high)
+{
+    if (n_layers < 0 || !isfinite(alpha)) return WQ_ERR_ARG;
+    if (n_layers > 0 && (!s || !t_low || !t_high)) return WQ_ERR_ARG;
+    for (int i = 0; i < n_layers; i++)
+        if (!(s[i] >= 0.0 && s[i] <= 1.0)) return WQ_ERR_ARG;
+    for (int i = 0; i < n_layers; i++) {
+        // expm1 keeps the quotient accurate where alpha * s is small; alpha = 0 is the limit s
+        const double lo = alpha == 0.0 ? s[i] : expm1(alpha * s[i]) / expm1(alpha);
+        const double hi = alpha == 0.0 ? s[i] : expm1(-alpha * s[i]) / expm1(-alpha);
+        t_low[i] = (float)lo;
+        t_high[i] = (float)hi;
+    }
+    return WQ_OK;
+}
+
+int wq_vote_bits(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, int max_windows, uint8_t* bits_out,
+                 int32_t* perm, int32_t* seg_windows)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || max_windows < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    if (max_windows > WQ_MAX_WINDOWS)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "more than %d windows per sequence", WQ_MAX_WINDOWS);
+    if (B == 0) return WQ_OK;
+    if (!win_off || !seg_windows) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
+    if (max_windows > 0 && (!bits_in || !bits_out || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL widths or output");
+    return wq_launch_vote(ctx, bits_in, B, win_off, bits_out, perm, seg_windows);
 }
 
 int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,

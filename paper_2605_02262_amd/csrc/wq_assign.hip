@@ -17,6 +17,64 @@ __device__ __forceinline__ int count_eq_bytes(uint32_t w, uint32_t me)
     return (int)((w & 0xFFu) == me) + (int)(((w >> 8) & 0xFFu) == me) + (int)(((w >> 16) & 0xFFu) == me) + (int)((w >> 24) == me);
 }
 
+// Widths of one sequence are in s_bits (padded with zeros to a multiple of four): writes them out, counts the
+// classes and lists the windows class by class (2-, 4-, 8-, 16-bit), each class in index order.
+__device__ __forceinline__ void emit_class_order(const uint8_t* s_bits, int* s_cnt, int W, int w0, int b, uint8_t* __restrict__ bits,
+                                                 int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
+{
+    const int tid = threadIdx.x;
+    for (int i = tid; i < W; i += ASSIGN_THREADS) {
+        bits[w0 + i] = s_bits[i];
+        atomicAdd(&s_cnt[class_of(s_bits[i])], 1);   // integer counts: order-independent
+    }
+    __syncthreads();
+    if (tid < 4) seg_windows[4 * b + tid] = s_cnt[tid];
+    const uint32_t* bits4 = reinterpret_cast<const uint32_t*>(s_bits);
+    for (int i = tid; i < W; i += ASSIGN_THREADS) {
+        int c = class_of(s_bits[i]);
+        int pos = 0;
+        for (int k = 0; k < c; k++) pos += s_cnt[k];
+        const uint32_t me = s_bits[i];
+        const int full = i >> 2;
+        for (int j = 0; j < full; j++) pos += count_eq_bytes(bits4[j], me);
+        for (int j = full * 4; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
+        perm[w0 + pos] = i;
+    }
+}
+
+// Batch-shared configuration (Sec. 3.2.3, last paragraph): one workgroup per sequence; every lane takes window
+// positions of that sequence and counts, over the sequences that have the position, how often each width occurs.
+// Most votes win, the wider width on a tie.
+__global__ __launch_bounds__(ASSIGN_THREADS) void k_vote(const uint8_t* __restrict__ bits_in, int B, const int32_t* __restrict__ win_off,
+                                                         uint8_t* __restrict__ bits, int32_t* __restrict__ perm,
+                                                         int32_t* __restrict__ seg_windows)
+{
+    __shared__ __align__(16) uint8_t s_bits[WQ_MAX_WINDOWS + 4];
+    __shared__ int s_cnt[4];
+    const int b = blockIdx.x;
+    const int w0 = win_off[b];
+    int W = win_off[b + 1] - w0;
+    if (W > WQ_MAX_WINDOWS) W = WQ_MAX_WINDOWS;
+    const int W4 = (W + 3) & ~3;
+    const int tid = threadIdx.x;
+    if (tid < 4) s_cnt[tid] = 0;
+    for (int p = tid; p < W4; p += ASSIGN_THREADS) {
+        int votes[4] = {0, 0, 0, 0};
+        if (p < W) {
+            for (int o = 0; o < B; o++) {
+                const int o0 = win_off[o];
+                if (win_off[o + 1] - o0 > p) votes[class_of(bits_in[o0 + p])]++;
+            }
+        }
+        int best = 0;
+#pragma unroll
+        for (int c = 1; c < 4; c++) best = votes[c] >= votes[best] ? c : best;     // >= : the wider width on a tie
+        s_bits[p] = p < W ? (uint8_t)(best == 0 ? 2 : (best == 1 ? 4 : (best == 2 ? 8 : 16))) : (uint8_t)0;
+    }
+    __syncthreads();                 // every lane is done reading bits_in before anything is written (it may alias bits)
+    emit_class_order(s_bits, s_cnt, W, w0, b, bits, perm, seg_windows);
+}
+
 __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
                                                            const int32_t* __restrict__ quota, const float* __restrict__ thresholds,
                                                            int top_bits, int pin_first, uint8_t* __restrict__ bits,
@@ -85,26 +143,18 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restri
         }
     }
     __syncthreads();
-    for (int i = tid; i < W; i += ASSIGN_THREADS) {
-        bits[w0 + i] = s_bits[i];
-        atomicAdd(&s_cnt[class_of(s_bits[i])], 1);   // integer counts: order-independent
-    }
-    __syncthreads();
-    if (tid < 4) seg_windows[4 * b + tid] = s_cnt[tid];
-    const uint32_t* bits4 = reinterpret_cast<const uint32_t*>(s_bits);
-    for (int i = tid; i < W; i += ASSIGN_THREADS) {
-        int c = class_of(s_bits[i]);
-        int pos = 0;
-        for (int k = 0; k < c; k++) pos += s_cnt[k];
-        const uint32_t me = s_bits[i];
-        const int full = i >> 2;
-        for (int j = 0; j < full; j++) pos += count_eq_bytes(bits4[j], me);
-        for (int j = full * 4; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
-        perm[w0 + pos] = i;
-    }
+    emit_class_order(s_bits, s_cnt, W, w0, b, bits, perm, seg_windows);
 }
 
 }  // namespace
+
+int wq_launch_vote(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, uint8_t* bits_out, int32_t* perm,
+                   int32_t* seg_windows)
+{
+    hipLaunchKernelGGL(k_vote, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, bits_in, B, win_off, bits_out, perm, seg_windows);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
 
 int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
                      const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,

@@ -88,3 +88,34 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert lib.wq_decode_attention(h, one, W.BF16, 0, 28, C.byref(d), 0.1, 0, 0, 0, None, None) == 0
     finally:
         lib.wq_destroy(h)
+
+
+def test_layer_thresholds_match_the_oracle_and_reject_bad_input(lib):
+    """Host-only call (Sec. 3.2.3 threshold functions): compared with the fp64 oracle, which the CPU pins tie to
+    the closed forms."""
+    import numpy as np
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    s = np.concatenate([[0.0, 1.0, 0.5, 1e-12], np.random.default_rng(3).random(28)])
+    lo, hi = W.wq_layer_thresholds(s, 1e-9)                # the written-out quotient cancels here; the limit is s
+    assert np.abs(np.asarray(lo) - s).max() <= 1e-6 and np.abs(np.asarray(hi) - s).max() <= 1e-6
+    for alpha in (0.0, 0.5, 2.0, 8.0, -1.0):
+        lo, hi = W.wq_layer_thresholds(s, alpha)
+        lo_o, hi_o = O.layer_thresholds(s, alpha)
+        assert np.abs(np.asarray(lo) - lo_o).max() <= 1e-7
+        assert np.abs(np.asarray(hi) - hi_o).max() <= 1e-7
+    lo, hi = W.wq_layer_thresholds([0.0, 1.0], 2.0)
+    assert lo == [0.0, 1.0] and hi == [0.0, 1.0]
+    for bad in ([1.5], [-0.1], [float("nan")]):
+        with pytest.raises(W.WQError):
+            W.wq_layer_thresholds(bad, 2.0)
+    with pytest.raises(W.WQError):
+        W.wq_layer_thresholds([0.5], float("inf"))
+    # vote: size checks before any launch
+    h = C.c_void_p()
+    assert lib.wq_create(C.byref(h), None, C.c_void_p(0x1000), 1 << 21) == 0
+    one = C.c_void_p(0x2000)
+    assert lib.wq_vote_bits(h, one, 1, one, 10000, one, one, one) == -2
+    assert lib.wq_vote_bits(h, None, 1, one, 8, one, one, one) == -1
+    assert lib.wq_vote_bits(h, one, 0, one, 8, one, one, one) == 0
+    lib.wq_destroy(h)

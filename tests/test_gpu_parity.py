@@ -155,3 +155,57 @@ def test_decode_fixed_shares_is_reproducible_and_agrees_with_block_pool():
         assert torch.equal(g2.out, first)
     g3, _, _ = _check(bt, H, splits=3, algo=W.DECODE_MFMA)
     assert H.attention_error(g3.out.cpu().numpy(), first.cpu().numpy().astype(np.float64)) <= H.ATTN_TOL
+
+
+def test_batch_shared_configuration_by_vote_then_threshold_mode_end_to_end():
+    """Sec. 3.2.3: thresholds from f1/f2 for a few layer similarities, widths by the threshold rule (16-bit top
+    tier), one configuration per batch by majority vote, then the cache and decode attention on it."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(6, 32, 16, 9, (0, 0, 0)), synth.SeqSpec(6, 32, 16, 5, (0, 0, 0)),
+             synth.SeqSpec(4, 32, 16, 7, (0, 0, 0)), synth.SeqSpec(6, 32, 16, 0, (0, 0, 0), tail=5),
+             synth.SeqSpec(5, 32, 16, 3, (0, 0, 0))]
+    bt = _custom(77, 128, 64, 2, 7, synth.BF16, specs, top_bits=16, pin=1)
+    w, t = bt.w, bt.t
+    sc = O.window_scores(bt.E_v, bt.E_t, t.vis_off, t.txt_off, t.win_size, t.win_off).astype(np.float32)
+    # layer similarities -> thresholds; rescale them to the range of these synthetic scores so all three tiers occur
+    lo, hi = W.wq_layer_thresholds([0.35, 0.6, 0.9], 2.0)
+    qs = np.quantile(sc, [0.0, 1.0])
+    for tl, th in zip(lo, hi):
+        thr = np.tile(np.array([[qs[0] + tl * (qs[1] - qs[0]), qs[0] + th * (qs[1] - qs[0])]], np.float32), (w.B, 1))
+        ctx = W.Context(W.workspace_bytes(w.B, w.Hq, w.hd, 4))
+        win_off = H.i32(t.win_off)
+        max_w = int(np.diff(t.win_off).max())
+        bits, perm, seg = W.wq_assign_bits(ctx, torch.from_numpy(sc).cuda(), win_off, max_w, W.MODE_THRESHOLD, None,
+                                           torch.from_numpy(thr).cuda(), 16, 1)
+        vb, vp, vs = W.wq_vote_bits(ctx, bits, win_off, max_w)
+        ob, op_, os_ = O.assign_bits(sc, t.win_off, 1, thresholds=thr, top_bits=16, pin_first=1)
+        assert np.array_equal(bits.cpu().numpy(), ob)
+        wb, wp, wseg = O.vote_bits(ob, t.win_off)
+        assert np.array_equal(vb.cpu().numpy(), wb) and np.array_equal(vp.cpu().numpy(), wp)
+        assert np.array_equal(vs.cpu().numpy(), wseg)
+        # in place (bits_out aliasing bits_in) gives the same
+        rc = W.lib().wq_vote_bits(ctx.handle, bits.data_ptr(), w.B, win_off.data_ptr(), max_w, bits.data_ptr(),
+                                  perm.data_ptr(), seg.data_ptr())
+        assert rc == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(bits.cpu().numpy(), wb) and np.array_equal(perm.cpu().numpy(), wp)
+        # the shared configuration through the rest of the path
+        cap, off16 = [0, 0, 0], []
+        for b, s in enumerate(w.seqs):
+            for c in range(3):
+                cap[c] += (int(wseg[b, c]) * s.win_size + 31) // 32 * 32
+            off16.append(int(wseg[b, 3]) * s.win_size + (s.n_vis - s.n_win * s.win_size) + s.n_text + 8)
+        off16 = np.concatenate([[0], np.cumsum(off16)]).astype(np.int32)
+        cap = [max(c, 32) for c in cap]
+        pk = W.PackedKV(w.B, w.Hkv, w.hd, w.group, torch.bfloat16, cap, off16, fill=0xA5)
+        K, V = H.to_dev(bt.K, w.dtype), H.to_dev(bt.V, w.dtype)
+        W.wq_reorder_quantize(ctx, K, V, H.i32(t.kv_off), H.i32(t.win_size), win_off, vp, vs, int(t.kv_off[-1]), pk)
+        out = W.wq_decode_attention(ctx, H.to_dev(bt.q, w.dtype), pk, 1.0 / float(np.sqrt(w.hd)), 2, 300)
+        torch.cuda.synchronize()
+        opk = O.reorder_quantize(bt.K, bt.V, t.kv_off, t.win_size, t.win_off, wp, wseg, w.group, off16=off16[:-1], cap=cap,
+                                 cap16=int(off16[-1]))
+        ref = O.decode_attention(bt.q, opk, 1.0 / np.sqrt(w.hd))
+        assert H.attention_error(out.cpu().numpy(), ref) <= H.ATTN_TOL
+        assert ctx.device_status() == 0
