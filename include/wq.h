@@ -183,6 +183,14 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
                         const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
                         const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out);
 
+/* ---- appending a generated token (Sec. 2.2: new keys and values go to the end of the cache; Sec. 3.1: generated
+ * tokens stay 16-bit) --------------------------------------------------------------------------------------
+ * Writes k_new, v_new [B, Hkv, hd] (device, element type `dtype`) as row off16[b]+len16[b] of sequence b's
+ * 16-bit segment and adds one to len16[b] (on the device, in stream order).  dtype pairs with dtype16 as in
+ * wq_reorder_quantize (fp32 values are rounded to fp16, nearest even).  A sequence whose segment is full
+ * (off16[b]+len16[b] == off16[b+1], or == cap16) is left unchanged and WQ_DEV_SEG16_OVERFLOW is raised.       */
+int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
+
 /* ---- a4: decode attention over the packed cache (Alg. 2, decode half) -------------------------------------
  * out[b,h,:] = sum_t softmax_t(sm_scale * q[b,h].k^_t) v^_t over the 2-, 4-, 8- and 16-bit segments of
  * sequence b, one softmax over all of them, no mask (Sec. 2.1); head h reads KV head h/(Hq/Hkv).

@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.wq_layer_thresholds.argtypes = [C.POINTER(C.c_double), i32, C.c_double, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.wq_vote_bits.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
+        L.wq_append_kv.argtypes = [vp, vp, vp, i32, i32, C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
         L.wq_decode_timing.argtypes = [vp, i32]
@@ -235,6 +236,11 @@ def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg
     ctx.check(lib().wq_reorder_quantize(ctx.handle, _ptr(K), _ptr(V), _dtype_id(K), B, _ptr(kv_off), _ptr(win_size),
                                         _ptr(win_off), _ptr(perm), _ptr(seg_windows), total_rows, C.byref(out.desc)))
     return out
+
+
+def wq_append_kv(ctx: Context, k_new, v_new, kv: PackedKV):
+    B = k_new.shape[0]
+    ctx.check(lib().wq_append_kv(ctx.handle, _ptr(k_new), _ptr(v_new), _dtype_id(k_new), B, C.byref(kv.desc)))
 
 
 def wq_decode_attention(ctx: Context, q, kv: PackedKV, sm_scale: float, num_splits: int = 0, max_seq_tokens: int = 0,

@@ -257,6 +257,21 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
     return wq_launch_quantize(ctx, K, V, dtype, B, kv_off, win_size, win_off, perm, seg_windows, total_rows, out);
 }
 
+int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    if (!dtype_ok(dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown dtype %d", dtype);
+    int rc = check_packed(ctx, kv, B, false);
+    if (rc != WQ_OK) return rc;
+    if ((dtype == WQ_BF16) != (kv->dtype16 == WQ_BF16))
+        return wq_fail(ctx, WQ_ERR_ARG, "dtype16 must be bf16 for bf16 input and fp16 for fp16/fp32 input");
+    if (B == 0) return WQ_OK;
+    if (!k_new || !v_new) return wq_fail(ctx, WQ_ERR_ARG, "NULL k_new or v_new");
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    return wq_launch_append(ctx, k_new, v_new, dtype, B, kv);
+}
+
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
 {

@@ -249,6 +249,34 @@ __global__ __launch_bounds__(256) void k_copy16(const T* __restrict__ K, const T
     }
 }
 
+// one generated token per sequence -> the end of its 16-bit segment
+template <typename T>
+__global__ __launch_bounds__(256) void k_append16(const T* __restrict__ k_new, const T* __restrict__ v_new, int row_elems,
+                                                  wq_packed_kv pk, uint32_t* __restrict__ status)
+{
+    const int b = blockIdx.x;
+    const int64_t row = (int64_t)pk.off16[b] + pk.len16[b];
+    const bool full = row >= pk.off16[b + 1] || row >= pk.cap16;
+    __syncthreads();                       // every lane has read len16[b] before it changes
+    if (full) {
+        if (threadIdx.x == 0) atomicOr(status, WQ_DEV_SEG16_OVERFLOW);
+        return;
+    }
+    uint16_t* k16 = static_cast<uint16_t*>(pk.k16) + row * row_elems;
+    uint16_t* v16 = static_cast<uint16_t*>(pk.v16) + row * row_elems;
+    for (int e = threadIdx.x; e < row_elems; e += 256) {
+        const float kx = wq_ld(k_new, (int64_t)b * row_elems + e), vx = wq_ld(v_new, (int64_t)b * row_elems + e);
+        if constexpr (std::is_same_v<T, __hip_bfloat16>) {
+            k16[e] = (uint16_t)(__float_as_uint(kx) >> 16);
+            v16[e] = (uint16_t)(__float_as_uint(vx) >> 16);
+        } else {
+            k16[e] = __half_as_ushort(__float2half_rn(kx));
+            v16[e] = __half_as_ushort(__float2half_rn(vx));
+        }
+    }
+    if (threadIdx.x == 0) pk.len16[b] += 1;
+}
+
 template <typename T, int HD>
 int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_off, const int32_t* win_size,
         const int32_t* win_off, const int32_t* perm, const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* pk)
@@ -277,6 +305,27 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
 }
 
 }  // namespace
+
+int wq_launch_append(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv)
+{
+    const int row_elems = kv->Hkv * kv->hd;
+    hipStream_t st = ctx->stream;
+    switch (dtype) {
+        case WQ_F32:
+            hipLaunchKernelGGL(k_append16<float>, dim3(B), dim3(256), 0, st, static_cast<const float*>(k_new),
+                               static_cast<const float*>(v_new), row_elems, *kv, wq_status_ptr(ctx));
+            break;
+        case WQ_BF16:
+            hipLaunchKernelGGL(k_append16<__hip_bfloat16>, dim3(B), dim3(256), 0, st, static_cast<const __hip_bfloat16*>(k_new),
+                               static_cast<const __hip_bfloat16*>(v_new), row_elems, *kv, wq_status_ptr(ctx));
+            break;
+        default:
+            hipLaunchKernelGGL(k_append16<__half>, dim3(B), dim3(256), 0, st, static_cast<const __half*>(k_new),
+                               static_cast<const __half*>(v_new), row_elems, *kv, wq_status_ptr(ctx));
+    }
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
 
 int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
                        const int32_t* win_size, const int32_t* win_off, const int32_t* perm,

@@ -209,3 +209,39 @@ def test_batch_shared_configuration_by_vote_then_threshold_mode_end_to_end():
         ref = O.decode_attention(bt.q, opk, 1.0 / np.sqrt(w.hd))
         assert H.attention_error(out.cpu().numpy(), ref) <= H.ATTN_TOL
         assert ctx.device_status() == 0
+
+
+def test_append_generated_tokens_then_decode():
+    """Sec. 2.2 / Sec. 3.1: generated tokens are appended 16-bit at the end of the cache; every decode step attends
+    over the quantized segments plus the grown 16-bit segment.  Three steps, then a full segment raises the flag."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(6, 21, 21, 9, (1, 3, 2)), synth.SeqSpec(4, 16, 16, 30, (1, 2, 1))]
+    bt = _custom(31, 128, 64, 2, 7, synth.BF16, specs)
+    w = bt.w
+    cap, off16 = H.capacities(w, slack=3)
+    g = H.run_gpu(bt, cap=cap, off16=off16, splits=2)
+    o = H.run_oracle(bt, scores_override=g.scores.cpu().numpy(), cap=cap, off16=off16)
+    H.assert_packed_equal(g, o)
+    rng = np.random.default_rng(9)
+    sm = 1.0 / float(np.sqrt(w.hd))
+    for step in range(3):
+        kn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        vn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        qn = synth.round_bf16(rng.standard_normal((w.B, w.Hq, w.hd)).astype(np.float32))
+        W.wq_append_kv(g.ctx, H.to_dev(kn, w.dtype), H.to_dev(vn, w.dtype), g.pk)
+        for b in range(w.B):                                   # the same append on the oracle's arrays
+            r = int(o.pk.off16[b] + o.pk.len16[b])
+            o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+            o.pk.len16[b] += 1
+        out = W.wq_decode_attention(g.ctx, H.to_dev(qn, w.dtype), g.pk, sm, 2, 400)
+        torch.cuda.synchronize()
+        assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+        ref = O.decode_attention(qn, o.pk, sm)
+        assert H.attention_error(out.cpu().numpy(), ref) <= H.ATTN_TOL
+    assert g.ctx.device_status() == 0
+    kn = H.to_dev(np.zeros((w.B, w.Hkv, w.hd), np.float32), w.dtype)
+    W.wq_append_kv(g.ctx, kn, kn, g.pk)                        # every segment had room for exactly three rows
+    assert g.ctx.device_status() == 2
+    assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
