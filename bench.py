@@ -50,6 +50,115 @@ def measured_traffic():
     return None
 
 
+def decode_loop(args):
+    """The 7B-shaped decoder loop (28 layers, 8 sequences of 64 frames x 196 + 256 text tokens, bit mix 20/50/30 %):
+    every decode step appends one generated token per sequence to every layer's 16-bit segment and attends over that
+    layer's packed cache.  One step (28 appends + 28 decode calls) is captured in a HIP graph and replayed.
+    K, V, queries and scores are drawn on the device (torch generator, same distributions as the host generator)."""
+    import torch
+    from paper_2605_02262_amd import binding as W
+    from paper_2605_02262_amd import synth
+
+    torch.cuda.set_device(0)
+    w = synth.workload(2)
+    t = synth.tables(w)
+    B, L = w.B, w.layers
+    steps, warm = args.steps, args.warmup
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    i32 = lambda x: torch.as_tensor(np.ascontiguousarray(x, dtype=np.int32)).cuda()
+    kv_off, win_size, win_off, quota = i32(t.kv_off), i32(t.win_size), i32(t.win_off), i32(t.quota)
+    total_rows, total_win = int(t.kv_off[-1]), int(t.win_off[-1])
+    max_tok = int(np.diff(t.kv_off).max()) + steps + warm
+    max_win = int(np.diff(t.win_off).max())
+    nsplit = args.splits or W.auto_splits(B, w.Hkv, max_tok)
+    ctx = W.Context(W.workspace_bytes(B, w.Hq, w.hd, nsplit))
+    cap = [0, 0, 0]
+    n16 = []
+    for sq in w.seqs:
+        n_top, n4, n2 = sq.quota
+        for c, n in enumerate((n2, n4, n_top)):
+            cap[c] += (n * sq.win_size + 31) // 32 * 32
+        n16.append(sq.n_text + steps + warm + 8)
+    off16 = np.concatenate([[0], np.cumsum(n16)]).astype(np.int32)
+    sm_scale = 1.0 / float(np.sqrt(w.hd))
+    caches, qs, kn, vn = [], [], [], []
+    randn = lambda *s: torch.randn(*s, generator=gen, device="cuda", dtype=torch.float32)
+    for layer in range(L):
+        csc = torch.exp(w.sigma_k * randn(w.Hkv, w.hd))                      # key channel outliers, lognormal
+        K = (randn(total_rows, w.Hkv, w.hd) * csc).to(torch.bfloat16)
+        V = randn(total_rows, w.Hkv, w.hd).to(torch.bfloat16)
+        scores = torch.rand(total_win, generator=gen, device="cuda")
+        bits, perm, seg = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
+        pk = W.PackedKV(B, w.Hkv, w.hd, w.group, torch.bfloat16, cap, off16)
+        W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, pk)
+        caches.append(pk)
+        q = randn(B, w.Hq, w.hd)
+        rep = w.Hq // w.Hkv                                                  # logits over the sequence: std 2
+        sd = sm_scale * torch.sqrt(((q.view(B, w.Hkv, rep, w.hd) * csc[None, :, None, :]) ** 2).sum(-1)).view(B, w.Hq, 1)
+        qs.append((q * (w.logit_std / sd)).to(torch.bfloat16))
+        kn.append((randn(B, w.Hkv, w.hd) * csc).to(torch.bfloat16))
+        vn.append(randn(B, w.Hkv, w.hd).to(torch.bfloat16))
+        del K, V
+    torch.cuda.synchronize()
+    assert ctx.device_status() == 0
+    outs = [torch.empty(B, w.Hq, w.hd, dtype=torch.float32, device="cuda") for _ in range(L)]
+
+    def one_step():
+        for layer in range(L):
+            W.wq_append_kv(ctx, kn[layer], vn[layer], caches[layer])
+            W.wq_decode_attention(ctx, qs[layer], caches[layer], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=outs[layer])
+
+    bytes0 = sum(pk.bytes_algorithmic() for pk in caches)
+    row_bytes = L * B * w.Hkv * w.hd * 2 * 2                                 # 16-bit rows added per step, all layers
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # eager reference of the first step's outputs (the graph must reproduce them: same cache state, fixed order)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        ctx.set_stream(side)
+        one_step()                                                           # step 1, eager, also warms the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            one_step()
+    ctx.set_stream(side)
+    with torch.cuda.stream(side):
+        for _ in range(max(warm - 2, 0)):
+            graph.replay()
+        side.synchronize()
+        e0.record(side)
+        for _ in range(steps):
+            graph.replay()
+        e1.record(side)
+        side.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    status = ctx.device_status()
+    len16 = caches[0].len16.cpu().numpy()
+    mean_rows = max(warm, 2) + (steps + 1) / 2.0                             # rows appended before + during the timed steps
+    bytes_step = bytes0 + mean_rows * row_bytes
+    # eager loop for comparison (launch-bound without the graph)
+    with torch.cuda.stream(side):
+        e0.record(side)
+        n_eager = 8
+        for _ in range(n_eager):
+            one_step()
+        e1.record(side)
+        side.synchronize()
+    us_eager = e0.elapsed_time(e1) * 1e3 / n_eager
+    finite = all(bool(torch.isfinite(o).all().item()) for o in outs)
+    res = {"metric": "mixed-precision KV decode loop us/step (28 layers, HIP graph) and GB/s", "value": round(bytes_step / (us * 1e-6) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(us * 1e-3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16 cache in, 2/4/8-bit codes, f16 MFMA, fp32 accumulate",
+           "data": "synthetic (device generator, LLaVA-OneVision-shaped)",
+           "config": {"workload": w.name + "-decode-loop", "layers": L, "B": B, "Hq": w.Hq, "Hkv": w.Hkv, "head_dim": w.hd,
+                      "group": w.group, "visual_tokens_per_seq": w.seqs[0].n_vis, "text_tokens_per_seq": w.seqs[0].n_text,
+                      "bit_mix_windows_8_4_2": list(map(int, w.seqs[0].quota)), "splits": nsplit},
+           "us_per_step_graph": round(us, 1), "us_per_layer": round(us / L, 2), "us_per_step_eager": round(us_eager, 1),
+           "bytes_per_step": int(bytes_step), "pct_hbm_peak": round(100 * bytes_step / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 1),
+           "rows_appended_per_sequence": int(len16[0] - w.seqs[0].n_text), "device_status": status, "outputs_finite": finite}
+    print(json.dumps(res), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +167,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload id (3 = long-video 7B-shaped layer)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-loop", action="store_true",
+                    help="time the 28-layer decode loop of the 7B-shaped batch-8 workload (one step = one HIP graph replay)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -70,6 +181,10 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.decode_loop:
+        if args.steps == 40:
+            args.steps = 128
+        return decode_loop(args)
     torch.cuda.set_device(0)
     TD = {synth.F32: torch.float32, synth.BF16: torch.bfloat16, synth.F16: torch.float16}
 

@@ -245,3 +245,47 @@ def test_append_generated_tokens_then_decode():
     W.wq_append_kv(g.ctx, kn, kn, g.pk)                        # every segment had room for exactly three rows
     assert g.ctx.device_status() == 2
     assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+
+
+def test_decode_step_in_a_hip_graph_replays_like_eager():
+    """append + decode of two layers captured in one HIP graph: every replay (with eager work and synchronisation in
+    between) gives what the same steps give when launched one by one on an identical second cache."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(6, 21, 21, 9, (1, 3, 2)), synth.SeqSpec(4, 16, 16, 30, (1, 2, 1))]
+    bt = _custom(41, 128, 64, 2, 7, synth.BF16, specs)
+    w = bt.w
+    cap, off16 = H.capacities(w, slack=6)
+    algo = W.DECODE_MFMA | W.DECODE_FIXED_SHARES
+    runs = [[H.run_gpu(bt, cap=cap, off16=off16, splits=2, algo=algo) for _ in range(2)] for _ in range(2)]   # [eager|graph][layer]
+    rng = np.random.default_rng(3)
+    mk = lambda *s: H.to_dev(synth.round_bf16(rng.standard_normal(s).astype(np.float32)), w.dtype)
+    kn, vn, qn = [mk(w.B, w.Hkv, w.hd) for _ in range(2)], [mk(w.B, w.Hkv, w.hd) for _ in range(2)], [mk(w.B, w.Hq, w.hd) for _ in range(2)]
+    sm = 1.0 / float(np.sqrt(w.hd))
+    outs = [[torch.zeros(w.B, w.Hq, w.hd, device="cuda") for _ in range(2)] for _ in range(2)]
+
+    def step(which):
+        for layer in range(2):
+            g = runs[which][layer]
+            W.wq_append_kv(g.ctx, kn[layer], vn[layer], g.pk)
+            W.wq_decode_attention(g.ctx, qn[layer], g.pk, sm, 2, 400, algo, out=outs[which][layer])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    for g in runs[1]:
+        g.ctx.set_stream(side)
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(1)
+    for rep in range(4):
+        step(0)                                   # eager, on the default stream
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        torch.cuda.synchronize()
+        for layer in range(2):
+            assert torch.equal(outs[0][layer], outs[1][layer]), f"replay {rep}, layer {layer}"
+            assert torch.equal(runs[0][layer].pk.len16, runs[1][layer].pk.len16)
+        assert float(outs[1][0].abs().max()) > 0
+    assert runs[1][0].ctx.device_status() == 0
