@@ -173,6 +173,7 @@ struct WaveState {
 // 32-token blocks in flight per wavefront and class: enough bytes to keep the memory system busy while a block
 // is being worked on (a 2-bit block is 2.5 KB, an 8-bit block 8.5 KB)
 constexpr int WQ_D2 = 4, WQ_D4 = 3, WQ_D8 = 2;
+constexpr int WQ_FIRST_TICKETS = 4;    // blocks every wavefront starts with (the deepest pipeline's fill)
 constexpr int WQ_WAVES = 8;            // wavefronts per workgroup: one workgroup per compute unit, two wavefronts per SIMD
 constexpr float WQ_MAX_SLACK = 8.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
 constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
@@ -306,7 +307,19 @@ struct Tickets {
     unsigned* ctr;      // the workgroup's counter (LDS)
     unsigned held, end; // tickets held: [held, end)
     bool spent;         // none left: another one is due
+    bool synced;        // this wavefront has passed the workgroup's set-up barrier
 };
+
+// The set-up barrier (staged query operands, initial value of the block counter) is taken by every wavefront
+// exactly once: after the first loads of the first class it walks have been issued, or, by a wavefront that has
+// no blocks at all, before the final merge.
+__device__ __forceinline__ void pass_setup_barrier(Tickets& t)
+{
+    if (!t.synced) {
+        __syncthreads();
+        t.synced = true;
+    }
+}
 
 // lane 0 draws n tickets; the first one's value is valid in lane 0 once the LDS operation has returned
 __device__ __forceinline__ unsigned draw_tickets(unsigned* ctr, unsigned n)
@@ -424,6 +437,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
         bi[d] = next_block(src, tk, DEPTH - d);
         if (bi[d] >= 0) load(bi[d], f[d]);
     }
+    pass_setup_barrier(tk);
     U4 Bqw[NK];
     float qexp, qsum;
     fetch_q_operands<HD>(sm, C, Bqw, qexp, qsum);
@@ -575,6 +589,7 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
     const int64_t rstride = (int64_t)kv.Hkv * HD;
     const uint16_t* k16 = static_cast<const uint16_t*>(kv.k16) + (int64_t)kvh * HD;
     const uint16_t* v16 = static_cast<const uint16_t*>(kv.v16) + (int64_t)kvh * HD;
+    pass_setup_barrier(tk);
     U4 Bq[NK];
     float qexp, qsum;
     fetch_q_operands<HD>(sm, 3, Bq, qexp, qsum);
@@ -734,7 +749,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     cls_len[3] = a.kv.len16[b];
     cls_off[3] = a.kv.off16[b];
-    if (tid == 0) sm.next_ticket = 0u;
+    if (tid == 0) sm.next_ticket = (unsigned)(WQ_FIRST_TICKETS * WQ_WAVES);
     // ---- the query operands of all classes, one class per wavefront ----
     stage_q_operands<HD>(a, sm, b, kvh, wave, bf16seg);
 
@@ -742,8 +757,12 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     //      fixed share of it (none unless the launch asks for fixed shares: then there is no pool) ----
     Tickets tk;
     tk.ctr = &sm.next_ticket;
-    tk.held = tk.end = 0u;
-    tk.spent = true;                       // the first tickets are drawn when the first class is entered
+    // the first tickets are fixed (WQ_FIRST_TICKETS consecutive blocks per wavefront), so that the first loads can go
+    // out before the workgroup's set-up barrier; the counter starts behind them
+    tk.held = (unsigned)(wave * WQ_FIRST_TICKETS);
+    tk.end = tk.held + (unsigned)WQ_FIRST_TICKETS;
+    tk.spent = false;
+    tk.synced = false;
     BlockSrc src[4];
     {
         int nb[4];
@@ -776,7 +795,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             base += (float)nb[c] * a.wgt[c];
         }
     }
-    __syncthreads();                       // the operands of all classes are in LDS, the block counter is zero
 
     WQ_STAMP(1);
 #ifdef WQ_TIMELINE
@@ -819,6 +837,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     l += __shfl_xor(l, 32, 64);
     am += __shfl_xor(am, 16, 64);
     am += __shfl_xor(am, 32, 64);
+    pass_setup_barrier(tk);
     __syncthreads();                               // every wave is done with the run-time part of LDS
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) {
