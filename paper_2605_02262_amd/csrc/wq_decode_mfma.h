@@ -185,7 +185,7 @@ struct MfmaSmem {
             uint32_t meta[WQ_WAVES][2][64];              // per wave: K and V metadata words of the current block
             uint16_t vt[WQ_WAVES][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
         } run;
-        float O[WQ_WAVES][WQ_MAX_REP][HD];               // per-wave numerators for the merge (after the loops)
+        float O[WQ_WAVES][WQ_MAX_REP][HD + 1];           // per-wave numerators for the merge (after the loops); rows one bank apart
     };
     U4 bq[4][HD / 32][64];                               // query operands of the four classes (index 3 = 16-bit segment), per lane
     float qx[4][2][64];                                  // ... with the head's power of two and the group's query sum
@@ -842,12 +842,8 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
-            float4 v;
-            v.x = fmaf(st.O[ct][0], 16777216.0f, am);
-            v.y = fmaf(st.O[ct][1], 16777216.0f, am);
-            v.z = fmaf(st.O[ct][2], 16777216.0f, am);
-            v.w = fmaf(st.O[ct][3], 16777216.0f, am);
-            *reinterpret_cast<float4*>(&sm.O[wave][h][16 * ct + 4 * j]) = v;
+#pragma unroll
+            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
         }
     }
     if (j == 0 && g == 0) {
