@@ -118,7 +118,8 @@ int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens);
  * total_vis, total_txt, total_win : host copies of vis_off[B], txt_off[B], win_off[B] (grid bounds)
  * algo    : WQ_SCORE_POOLED uses the identity score = (mean_j t_j/|t_j|) . (mean_k w_k/|w_k|) and reads each
  *           embedding once (HBM-bound); WQ_SCORE_PAIRWISE_MFMA forms the [tokens x text] product on the
- *           matrix cores (bf16/fp16 inputs only) and normalises/reduces it in the epilogue.
+ *           matrix cores (bf16/fp16 inputs only, D a multiple of 128, 16-byte aligned embeddings, at most
+ *           4 GiB of text embeddings) and normalises/reduces it in the epilogue.
  * scores  [total_win] device fp32, written.   Accumulation is fp32; no atomics, results are deterministic. */
 int wq_window_scores(wq_ctx* ctx, const void* vis_emb, const void* txt_emb, int dtype, int B, int D,
                      const int32_t* vis_off, const int32_t* txt_off, const int32_t* win_size, const int32_t* win_off,

@@ -10,6 +10,8 @@
 // All accumulation is fp32 and every reduction has a fixed order (no atomics): results are deterministic.
 #include "wq_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int WAVE = 64;
@@ -169,11 +171,22 @@ __global__ __launch_bounds__(256) void k_window_mean(const float* __restrict__ t
 
 // ---- pairwise path on the matrix cores --------------------------------------------------------------------------
 // The similarity equation taken literally: C = E_v E_t^T (every window token against every text token), then
-// c_k = 1/(N |w_k|) sum_j C[k,j] / |t_j|.  One workgroup owns 128 visual rows of one sequence and walks the text
-// tokens in column tiles of 128; per column tile a classic LDS-tiled GEMM over D in steps of 32
-// (v_mfma_f32_16x16x32 bf16/f16, four wavefronts as 2x2, 64x64 per wavefront), whose epilogue multiplies by
-// 1/|t_j| and reduces over the columns, so C never leaves the registers.  |w_k|^2 comes from the A tiles on their
-// way to LDS during the first column tile.  Reductions have a fixed order: results are deterministic.
+// c_k = 1/(N |w_k|) sum_j C[k,j] / |t_j|.  One workgroup of eight wavefronts owns 128 visual rows of one sequence and
+// walks the text tokens in passes of up to 512 columns, so that the visual rows are read from memory once when the
+// sequence has at most 512 text tokens.  Over D it goes in steps of 64 elements (one 128-byte line per row):
+//   visual rows   global -> registers (a step ahead) -> LDS (two buffers, one barrier per step) -> A operands of
+//                 all wavefronts;
+//   text rows     each wavefront owns 64 columns of the pass, so its B operands are private to it.  An operand is
+//                 16 rows x 16 bytes per lane group: read from the row-major text that is 64 scattered pieces per
+//                 load, which the memory pipeline takes one lane at a time.  k_pack_text therefore rewrites the text
+//                 once (a few MB) into operand order, [tile of 16 rows][32 elements of D][lane][8 elements], so that
+//                 a wavefront's operand is one contiguous KB; it goes from there (L2) straight into registers, half
+//                 a step ahead.
+// A wavefront multiplies a [16 RT] x 64 tile per step with v_mfma_f32_16x16x32 bf16/f16 (RT = 8 row tiles: 128
+// accumulator registers, two wavefronts per SIMD).  Sequences with at most 256 (128) text tokens use passes of 256
+// (128) columns and split the rows between wavefronts instead, RT = 4 (2).  The epilogue of a pass multiplies by
+// 1/|t_j| and reduces over the columns, so C never leaves the registers.  |w_k|^2 comes from the visual rows on
+// their way to LDS during the first pass.  Reductions have a fixed order: results are deterministic.
 typedef float floatx4s __attribute__((ext_vector_type(4)));
 typedef _Float16 half8s __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
@@ -187,6 +200,10 @@ __device__ __forceinline__ floatx4s mfma_s(const uint4& a, const uint4& b, float
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8s, a), __builtin_bit_cast(half8s, b), c, 0, 0, 0);
 }
 
+typedef __bf16 bf16x2s __attribute__((ext_vector_type(2)));
+typedef _Float16 half2s __attribute__((ext_vector_type(2)));
+
+// sum of the squares of eight 16-bit elements (v_dot2_f32: both products and the sum in fp32)
 template <bool BF>
 __device__ __forceinline__ float sumsq8(const uint4& u)
 {
@@ -194,121 +211,209 @@ __device__ __forceinline__ float sumsq8(const uint4& u)
     float s = 0.f;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
-        const float a = BF ? __uint_as_float(w[k] << 16) : wq_f16_bits_to_float(w[k] & 0xFFFFu);
-        const float b = BF ? __uint_as_float(w[k] & 0xFFFF0000u) : wq_f16_bits_to_float(w[k] >> 16);
-        s = fmaf(a, a, s);
-        s = fmaf(b, b, s);
+        if constexpr (BF) {
+            const bf16x2s p = __builtin_bit_cast(bf16x2s, w[k]);
+            s = __builtin_amdgcn_fdot2_f32_bf16(p, p, s, false);
+        } else {
+            const half2s p = __builtin_bit_cast(half2s, w[k]);
+            s = __builtin_amdgcn_fdot2(p, p, s, false);
+        }
     }
     return s;
 }
 
-constexpr int SG_PITCH = 40;     // 16-bit elements per LDS row: 32 of the k-step + 8 of padding (80 bytes)
+constexpr int PA_THREADS = 512, PA_WAVES = 8;
+constexpr int PA_ROWS = 128;             // visual rows per workgroup
+constexpr int PA_KS = 64;                // elements of D per step
+constexpr int PA_PITCH = PA_KS + 8;      // LDS row pitch in elements (144 bytes): 16-byte reads of 16 rows hit 64 distinct banks
+constexpr int PA_WCOLS = 64;             // text columns per wavefront and pass
+constexpr int PA_CT = PA_WCOLS / 16;     // column tiles per wavefront
 
-template <bool BF>
-__global__ __launch_bounds__(256) void k_pair_mfma(const uint16_t* __restrict__ vis, const uint16_t* __restrict__ txt,
-                                                   const float* __restrict__ inv_tnorm, int D,
-                                                   const int32_t* __restrict__ vis_off, const int32_t* __restrict__ txt_off,
-                                                   float* __restrict__ tok_score)
+// Tiles of 16 text rows in operand order.  Sequence b's tiles start at tile txt_off[b] / 16 + b: room for
+// ceil(N_b / 16) tiles each, whatever the lengths.  Rows past N_b are zero.
+__device__ __forceinline__ int pair_tile_base(const int32_t* txt_off, int b) { return (txt_off[b] >> 4) + b; }
+
+__global__ __launch_bounds__(256) void k_pack_text(const uint16_t* __restrict__ txt, int D, int B, const int32_t* __restrict__ txt_off,
+                                                   int64_t total_tiles, uint4* __restrict__ packed)
 {
-    __shared__ __align__(16) uint16_t sA[128 * SG_PITCH];
-    __shared__ __align__(16) uint16_t sB[128 * SG_PITCH];
-    __shared__ float sW[128];          // 1/|t_j| of the column tile (0 past the end)
-    __shared__ float sR[2][128];       // row sums, one array per column half of the wavefront grid
-    __shared__ float sN[128];          // |w_k|^2
-    const int b = blockIdx.y;
-    const int m0 = vis_off[b], M = vis_off[b + 1] - m0;
-    const int n0 = txt_off[b], N = txt_off[b + 1] - n0;
-    const int row0 = blockIdx.x * 128;
-    if (row0 >= M) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;             // 2 x 2 wavefronts, 64 x 64 each
-    const int lj = lane >> 4, lm = lane & 15;
-    // global -> LDS staging: 128 rows x 64 bytes = 512 pieces of 16 bytes, two per thread (pieces tid, tid + 256)
-    const int pr0 = tid >> 2, pp = tid & 3;              // row and 16-byte part of piece tid; piece tid+256: row + 64
-    const int ra0 = min(row0 + pr0, M - 1), ra1 = min(row0 + pr0 + 64, M - 1);      // rows past the end re-read the last
-    const uint16_t* pa0 = vis + ((int64_t)m0 + ra0) * D + pp * 8;
-    const uint16_t* pa1 = vis + ((int64_t)m0 + ra1) * D + pp * 8;
-    if (tid < 128) {
-        sR[0][tid] = 0.f;
-        sR[1][tid] = 0.f;
+    const int chunks = D / 32;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // (tile, chunk of 32 elements)
+    if (item >= total_tiles * chunks) return;
+    const int64_t tile = item / chunks;
+    const int c = (int)(item - tile * chunks), lane = threadIdx.x & 63, lm = lane & 15, lj = lane >> 4;
+    // the sequence that owns this tile: the last b with pair_tile_base(b) <= tile
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pair_tile_base(txt_off, mid) <= tile) lo = mid; else hi = mid - 1;
     }
-    float nsq0 = 0.f, nsq1 = 0.f;
-    const int ksteps = D / 32;
-    for (int c0 = 0; c0 < N; c0 += 128) {
-        const int rb0 = min(c0 + pr0, N - 1), rb1 = min(c0 + pr0 + 64, N - 1);
-        const uint16_t* pb0 = txt + ((int64_t)n0 + rb0) * D + pp * 8;
-        const uint16_t* pb1 = txt + ((int64_t)n0 + rb1) * D + pp * 8;
-        __syncthreads();                                  // previous tile's epilogue has read sW
-        if (tid < 128) sW[tid] = (c0 + tid < N) ? inv_tnorm[n0 + c0 + tid] : 0.f;
-        floatx4s acc[4][4];
+    const int n0 = txt_off[lo], N = txt_off[lo + 1] - n0;
+    const int row = (int)(tile - pair_tile_base(txt_off, lo)) * 16 + lm;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < N) v = *reinterpret_cast<const uint4*>(txt + ((int64_t)n0 + row) * D + c * 32 + lj * 8);
+    packed[item * 64 + lane] = v;
+}
+
+struct PairSmem {
+    __attribute__((aligned(16))) uint16_t A[2][PA_ROWS * PA_PITCH];
+    float W[PA_WAVES * PA_WCOLS];        // 1/|t_j| of the pass (0 past the end)
+    float R[PA_WAVES][PA_ROWS];          // row sums, one array per column block
+    float N2[PA_ROWS];                   // |w_k|^2
+};
+
+// RT row tiles of 16 per wavefront: 8 -> the eight wavefronts are eight column blocks of a 512-column pass,
+// 4 -> two row halves x four column blocks (256 columns), 2 -> four row quarters x two column blocks (128).
+template <bool BF, int RT>
+__device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
+                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, float (&nsq)[2])
+{
+    constexpr int NCB = RT, PASS = NCB * PA_WCOLS;        // column blocks per pass
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lj = lane >> 4, lm = lane & 15;
+    const int cb = wave % NCB, rb = (wave / NCB) * RT;
+    const int pp = tid & 7, pr = tid >> 3;                // visual rows to LDS: thread -> 16-byte piece pp of rows pr, pr + 64
+    const uint16_t* pa[2];
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+    for (int u = 0; u < 2; u++) pa[u] = va + (int64_t)min(row0 + pr + 64 * u, M - 1) * D + pp * 8;   // rows past the end re-read the last
+    const int steps = D / PA_KS, ntile = (N + 15) >> 4;
+
+    auto load_a = [&](int s, uint4 (&ga)[2]) {
 #pragma unroll
-            for (int k = 0; k < 4; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
-        uint4 ga0 = *reinterpret_cast<const uint4*>(pa0), ga1 = *reinterpret_cast<const uint4*>(pa1);
-        uint4 gb0 = *reinterpret_cast<const uint4*>(pb0), gb1 = *reinterpret_cast<const uint4*>(pb1);
-        for (int ks = 0; ks < ksteps; ks++) {
-            __syncthreads();                              // everyone is done reading the previous k-step's tiles
-            *reinterpret_cast<uint4*>(&sA[pr0 * SG_PITCH + pp * 8]) = ga0;
-            *reinterpret_cast<uint4*>(&sA[(pr0 + 64) * SG_PITCH + pp * 8]) = ga1;
-            *reinterpret_cast<uint4*>(&sB[pr0 * SG_PITCH + pp * 8]) = gb0;
-            *reinterpret_cast<uint4*>(&sB[(pr0 + 64) * SG_PITCH + pp * 8]) = gb1;
-            if (c0 == 0) {
-                nsq0 += sumsq8<BF>(ga0);
-                nsq1 += sumsq8<BF>(ga1);
-            }
-            __syncthreads();
-            if (ks + 1 < ksteps) {                        // next k-step's pieces fly while this one is multiplied
-                const int o = (ks + 1) * 32;
-                ga0 = *reinterpret_cast<const uint4*>(pa0 + o);
-                ga1 = *reinterpret_cast<const uint4*>(pa1 + o);
-                gb0 = *reinterpret_cast<const uint4*>(pb0 + o);
-                gb1 = *reinterpret_cast<const uint4*>(pb1 + o);
-            }
-            uint4 fa[4], fb[4];
+        for (int u = 0; u < 2; u++) ga[u] = *reinterpret_cast<const uint4*>(pa[u] + s * PA_KS);
+    };
+    // count: 1 when these rows have not been summed into |w_k|^2 yet, else 0 (a factor, not a branch: the loop body
+    // stays one block, which keeps the wait counts of the loads in flight exact)
+    auto store_a = [&](int buf, const uint4 (&ga)[2], float count) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                fa[i] = *reinterpret_cast<const uint4*>(&sA[(wr * 64 + i * 16 + lm) * SG_PITCH + lj * 8]);
-                fb[i] = *reinterpret_cast<const uint4*>(&sB[(wc * 64 + i * 16 + lm) * SG_PITCH + lj * 8]);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-#pragma unroll
-                for (int k = 0; k < 4; k++) acc[i][k] = mfma_s<BF>(fa[i], fb[k], acc[i][k]);
+        for (int u = 0; u < 2; u++) {
+            *reinterpret_cast<uint4*>(&sm.A[0][(pr + 64 * u) * PA_PITCH + pp * 8] + buf * (PA_ROWS * PA_PITCH)) = ga[u];
+            nsq[u] = fmaf(sumsq8<BF>(ga[u]), count, nsq[u]);
         }
-        // epilogue: lane holds rows 4*lj + e of row tile i, column lm of column tile k
+    };
+
+    for (int c0 = 0; c0 < N; c0 += PASS) {
+        const bool first_pass = c0 == 0;
+        // this wavefront's column tiles in the packed text: byte offsets (32 bits: checked by the host) of the lane's
+        // 16 bytes in the tile's first operand; tiles past the end re-read the last one (their weights are zero)
+        uint32_t ob[PA_CT];
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            float rs[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < PA_CT; k++)
+            ob[k] = (uint32_t)min((c0 + cb * PA_WCOLS) / 16 + k, ntile - 1) * (uint32_t)(D / 32) * 1024u + (uint32_t)lane * 16u;
+        auto load_b = [&](int s, int h, uint4 (&gb)[PA_CT]) {      // half h of step s: elements 64 s + 32 h .. + 31
 #pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const float w = sW[wc * 64 + k * 16 + lm];
+            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tbb + (ob[k] + (uint32_t)((2 * s + h) * 1024)));
+        };
+        floatx4s acc[RT][PA_CT];
 #pragma unroll
-                for (int e = 0; e < 4; e++) rs[e] = fmaf(acc[i][k][e], w, rs[e]);
+        for (int i = 0; i < RT; i++)
+#pragma unroll
+            for (int k = 0; k < PA_CT; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
+
+        __syncthreads();                                  // the previous pass is done with W and with both A buffers
+        for (int k = tid; k < PASS; k += PA_THREADS) sm.W[k] = (c0 + k < N) ? inv_tn[c0 + k] : 0.f;
+        // gx, gy: B operands of the first and second half of a step; ga0, ga1: visual rows of the even and odd steps
+        uint4 ga0[2], ga1[2], gx[PA_CT], gy[PA_CT];
+        load_b(0, 0, gx);
+        load_b(0, 1, gy);
+        load_a(0, ga0);
+        load_a(1, ga1);                                   // steps >= 2 (D is a multiple of 128)
+        store_a(0, ga0, first_pass ? 1.f : 0.f);
+
+        // step s: LDS buffer s % 2 x (gx, gy).  gload takes the rows of step s + 2 (sent for first: two steps to
+        // arrive from memory), gstore holds the rows of step s + 1 and goes to the other LDS buffer at the end.
+        // Past the end the last steps' operands are fetched again, unused.  No branches: the body stays one block,
+        // which keeps the wait counts of the loads in flight exact.
+        auto step = [&](int s, int buf, uint4 (&gload)[2], const uint4 (&gstore)[2]) {
+            load_a(min(s + 2, steps - 1), gload);
+            const int sn = min(s + 1, steps - 1);
+            __syncthreads();                              // A tile of step s is written; the other buffer is free
+            __builtin_amdgcn_sched_barrier(0);
+            const uint16_t* sa = &sm.A[0][(rb * 16 + lm) * PA_PITCH + lj * 8] + buf * (PA_ROWS * PA_PITCH);
+            // 2 RT groups of PA_CT products: row tile i, half h; the A operand of the next group is read from LDS
+            // while this one is multiplied.  Each half's B operands are replaced as soon as their last product has
+            // issued, so they have half a step to arrive (the text rows are in L2).
+            auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + (g % RT) * 16 * PA_PITCH + (g / RT) * 32); };
+            uint4 f[3];
+            f[0] = read_a(0);
+            f[1] = read_a(1);
+#pragma unroll
+            for (int g = 0; g < 2 * RT; g++) {
+                const int i = g % RT, h = g / RT;
+                if (g + 2 < 2 * RT) f[(g + 2) % 3] = read_a(g + 2);       // two groups ahead
+#pragma unroll
+                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], h == 0 ? gx[k] : gy[k], acc[i][k]);
+                if (g == RT - 1) load_b(sn, 0, gx);
+                __builtin_amdgcn_sched_barrier(0);        // issue order as written: one LDS read, then the group's products
             }
+            load_b(sn, 1, gy);
+            __builtin_amdgcn_sched_barrier(0);            // the rows below were sent for two steps ago: nothing before this waits for them
+            store_a(buf ^ 1, gstore, (first_pass && s + 1 < steps) ? 1.f : 0.f);
+        };
+        for (int s = 0; s < steps; s += 2) {
+            step(s, 0, ga0, ga1);
+            step(s + 1, 1, ga1, ga0);
+        }
+
+        // epilogue: lane holds rows 4 lj + e of row tile i, column lm of column tile k
+        float wk[PA_CT];
+#pragma unroll
+        for (int k = 0; k < PA_CT; k++) wk[k] = sm.W[cb * PA_WCOLS + k * 16 + lm];
+#pragma unroll
+        for (int i = 0; i < RT; i++) {
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                float v = rs[e];
+                float v = 0.f;
+#pragma unroll
+                for (int k = 0; k < PA_CT; k++) v = fmaf(acc[i][k][e], wk[k], v);
                 v += __shfl_xor(v, 1, 64);
                 v += __shfl_xor(v, 2, 64);
                 v += __shfl_xor(v, 4, 64);
                 v += __shfl_xor(v, 8, 64);
-                if (lm == 0) sR[wc][wr * 64 + i * 16 + 4 * lj + e] += v;     // one writer per (column half, row)
+                if (lm == 0) sm.R[cb][(rb + i) * 16 + 4 * lj + e] += v;     // one writer per (column block, row)
             }
         }
     }
-    // |w_k|^2: the four threads that staged a row hold its four 16-byte parts of every k-step
-    nsq0 += __shfl_xor(nsq0, 1, 64);
-    nsq0 += __shfl_xor(nsq0, 2, 64);
-    nsq1 += __shfl_xor(nsq1, 1, 64);
-    nsq1 += __shfl_xor(nsq1, 2, 64);
-    if (pp == 0) {
-        sN[pr0] = nsq0;
-        sN[pr0 + 64] = nsq1;
+}
+
+template <bool BF>
+__global__ __launch_bounds__(PA_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_pair_mfma(const uint16_t* __restrict__ vis, const uint4* __restrict__ packed_txt,
+                                                          const float* __restrict__ inv_tnorm, int D,
+                                                          const int32_t* __restrict__ vis_off, const int32_t* __restrict__ txt_off,
+                                                          float* __restrict__ tok_score)
+{
+    __shared__ PairSmem sm;
+    const int b = blockIdx.y;
+    const int m0 = vis_off[b], M = vis_off[b + 1] - m0;
+    const int n0 = txt_off[b], N = txt_off[b + 1] - n0;
+    const int row0 = blockIdx.x * PA_ROWS;
+    if (row0 >= M) return;
+    const int tid = threadIdx.x;
+    for (int k = tid; k < PA_WAVES * PA_ROWS; k += PA_THREADS) sm.R[k / PA_ROWS][k % PA_ROWS] = 0.f;
+    float nsq[2] = {0.f, 0.f};
+    const uint16_t* va = vis + (int64_t)m0 * D;
+    const char* tb = reinterpret_cast<const char*>(packed_txt) + (int64_t)pair_tile_base(txt_off, b) * (D / 32) * 1024;
+    if (N > 4 * PA_WCOLS)
+        pair_body<BF, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
+    else if (N > 2 * PA_WCOLS)
+        pair_body<BF, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
+    else
+        pair_body<BF, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
+    // |w_k|^2: the eight threads that staged a row hold its eight 16-byte pieces of every step
+    const int pp = tid & 7, pr = tid >> 3;
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+        float v = nsq[u];
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        v += __shfl_xor(v, 4, 64);
+        if (pp == 0) sm.N2[pr + 64 * u] = v;
     }
     __syncthreads();
-    if (tid < 128 && row0 + tid < M) {
-        const float r = sR[0][tid] + sR[1][tid], nn = sN[tid];
+    if (tid < PA_ROWS && row0 + tid < M) {
+        float r = 0.f;
+#pragma unroll
+        for (int c = 0; c < PA_WAVES; c++) r += sm.R[c][tid];
+        const float nn = sm.N2[tid];
         tok_score[m0 + row0 + tid] = (nn > 0.f && N > 0) ? r / (sqrtf(nn) * (float)N) : 0.f;
     }
 }
@@ -343,11 +448,15 @@ int run_pooled(wq_ctx* ctx, const void* vis_, const void* txt_, int B, int D, co
 
 }  // namespace
 
+// tiles of 16 text rows that the packed text of B sequences with total_txt rows can take (see pair_tile_base)
+static int64_t pair_total_tiles(int B, int64_t total_txt) { return total_txt / 16 + B; }
+
 size_t wq_scores_ws_bytes(int B, int64_t total_vis, int64_t total_txt, int D)
 {
     if (B <= 0 || D <= 0) return 0;
     return wq_align256(sizeof(float) * (size_t)(total_txt > 0 ? total_txt : 1)) + wq_align256(sizeof(float) * (size_t)B * D) +
-           wq_align256(sizeof(float) * (size_t)(total_vis > 0 ? total_vis : 1));
+           wq_align256(sizeof(float) * (size_t)(total_vis > 0 ? total_vis : 1)) +
+           wq_align256((size_t)pair_total_tiles(B, total_txt) * 16 * (size_t)D * 2);      // text in operand order (pairwise path)
 }
 
 int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, int B, int D, const int32_t* vis_off,
@@ -355,14 +464,19 @@ int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, i
                      int64_t total_txt, int64_t total_win, int algo, float* scores)
 {
     if (algo == WQ_SCORE_PAIRWISE_MFMA) {
-        if (D % 32 != 0) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path needs D %% 32 == 0");
+        if (D % 128 != 0) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path needs D %% 128 == 0");
         if ((reinterpret_cast<uintptr_t>(vis) | reinterpret_cast<uintptr_t>(txt)) % 16 != 0)
             return wq_fail(ctx, WQ_ERR_ARG, "embeddings must be 16-byte aligned");
+        const int64_t tiles = pair_total_tiles(B, total_txt);
+        if (tiles * 16 * (int64_t)D * 2 > (int64_t)UINT32_MAX)
+            return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path takes at most 4 GiB of text embeddings");
         char* ws = ctx->ws + WQ_WS_HEADER;
         float* inv_norm = reinterpret_cast<float*>(ws);
         ws += wq_align256(sizeof(float) * (size_t)(total_txt > 0 ? total_txt : 1));
         ws += wq_align256(sizeof(float) * (size_t)B * D);
         float* tok_score = reinterpret_cast<float*>(ws);
+        ws += wq_align256(sizeof(float) * (size_t)(total_vis > 0 ? total_vis : 1));
+        uint4* packed = reinterpret_cast<uint4*>(ws);
         hipStream_t st = ctx->stream;
         const uint16_t* v16 = static_cast<const uint16_t*>(vis);
         const uint16_t* t16 = static_cast<const uint16_t*>(txt);
@@ -375,12 +489,14 @@ int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, i
                                    static_cast<const __half*>(txt), D, total_txt, inv_norm);
         }
         if (total_vis > 0) {
+            const int64_t items = tiles * (D / 32);
+            hipLaunchKernelGGL(k_pack_text, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, st, t16, D, B, txt_off, tiles, packed);
             // any one sequence has at most total_vis rows: row tiles past a sequence's end return at once
-            const dim3 grid((unsigned)((total_vis + 127) / 128), B);
+            const dim3 grid((unsigned)((total_vis + PA_ROWS - 1) / PA_ROWS), B);
             if (dtype == WQ_BF16)
-                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(256), 0, st, v16, t16, inv_norm, D, vis_off, txt_off, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, tok_score);
             else
-                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(256), 0, st, v16, t16, inv_norm, D, vis_off, txt_off, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, tok_score);
         }
         hipLaunchKernelGGL(k_window_mean, dim3((unsigned)((total_win + 3) / 4)), dim3(256), 0, st, tok_score, B, vis_off, txt_off,
                            win_size, win_off, total_win, scores);
