@@ -303,6 +303,10 @@ def main():
     W.wq_probe_stream(ctx, big[:half], big[half:])      # plain copy of 1 GiB: the reference for byte counters
     torch.cuda.synchronize()
     del big
+    # ---- matrix-core rate this GPU sustains on register operands that change from product to product ---------
+    W.wq_probe_mfma(ctx, True, 2048, 100)
+    probe_flops = W.wq_probe_mfma(ctx, True, 2048, 1000)
+    mfma_tflops = probe_flops / (timed(lambda i: W.wq_probe_mfma(ctx, True, 2048, 1000), 3) * 1e-6) / 1e12
 
     res = {
         "metric": "mixed-precision KV decode-attention GB/s (% HBM peak) + us/step at 50K ctx",
@@ -330,7 +334,9 @@ def main():
             "window_scores_pairwise_mfma": {"bound": "mfma", "unit": "TFLOP/s", "peak": 2500.0, "us": round(scm_us, 1),
                                             "achieved": round(pair_flops / (scm_us * 1e-6) / 1e12, 1),
                                             "frac": round(pair_flops / (scm_us * 1e-6) / 1e12 / 2500.0, 4),
-                                            "note": "literal pairwise form on the matrix cores; the default is the pooled form"},
+                                            "probe_random_operands_TFLOPs": round(mfma_tflops, 1),
+                                            "note": "literal pairwise form on the matrix cores; the default is the pooled form; "
+                                                    "the probe is the rate of the same instruction on register operands"},
             "window_scores": {"bound": "hbm", "unit": "GB/s",
                               "achieved": round((total_vis + total_txt) * w.D * 2 / (st_mean[0] * 1e-6) / 1e9, 1)
                               if st_mean[0] > 0 else None}},

@@ -214,11 +214,17 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
 int wq_decode_timing(wq_ctx* ctx, int enable);
 int wq_decode_times_us(wq_ctx* ctx, float* us, int n);
 
-/* ---- measurement probe (not part of the method; for callers that cannot time a plain kernel themselves) ----
- * Streams `bytes` (multiple of 16) of device memory with 16-byte loads from `blocks` workgroups of 256 lanes:
+/* ---- measurement probes (not part of the method; for callers that cannot time a plain kernel themselves) ----
+ * wq_probe_stream streams `bytes` (multiple of 16) of device memory with 16-byte loads from `blocks` workgroups of 256 lanes:
  * read-only when dst is NULL, a plain copy otherwise.  Gives the achievable HBM rate and the reference that
  * hardware byte counters are scaled by.                                                                       */
 int wq_probe_stream(wq_ctx* ctx, const void* src, void* dst, int64_t bytes, int blocks);
+/* Runs `workgroups` x 8 wavefronts of `iters` x 32 independent v_mfma_f32_16x16x32_bf16 products on register
+ * operands (no memory traffic): all ones when random_operands == 0, else random values that change from product to
+ * product.  Gives the matrix-core rate this GPU sustains, which depends on the data (the clock drops under
+ * load): the figure the pairwise scoring kernel is to be read against.  *flops (host, may be NULL) receives the
+ * floating-point operations of the launch.  Needs a workspace (one word of it is the kernel's sink).               */
+int wq_probe_mfma(wq_ctx* ctx, int random_operands, int workgroups, int iters, double* flops);
 
 #ifdef __cplusplus
 }

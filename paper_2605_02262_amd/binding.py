@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
         L.wq_append_kv.argtypes = [vp, vp, vp, i32, i32, C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
+        L.wq_probe_mfma.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_double)]
         L.wq_decode_timing.argtypes = [vp, i32]
         L.wq_decode_times_us.argtypes = [vp, C.POINTER(C.c_float), i32]
         _lib = L
@@ -251,6 +252,13 @@ def wq_decode_attention(ctx: Context, q, kv: PackedKV, sm_scale: float, num_spli
     ctx.check(lib().wq_decode_attention(ctx.handle, _ptr(q), _dtype_id(q), B, Hq, C.byref(kv.desc), sm_scale, num_splits,
                                         max_seq_tokens, algo, _ptr(out), _ptr(lse)))
     return out
+
+
+def wq_probe_mfma(ctx: Context, random_operands: bool, workgroups: int = 2048, iters: int = 1000) -> float:
+    """Launches the matrix-core rate probe; returns the floating-point operations of the launch."""
+    fl = C.c_double(0.0)
+    ctx.check(lib().wq_probe_mfma(ctx.handle, int(random_operands), workgroups, iters, C.byref(fl)))
+    return fl.value
 
 
 def wq_probe_stream(ctx: Context, src: torch.Tensor, dst: Optional[torch.Tensor] = None, blocks: int = 4096):

@@ -173,20 +173,24 @@ __global__ __launch_bounds__(256) void k_window_mean(const float* __restrict__ t
 // The similarity equation taken literally: C = E_v E_t^T (every window token against every text token), then
 // c_k = 1/(N |w_k|) sum_j C[k,j] / |t_j|.  One workgroup of eight wavefronts owns 128 visual rows of one sequence and
 // walks the text tokens in passes of up to 512 columns, so that the visual rows are read from memory once when the
-// sequence has at most 512 text tokens.  Over D it goes in steps of 64 elements (one 128-byte line per row):
+// sequence has at most 512 text tokens.  Over D it goes in steps of 128 elements (two 128-byte lines per row):
 //   visual rows   global -> registers (a step ahead) -> LDS (two buffers, one barrier per step) -> A operands of
-//                 all wavefronts;
+//                 all wavefronts, read two products groups ahead of their use;
 //   text rows     each wavefront owns 64 columns of the pass, so its B operands are private to it.  An operand is
 //                 16 rows x 16 bytes per lane group: read from the row-major text that is 64 scattered pieces per
 //                 load, which the memory pipeline takes one lane at a time.  k_pack_text therefore rewrites the text
 //                 once (a few MB) into operand order, [tile of 16 rows][32 elements of D][lane][8 elements], so that
-//                 a wavefront's operand is one contiguous KB; it goes from there (L2) straight into registers, half
-//                 a step ahead.
+//                 a wavefront's operand is one contiguous KB; it goes from there (L2) straight into registers, a
+//                 quarter of a step ahead.
 // A wavefront multiplies a [16 RT] x 64 tile per step with v_mfma_f32_16x16x32 bf16/f16 (RT = 8 row tiles: 128
 // accumulator registers, two wavefronts per SIMD).  Sequences with at most 256 (128) text tokens use passes of 256
 // (128) columns and split the rows between wavefronts instead, RT = 4 (2).  The epilogue of a pass multiplies by
 // 1/|t_j| and reduces over the columns, so C never leaves the registers.  |w_k|^2 comes from the visual rows on
 // their way to LDS during the first pass.  Reductions have a fixed order: results are deterministic.
+// With operands that change from product to product the matrix cores of this GPU sustain about two thirds of their
+// nominal rate (wq_probe_mfma measures it: the clock drops under the load); this kernel reaches somewhat more than
+// half of that.  Variants measured and dropped because they were not faster: visual rows sent straight into LDS
+// (no registers) with B operands three quarters of a step ahead; steps of 64 elements.
 typedef float floatx4s __attribute__((ext_vector_type(4)));
 typedef _Float16 half8s __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
@@ -224,10 +228,14 @@ __device__ __forceinline__ float sumsq8(const uint4& u)
 
 constexpr int PA_THREADS = 512, PA_WAVES = 8;
 constexpr int PA_ROWS = 128;             // visual rows per workgroup
-constexpr int PA_KS = 64;                // elements of D per step
-constexpr int PA_PITCH = PA_KS + 8;      // LDS row pitch in elements (144 bytes): 16-byte reads of 16 rows hit 64 distinct banks
+constexpr int PA_KS = 128;               // elements of D per step (two 128-byte lines per row)
+constexpr int PA_Q = PA_KS / 32;         // quarters of a step: one matrix instruction deep each
+constexpr int PA_PITCH = PA_KS + 16;     // LDS row pitch in elements (288 bytes: rows start 32 bytes apart in the banks; measured free of bank conflicts, a pitch of 272 bytes is not)
 constexpr int PA_WCOLS = 64;             // text columns per wavefront and pass
 constexpr int PA_CT = PA_WCOLS / 16;     // column tiles per wavefront
+constexpr int PA_PPR = PA_KS / 8;        // 16-byte pieces per row and step
+constexpr int PA_RPT = PA_THREADS / PA_PPR;   // rows that the workgroup stages at a time
+constexpr int PA_NU = PA_ROWS / PA_RPT;  // pieces per thread and step
 
 // Tiles of 16 text rows in operand order.  Sequence b's tiles start at tile txt_off[b] / 16 + b: room for
 // ceil(N_b / 16) tiles each, whatever the lengths.  Rows past N_b are zero.
@@ -265,28 +273,28 @@ struct PairSmem {
 // 4 -> two row halves x four column blocks (256 columns), 2 -> four row quarters x two column blocks (128).
 template <bool BF, int RT>
 __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
-                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, float (&nsq)[2])
+                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, float (&nsq)[PA_NU])
 {
     constexpr int NCB = RT, PASS = NCB * PA_WCOLS;        // column blocks per pass
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lj = lane >> 4, lm = lane & 15;
     const int cb = wave % NCB, rb = (wave / NCB) * RT;
-    const int pp = tid & 7, pr = tid >> 3;                // visual rows to LDS: thread -> 16-byte piece pp of rows pr, pr + 64
-    const uint16_t* pa[2];
+    const int pp = tid % PA_PPR, pr = tid / PA_PPR;       // visual rows to LDS: thread -> 16-byte piece pp of rows pr + PA_RPT u
+    const uint16_t* pa[PA_NU];
 #pragma unroll
-    for (int u = 0; u < 2; u++) pa[u] = va + (int64_t)min(row0 + pr + 64 * u, M - 1) * D + pp * 8;   // rows past the end re-read the last
+    for (int u = 0; u < PA_NU; u++) pa[u] = va + (int64_t)min(row0 + pr + PA_RPT * u, M - 1) * D + pp * 8;   // rows past the end re-read the last
     const int steps = D / PA_KS, ntile = (N + 15) >> 4;
 
-    auto load_a = [&](int s, uint4 (&ga)[2]) {
+    auto load_a = [&](int s, uint4 (&ga)[PA_NU]) {
 #pragma unroll
-        for (int u = 0; u < 2; u++) ga[u] = *reinterpret_cast<const uint4*>(pa[u] + s * PA_KS);
+        for (int u = 0; u < PA_NU; u++) ga[u] = *reinterpret_cast<const uint4*>(pa[u] + s * PA_KS);
     };
     // count: 1 when these rows have not been summed into |w_k|^2 yet, else 0 (a factor, not a branch: the loop body
     // stays one block, which keeps the wait counts of the loads in flight exact)
-    auto store_a = [&](int buf, const uint4 (&ga)[2], float count) {
+    auto store_a = [&](int buf, const uint4 (&ga)[PA_NU], float count) {
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
-            *reinterpret_cast<uint4*>(&sm.A[0][(pr + 64 * u) * PA_PITCH + pp * 8] + buf * (PA_ROWS * PA_PITCH)) = ga[u];
+        for (int u = 0; u < PA_NU; u++) {
+            *reinterpret_cast<uint4*>(&sm.A[0][(pr + PA_RPT * u) * PA_PITCH + pp * 8] + buf * (PA_ROWS * PA_PITCH)) = ga[u];
             nsq[u] = fmaf(sumsq8<BF>(ga[u]), count, nsq[u]);
         }
     };
@@ -299,9 +307,9 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
 #pragma unroll
         for (int k = 0; k < PA_CT; k++)
             ob[k] = (uint32_t)min((c0 + cb * PA_WCOLS) / 16 + k, ntile - 1) * (uint32_t)(D / 32) * 1024u + (uint32_t)lane * 16u;
-        auto load_b = [&](int s, int h, uint4 (&gb)[PA_CT]) {      // half h of step s: elements 64 s + 32 h .. + 31
+        auto load_b = [&](int c, uint4 (&gb)[PA_CT]) {    // elements 32 c .. 32 c + 31 of D
 #pragma unroll
-            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tbb + (ob[k] + (uint32_t)((2 * s + h) * 1024)));
+            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tbb + (ob[k] + (uint32_t)(c * 1024)));
         };
         floatx4s acc[RT][PA_CT];
 #pragma unroll
@@ -311,47 +319,45 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
 
         __syncthreads();                                  // the previous pass is done with W and with both A buffers
         for (int k = tid; k < PASS; k += PA_THREADS) sm.W[k] = (c0 + k < N) ? inv_tn[c0 + k] : 0.f;
-        // gx, gy: B operands of the first and second half of a step; ga0, ga1: visual rows of the even and odd steps
-        uint4 ga0[2], ga1[2], gx[PA_CT], gy[PA_CT];
-        load_b(0, 0, gx);
-        load_b(0, 1, gy);
-        load_a(0, ga0);
-        load_a(1, ga1);                                   // steps >= 2 (D is a multiple of 128)
-        store_a(0, ga0, first_pass ? 1.f : 0.f);
+        // gx, gy: B operands of the even and odd quarters of a step; ga: visual rows of the next step
+        uint4 ga[PA_NU], gx[PA_CT], gy[PA_CT];
+        const int last_c = D / 32 - 1;
+        load_b(0, gx);
+        load_b(1, gy);
+        load_a(0, ga);
+        store_a(0, ga, first_pass ? 1.f : 0.f);
+        load_a(min(1, steps - 1), ga);
 
-        // step s: LDS buffer s % 2 x (gx, gy).  gload takes the rows of step s + 2 (sent for first: two steps to
-        // arrive from memory), gstore holds the rows of step s + 1 and goes to the other LDS buffer at the end.
-        // Past the end the last steps' operands are fetched again, unused.  No branches: the body stays one block,
-        // which keeps the wait counts of the loads in flight exact.
-        auto step = [&](int s, int buf, uint4 (&gload)[2], const uint4 (&gstore)[2]) {
-            load_a(min(s + 2, steps - 1), gload);
-            const int sn = min(s + 1, steps - 1);
+        // step s: LDS buffer s % 2 x the B operands, a quarter (32 elements of D) at a time.  No branches: the body
+        // stays one block, which keeps the wait counts of the loads in flight exact.  Past the end the last
+        // operands are fetched again, unused.
+        for (int s = 0; s < steps; s++) {
+            const int buf = s & 1;
             __syncthreads();                              // A tile of step s is written; the other buffer is free
             __builtin_amdgcn_sched_barrier(0);
             const uint16_t* sa = &sm.A[0][(rb * 16 + lm) * PA_PITCH + lj * 8] + buf * (PA_ROWS * PA_PITCH);
-            // 2 RT groups of PA_CT products: row tile i, half h; the A operand of the next group is read from LDS
-            // while this one is multiplied.  Each half's B operands are replaced as soon as their last product has
-            // issued, so they have half a step to arrive (the text rows are in L2).
+            // PA_Q RT groups of PA_CT products: row tile i, quarter q; the A operand is read from LDS two groups
+            // ahead.  A quarter's B operands are replaced as soon as their last product has issued, so they have
+            // a quarter of a step to arrive (the packed text is in L2).
             auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + (g % RT) * 16 * PA_PITCH + (g / RT) * 32); };
             uint4 f[3];
             f[0] = read_a(0);
             f[1] = read_a(1);
 #pragma unroll
-            for (int g = 0; g < 2 * RT; g++) {
-                const int i = g % RT, h = g / RT;
-                if (g + 2 < 2 * RT) f[(g + 2) % 3] = read_a(g + 2);       // two groups ahead
+            for (int g = 0; g < PA_Q * RT; g++) {
+                const int i = g % RT, q = g / RT;
+                if (g + 2 < PA_Q * RT) f[(g + 2) % 3] = read_a(g + 2);
 #pragma unroll
-                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], h == 0 ? gx[k] : gy[k], acc[i][k]);
-                if (g == RT - 1) load_b(sn, 0, gx);
+                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], (q & 1) == 0 ? gx[k] : gy[k], acc[i][k]);
+                if (i == RT - 1) {                        // quarter q is done: its buffer takes quarter q + 2
+                    const int c = min(PA_Q * s + q + 2, last_c);
+                    if ((q & 1) == 0) load_b(c, gx); else load_b(c, gy);
+                }
                 __builtin_amdgcn_sched_barrier(0);        // issue order as written: one LDS read, then the group's products
             }
-            load_b(sn, 1, gy);
-            __builtin_amdgcn_sched_barrier(0);            // the rows below were sent for two steps ago: nothing before this waits for them
-            store_a(buf ^ 1, gstore, (first_pass && s + 1 < steps) ? 1.f : 0.f);
-        };
-        for (int s = 0; s < steps; s += 2) {
-            step(s, 0, ga0, ga1);
-            step(s + 1, 1, ga1, ga0);
+            // the next step's rows (sent for a step ago) go to the other LDS buffer; then send for the rows after them
+            store_a(buf ^ 1, ga, (first_pass && s + 1 < steps) ? 1.f : 0.f);
+            load_a(min(s + 2, steps - 1), ga);
         }
 
         // epilogue: lane holds rows 4 lj + e of row tile i, column lm of column tile k
@@ -389,7 +395,9 @@ __global__ __launch_bounds__(PA_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     if (row0 >= M) return;
     const int tid = threadIdx.x;
     for (int k = tid; k < PA_WAVES * PA_ROWS; k += PA_THREADS) sm.R[k / PA_ROWS][k % PA_ROWS] = 0.f;
-    float nsq[2] = {0.f, 0.f};
+    float nsq[PA_NU];
+#pragma unroll
+    for (int u = 0; u < PA_NU; u++) nsq[u] = 0.f;
     const uint16_t* va = vis + (int64_t)m0 * D;
     const char* tb = reinterpret_cast<const char*>(packed_txt) + (int64_t)pair_tile_base(txt_off, b) * (D / 32) * 1024;
     if (N > 4 * PA_WCOLS)
@@ -398,15 +406,14 @@ __global__ __launch_bounds__(PA_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         pair_body<BF, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
     else
         pair_body<BF, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
-    // |w_k|^2: the eight threads that staged a row hold its eight 16-byte pieces of every step
-    const int pp = tid & 7, pr = tid >> 3;
+    // |w_k|^2: the PA_PPR threads that staged a row hold its 16-byte pieces of every step
+    const int pp = tid % PA_PPR, pr = tid / PA_PPR;
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
+    for (int u = 0; u < PA_NU; u++) {
         float v = nsq[u];
-        v += __shfl_xor(v, 1, 64);
-        v += __shfl_xor(v, 2, 64);
-        v += __shfl_xor(v, 4, 64);
-        if (pp == 0) sm.N2[pr + 64 * u] = v;
+#pragma unroll
+        for (int o = 1; o < PA_PPR; o <<= 1) v += __shfl_xor(v, o, 64);
+        if (pp == 0) sm.N2[pr + PA_RPT * u] = v;
     }
     __syncthreads();
     if (tid < PA_ROWS && row0 + tid < M) {
@@ -537,6 +544,64 @@ __global__ __launch_bounds__(256) void k_probe_copy(const uint4* __restrict__ sr
 }
 
 }  // namespace
+
+namespace {
+
+__device__ __forceinline__ uint32_t probe_mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+// 32 independent accumulator tiles per wavefront, operands in registers only; RANDOM: bf16 values in (-2, 2) that
+// move to other products every iteration (a handful of register moves per 32 products), else all ones.
+template <bool RANDOM>
+__global__ __launch_bounds__(512) void k_probe_mfma(uint32_t* __restrict__ sink, int iters)
+{
+    floatx4s acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; i++) acc[i] = floatx4s{0.f, 0.f, 0.f, 0.f};
+    uint32_t s = probe_mix(blockIdx.x * 512 + threadIdx.x + 1);
+    auto rnd = [&]() { s = probe_mix(s + 0x9e3779b9u); return RANDOM ? ((s & 0x80ff80ffu) | 0x3f003f00u) : 0x3f803f80u; };
+    uint4 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; i++) a[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
+#pragma unroll
+    for (int i = 0; i < 4; i++) b[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) acc[i * 4 + j] = mfma_s<true>(a[i], b[j], acc[i * 4 + j]);
+        if (RANDOM) {
+            const uint4 t = a[0];
+#pragma unroll
+            for (int i = 0; i < 7; i++) a[i] = a[i + 1];
+            a[7] = make_uint4(t.y, t.z, t.w, t.x);
+            const uint4 u = b[0];
+            b[0] = b[1], b[1] = b[2], b[2] = b[3], b[3] = make_uint4(u.w, u.x, u.y, u.z);
+        }
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; i++) r += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    if (__float_as_uint(r) == 0x9E3779B9u) sink[0] = 1u;   // practically never true; keeps the products alive
+}
+
+}  // namespace
+
+extern "C" int wq_probe_mfma(wq_ctx* ctx, int random_operands, int workgroups, int iters, double* flops)
+{
+    if (!ctx || workgroups <= 0 || iters <= 0) return WQ_ERR_ARG;
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    if (random_operands)
+        hipLaunchKernelGGL(k_probe_mfma<true>, dim3(workgroups), dim3(512), 0, ctx->stream, wq_status_ptr(ctx) + 8, iters);
+    else
+        hipLaunchKernelGGL(k_probe_mfma<false>, dim3(workgroups), dim3(512), 0, ctx->stream, wq_status_ptr(ctx) + 8, iters);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    if (flops) *flops = (double)workgroups * 8.0 * (double)iters * 32.0 * (2.0 * 16 * 16 * 32);
+    return WQ_OK;
+}
 
 extern "C" int wq_probe_stream(wq_ctx* ctx, const void* src, void* dst, int64_t bytes, int blocks)
 {
