@@ -291,6 +291,22 @@ def main():
     as_us = timed(lambda i: W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first), n)
     rq_us = timed(lambda i: W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, copies[i % N_COPIES]), n)
     st_mean = [sc_us, as_us, rq_us, dec_us]
+
+    # ---- operator-fusion ablation: dequantize the packed cache to 16-bit rows in memory, then plain 16-bit attention
+    #      over them (what runs at every decode step without the fused kernel); two dense copies, rotated ------------
+    tot = [int(sum(copies[0].cls_len[c][b].item() for c in range(3)) + copies[0].len16[b].item()) for b in range(B)]
+    dense_off = np.concatenate([[0], np.cumsum(tot)]).astype(np.int32)
+    dense = [W.PackedKV(B, w.Hkv, w.hd, w.group, TD[w.dtype16], [0, 0, 0], dense_off) for _ in range(2)]
+    for i in range(2):
+        W.wq_dequantize(ctx, copies[i], dense[i])
+        W.wq_decode_attention(ctx, q, dense[i], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)
+    nd = max(8, n // 4)
+    deq_us = timed(lambda i: W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]), nd)
+    att16_us = timed(lambda i: W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse), nd)
+    unf_us = timed(lambda i: (W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]),
+                              W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)), nd)
+    dense_bytes = sum(tot) * w.Hkv * w.hd * 2 * 2
+    del dense
     gbs = alg_bytes / (dec_us * 1e-6) / 1e9
     kern_gbs = gbs
 
@@ -323,6 +339,10 @@ def main():
         "stage_us": {"window_scores": round(float(st_mean[0]), 1), "assign_bits": round(float(st_mean[1]), 1),
                      "reorder_quantize": round(float(st_mean[2]), 1), "decode_attention": round(dec_us, 2)},
         "stream_read_GBs": round(read_gbs, 0),
+        "ablation_operator_fusion": {"fused_decode_us": round(dec_us, 2), "unfused_decode_us": round(unf_us, 2),
+                                     "dequantize_to_memory_us": round(deq_us, 2), "attention_16bit_us": round(att16_us, 2),
+                                     "bytes_16bit_cache": dense_bytes, "speedup_of_fusion": round(unf_us / dec_us, 2),
+                                     "note": "unfused = wq_dequantize (packed -> 16-bit rows in HBM) + wq_decode_attention over those rows, per step"},
         "roofline": {"kernel": "k_decode_mfma<128>", "bound": "hbm", "achieved": round(kern_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kern_gbs / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic() if args.config == 3 else None, "algorithmic_bytes_per_launch": alg_bytes,

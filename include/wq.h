@@ -192,6 +192,17 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * (off16[b]+len16[b] == off16[b+1], or == cap16) is left unchanged and WQ_DEV_SEG16_OVERFLOW is raised.       */
 int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
 
+/* ---- the unfused variant of the operator-fusion ablation (Sec. 4.6, Table "operator fusion") ------------------
+ * Dequantizes a packed cache to memory: sequence b's rows off16[b] .. of dst's 16-bit segment receive the values
+ * m + s*code (one fp32 fused multiply-add, rounded to nearest even into dtype16) of src's 2-bit, 4-bit and 8-bit
+ * tokens, in this order (the order of the cache), followed by src's 16-bit rows; dst's len16 is written, dst's
+ * classes are made empty (cls_len = 0, cls_off = 0).  wq_decode_attention over dst is then plain 16-bit attention
+ * over the dequantized cache: what an implementation without the fused kernel runs at every decode step.
+ * src, dst: same B, Hkv, hd, dtype16; dst's tables and 16-bit segment are the caller's (its class capacities may be
+ * 0).  A sequence that does not fit dst's rows (off16[b+1]-off16[b], cap16) gets len16 = 0 and raises
+ * WQ_DEV_SEG16_OVERFLOW.                                                                                         */
+int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst);
+
 /* ---- a4: decode attention over the packed cache (Alg. 2, decode half) -------------------------------------
  * out[b,h,:] = sum_t softmax_t(sm_scale * q[b,h].k^_t) v^_t over the 2-, 4-, 8- and 16-bit segments of
  * sequence b, one softmax over all of them, no mask (Sec. 2.1); head h reads KV head h/(Hq/Hkv).

@@ -64,6 +64,7 @@ def lib() -> C.CDLL:
         L.wq_vote_bits.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_append_kv.argtypes = [vp, vp, vp, i32, i32, C.POINTER(_PackedKV)]
+        L.wq_dequantize.argtypes = [vp, i32, C.POINTER(_PackedKV), C.POINTER(_PackedKV)]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
         L.wq_probe_mfma.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_double)]
@@ -242,6 +243,10 @@ def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg
 def wq_append_kv(ctx: Context, k_new, v_new, kv: PackedKV):
     B = k_new.shape[0]
     ctx.check(lib().wq_append_kv(ctx.handle, _ptr(k_new), _ptr(v_new), _dtype_id(k_new), B, C.byref(kv.desc)))
+
+
+def wq_dequantize(ctx: Context, src: PackedKV, dst: PackedKV):
+    ctx.check(lib().wq_dequantize(ctx.handle, src.B, C.byref(src.desc), C.byref(dst.desc)))
 
 
 def wq_decode_attention(ctx: Context, q, kv: PackedKV, sm_scale: float, num_splits: int = 0, max_seq_tokens: int = 0,

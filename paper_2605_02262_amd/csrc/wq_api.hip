@@ -272,6 +272,22 @@ int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, i
     return wq_launch_append(ctx, k_new, v_new, dtype, B, kv);
 }
 
+int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    int rc = check_packed(ctx, src, B, true);
+    if (rc != WQ_OK) return rc;
+    rc = check_packed(ctx, dst, B, true);
+    if (rc != WQ_OK) return rc;
+    if (src->Hkv != dst->Hkv || src->hd != dst->hd || src->dtype16 != dst->dtype16)
+        return wq_fail(ctx, WQ_ERR_ARG, "source and destination differ in Hkv, hd or dtype16");
+    if (src->k16 == dst->k16 || src->v16 == dst->v16) return wq_fail(ctx, WQ_ERR_ARG, "source and destination share their 16-bit segment");
+    if (B == 0) return WQ_OK;
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    return wq_launch_dequantize(ctx, B, src, dst);
+}
+
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
 {

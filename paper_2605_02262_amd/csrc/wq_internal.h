@@ -115,6 +115,7 @@ int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int
                        const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
                        const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out);
 int wq_launch_append(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
+int wq_launch_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst);
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
                      int num_splits, int algo, float* out, float* lse);
 size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits);

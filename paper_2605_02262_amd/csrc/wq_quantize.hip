@@ -277,6 +277,156 @@ __global__ __launch_bounds__(256) void k_append16(const T* __restrict__ k_new, c
     if (threadIdx.x == 0) pk.len16[b] += 1;
 }
 
+// ---- the unfused variant of the operator-fusion ablation (Sec. 4.6): packed classes back to 16-bit rows -------------
+// dst's 16-bit segment receives, per sequence, the dequantized tokens of src's 2-, 4- and 8-bit classes (in this order,
+// the order of the cache) and then src's 16-bit rows; dst's classes are empty.  Decode attention over dst is then the
+// plain 16-bit attention that a dequantize-to-memory implementation would run.
+//   k_dense_plan   dst tables, capacity check
+//   k_dequantize   one workgroup per (32-token block of a class, KV head): value = fma(code, s, m) in fp32, rounded to
+//                  nearest even into the 16-bit type
+//   k_dense_copy   src's 16-bit rows
+__device__ __forceinline__ int dense_total(const wq_packed_kv& src, int b)
+{
+    return src.cls_len[0][b] + src.cls_len[1][b] + src.cls_len[2][b] + src.len16[b];
+}
+__device__ __forceinline__ bool dense_fits(const wq_packed_kv& src, const wq_packed_kv& dst, int b)
+{
+    const int n = dense_total(src, b);
+    return dst.off16[b] >= 0 && n <= dst.off16[b + 1] - dst.off16[b] && (int64_t)dst.off16[b] + n <= dst.cap16;
+}
+
+__global__ __launch_bounds__(256) void k_dense_plan(int B, wq_packed_kv src, wq_packed_kv dst, uint32_t* __restrict__ status)
+{
+    for (int b = threadIdx.x; b < B; b += 256) {
+        const bool ok = dense_fits(src, dst, b);
+        dst.len16[b] = ok ? dense_total(src, b) : 0;
+        if (!ok) atomicOr(status, WQ_DEV_SEG16_OVERFLOW);
+#pragma unroll
+        for (int c = 0; c < 3; c++) dst.cls_len[c][b] = 0;
+    }
+    for (int b = threadIdx.x; b <= B; b += 256)
+#pragma unroll
+        for (int c = 0; c < 3; c++) dst.cls_off[c][b] = 0;
+}
+
+__device__ __forceinline__ uint16_t to_16bit(float x, bool bf16)
+{
+    if (bf16) {
+        const uint32_t u = __float_as_uint(x);
+        return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);       // nearest even (finite values)
+    }
+    return __half_as_ushort(__float2half_rn(x));
+}
+
+template <int HD, int BITS>
+__global__ __launch_bounds__(256) void k_dequantize(int B, wq_packed_kv src, wq_packed_kv dst)
+{
+    constexpr int C = cls_index(BITS);
+    constexpr int CPT = HD / 8;                 // channels per thread: 8 threads share one token row
+    constexpr int Q = HD / 4, CT = HD / 16;
+    constexpr int BLK_B = 32 * HD * BITS / 8;   // bytes of a 32-token block of one plane
+    __shared__ __align__(16) uint8_t s_v[BLK_B];
+    const int tid = threadIdx.x, kvh = blockIdx.y, Hkv = src.Hkv, G = HD / src.group;
+    const int32_t* off = src.cls_off[C];
+    const int64_t tok0 = (int64_t)blockIdx.x * 32;
+    if (tok0 >= off[B]) return;                 // unused capacity
+    const int b = wq_find_seq(off, B, tok0);
+    if (!dense_fits(src, dst, b)) return;
+    const int d0 = (int)(tok0 - off[b]), len = src.cls_len[C][b];
+    int before = 0;                             // tokens of the lower classes come first
+    for (int c = 0; c < C; c++) before += src.cls_len[c][b];
+    const bool bf16 = dst.dtype16 == WQ_BF16;
+
+    const uint8_t* kc = static_cast<const uint8_t*>(src.codes[C]) + ((int64_t)kvh * src.cap[C] + tok0) * HD * BITS / 8;
+    const uint8_t* vc = static_cast<const uint8_t*>(src.codes[C]) + (((int64_t)Hkv + kvh) * src.cap[C] + tok0) * HD * BITS / 8;
+    for (int i = tid; i < BLK_B / 16; i += 256) reinterpret_cast<uint4*>(s_v)[i] = reinterpret_cast<const uint4*>(vc)[i];
+    __syncthreads();
+
+    const int u = tid >> 3, p = tid & 7;        // token of the block, part of its row
+    if (d0 + u >= len) return;
+    const int64_t row = (int64_t)dst.off16[b] + before + d0 + u;
+    const int tile = u >> 4, m = u & 15;
+    const int gi = (p * CPT) / src.group;       // the thread's channels lie in one group (group >= CPT)
+    uint32_t ko[CPT / 2], vo[CPT / 2];              // pairs of 16-bit values
+#pragma unroll
+    for (int i = 0; i < CPT / 2; i++) ko[i] = vo[i] = 0u;
+    {   // K: the thread's codes are consecutive fields of its token's row quarter
+        const uint32_t word = static_cast<const uint32_t*>(src.meta[C])[((int64_t)kvh * src.cap[C] + tok0) * G + (tile * G + gi) * 16 + m];
+        const float s = __half2float(__ushort_as_half((uint16_t)(word & 0xFFFFu))), mn = __half2float(__ushort_as_half((uint16_t)(word >> 16)));
+        const int j = (p * CPT) / Q, e0 = (p * CPT) % Q;
+        const uint8_t* in = kc + tile * (16 * HD * BITS / 8) + ((j * 16 + m) * Q + e0) * BITS / 8;
+        constexpr int NB = CPT * BITS / 8;      // bytes of the thread's codes: 2..16, aligned to their size
+        uint32_t pw[(NB + 3) / 4];
+        if constexpr (NB == 2) {
+            pw[0] = *reinterpret_cast<const uint16_t*>(in);
+        } else if constexpr (NB == 4) {
+            pw[0] = *reinterpret_cast<const uint32_t*>(in);
+        } else if constexpr (NB == 8) {
+            const uint2 t = *reinterpret_cast<const uint2*>(in);
+            pw[0] = t.x, pw[1] = t.y;
+        } else {
+            const uint4 t = *reinterpret_cast<const uint4*>(in);
+            pw[0] = t.x, pw[1] = t.y, pw[2] = t.z, pw[3] = t.w;
+        }
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            const uint32_t code = (pw[(i * BITS) >> 5] >> ((i * BITS) & 31)) & ((1u << BITS) - 1u);
+            ko[i >> 1] |= (uint32_t)to_16bit(fmaf((float)code, s, mn), bf16) << (16 * (i & 1));
+        }
+    }
+    {   // V: field n = ((jj*16 + mm)*CT + ct)*8 + tau of the block, channel 16 ct + mm
+        const uint32_t word = static_cast<const uint32_t*>(src.meta[C])[(((int64_t)Hkv + kvh) * src.cap[C] + tok0) * G + (tile * G + gi) * 16 + m];
+        const float s = __half2float(__ushort_as_half((uint16_t)(word & 0xFFFFu))), mn = __half2float(__ushort_as_half((uint16_t)(word >> 16)));
+        const int jj = m >> 2, tau = 4 * tile + (u & 3);
+#pragma unroll
+        for (int i = 0; i < CPT; i++) {
+            const int ch = p * CPT + i, ct = ch >> 4, mm = ch & 15;
+            const int bit = (((jj * 16 + mm) * CT + ct) * 8 + tau) * BITS;
+            const uint32_t code = (s_v[bit >> 3] >> (bit & 7)) & ((1u << BITS) - 1u);
+            vo[i >> 1] |= (uint32_t)to_16bit(fmaf((float)code, s, mn), bf16) << (16 * (i & 1));
+        }
+    }
+    uint16_t* k16 = static_cast<uint16_t*>(dst.k16) + (row * Hkv + kvh) * HD + p * CPT;
+    uint16_t* v16 = static_cast<uint16_t*>(dst.v16) + (row * Hkv + kvh) * HD + p * CPT;
+#pragma unroll
+    for (int i = 0; i < CPT; i += 8) {
+        *reinterpret_cast<uint4*>(k16 + i) = make_uint4(ko[i / 2], ko[i / 2 + 1], ko[i / 2 + 2], ko[i / 2 + 3]);
+        *reinterpret_cast<uint4*>(v16 + i) = make_uint4(vo[i / 2], vo[i / 2 + 1], vo[i / 2 + 2], vo[i / 2 + 3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_dense_copy(int B, int row_elems, wq_packed_kv src, wq_packed_kv dst)
+{
+    const int64_t r = blockIdx.x;               // a row of src's 16-bit segment
+    const int b = wq_find_seq(src.off16, B, r);
+    if (r < src.off16[0] || r >= src.off16[B]) return;
+    const int i = (int)(r - src.off16[b]);
+    if (i >= src.len16[b] || !dense_fits(src, dst, b)) return;
+    const int64_t d = (int64_t)dst.off16[b] + src.cls_len[0][b] + src.cls_len[1][b] + src.cls_len[2][b] + i;
+    const uint4* ks = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src.k16) + r * row_elems);
+    const uint4* vs = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src.v16) + r * row_elems);
+    uint4* kd = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dst.k16) + d * row_elems);
+    uint4* vd = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dst.v16) + d * row_elems);
+    for (int e = threadIdx.x; e < row_elems / 8; e += 256) {
+        kd[e] = ks[e];
+        vd[e] = vs[e];
+    }
+}
+
+template <int HD>
+int run_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst)
+{
+    hipStream_t st = ctx->stream;
+    hipLaunchKernelGGL(k_dense_plan, dim3(1), dim3(256), 0, st, B, *src, *dst, wq_status_ptr(ctx));
+    const dim3 blk(256);
+    if (src->cap[0] > 0) hipLaunchKernelGGL((k_dequantize<HD, 2>), dim3((unsigned)(src->cap[0] / 32), src->Hkv), blk, 0, st, B, *src, *dst);
+    if (src->cap[1] > 0) hipLaunchKernelGGL((k_dequantize<HD, 4>), dim3((unsigned)(src->cap[1] / 32), src->Hkv), blk, 0, st, B, *src, *dst);
+    if (src->cap[2] > 0) hipLaunchKernelGGL((k_dequantize<HD, 8>), dim3((unsigned)(src->cap[2] / 32), src->Hkv), blk, 0, st, B, *src, *dst);
+    if (src->cap16 > 0) hipLaunchKernelGGL(k_dense_copy, dim3((unsigned)src->cap16), blk, 0, st, B, src->Hkv * HD, *src, *dst);
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
+
 template <typename T, int HD>
 int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_off, const int32_t* win_size,
         const int32_t* win_off, const int32_t* perm, const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* pk)
@@ -325,6 +475,12 @@ int wq_launch_append(wq_ctx* ctx, const void* k_new, const void* v_new, int dtyp
     }
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
+}
+
+int wq_launch_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst)
+{
+    if (src->hd == 64 && src->group == 128) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "group larger than hd");
+    return src->hd == 128 ? run_dequantize<128>(ctx, B, src, dst) : run_dequantize<64>(ctx, B, src, dst);
 }
 
 int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,

@@ -78,6 +78,16 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert lib.wq_decode_attention(h, one, W.BF16, 1, 30, C.byref(d), 0.1, 0, 100, 0, one, None) == -2  # Hq % Hkv
         assert lib.wq_decode_attention(h, one, W.BF16, 2, 28, C.byref(d), 0.1, 0, 100, 0, one, None) == -1  # B mismatch
         assert lib.wq_reorder_quantize(h, one, one, W.F16, 1, one, one, one, one, one, 10, C.byref(d)) == -1  # dtype16
+        # dequantize: descriptors must agree; the two 16-bit segments must differ; the probe checks its sizes
+        d.k16, d.v16, d.cap16 = 0x4000, 0x5000, 64
+        d2 = W._PackedKV()
+        C.memmove(C.byref(d2), C.byref(d), C.sizeof(d))
+        assert lib.wq_dequantize(h, 1, C.byref(d), C.byref(d2)) == -1 and b"share" in lib.wq_last_error(h)
+        d2.k16, d2.v16 = 0x6000, 0x7000
+        d2.dtype16 = W.F16
+        assert lib.wq_dequantize(h, 1, C.byref(d), C.byref(d2)) == -1 and b"differ" in lib.wq_last_error(h)
+        assert lib.wq_dequantize(h, 1, C.byref(d), None) == -1
+        assert lib.wq_probe_mfma(h, 1, 0, 10, None) == -1
         # workspace too small
         h2 = C.c_void_p()
         assert lib.wq_create(C.byref(h2), None, fake_ws, 512) == 0

@@ -289,3 +289,86 @@ def test_decode_step_in_a_hip_graph_replays_like_eager():
             assert torch.equal(runs[0][layer].pk.len16, runs[1][layer].pk.len16)
         assert float(outs[1][0].abs().max()) > 0
     assert runs[1][0].ctx.device_status() == 0
+
+
+def _dense_expected(o, dtype16):
+    """Per sequence: the values m + s*code of the oracle's logical codes (fp64, the format's definition written out) in
+    cache order [2-bit | 4-bit | 8-bit], then the oracle's 16-bit rows.  Returns (K, V) lists of [rows, Hkv, hd]."""
+    pk = o.pk
+    G = pk.hd // pk.group
+    Ks, Vs = [], []
+    for b in range(pk.B):
+        parts = [[], []]
+        for c in range(3):
+            a, n = int(pk.cls_off[c][b]), int(pk.cls_len[c][b])
+            for pl in range(2):
+                code = pk.codes[c][pl, :, a:a + n, :].astype(np.float64)                       # [Hkv, n, hd]
+                s = pk.sbits[c][pl, :, a:a + n, :].astype(np.uint16).view(np.float16).astype(np.float64)
+                m = pk.mbits[c][pl, :, a:a + n, :].astype(np.uint16).view(np.float16).astype(np.float64)
+                val = np.repeat(m, pk.group, axis=-1) + np.repeat(s, pk.group, axis=-1) * code
+                parts[pl].append(np.transpose(val, (1, 0, 2)))                                   # [n, Hkv, hd]
+        a, n = int(pk.off16[b]), int(pk.len16[b])
+        parts[0].append(pk.k16[a:a + n].astype(np.float64))
+        parts[1].append(pk.v16[a:a + n].astype(np.float64))
+        Ks.append(np.concatenate(parts[0]))
+        Vs.append(np.concatenate(parts[1]))
+    return Ks, Vs
+
+
+@pytest.mark.parametrize("dtype,hd,g", [(synth.BF16, 128, 64), (synth.F16, 64, 32)])
+def test_unfused_ablation_dequantize_to_memory_then_16bit_attention(dtype, hd, g):
+    """wq_dequantize (the unfused variant of the operator-fusion ablation, Sec. 4.6): every dequantized value is the
+    format's m + s*code rounded once into the 16-bit type; decode attention over the dense copy agrees with the fp64
+    textbook attention over those rows."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(9, 21, 21, 13, (2, 3, 4)),             # 189 tokens: blocks of 32 with ragged ends in every class
+             synth.SeqSpec(4, 16, 16, 40, (1, 1, 2)),
+             synth.SeqSpec(0, 10, 4, 5, (0, 0, 0)),               # text only
+             synth.SeqSpec(6, 32, 32, 0, (2, 2, 2), tail=7)]      # video tail, no text
+    bt = _custom(321 + hd, hd, g, 2, 7, dtype, specs)
+    w, t = bt.w, bt.t
+    g_run, o, _ = _check(bt, H, splits=2)
+    pk = g_run.pk
+    totals = [int(sum(o.pk.cls_len[c][b] for c in range(3)) + o.pk.len16[b]) for b in range(w.B)]
+    off = np.concatenate([[0], np.cumsum([n + 3 for n in totals])]).astype(np.int32)      # a little slack per sequence
+    dense = W.PackedKV(w.B, w.Hkv, w.hd, w.group, pk.dtype16, [0, 0, 0], off, fill=0xA5)
+    W.wq_dequantize(g_run.ctx, pk, dense)
+    q = H.to_dev(bt.q, w.dtype)
+    out = W.wq_decode_attention(g_run.ctx, q, dense, 1.0 / float(np.sqrt(w.hd)), 2, max(totals))
+    torch.cuda.synchronize()
+    assert g_run.ctx.device_status() == 0
+    assert np.array_equal(dense.len16.cpu().numpy(), np.asarray(totals, np.int32))
+    for c in range(3):
+        assert int(dense.cls_len[c].abs().sum().item()) == 0 and int(dense.cls_off[c].abs().sum().item()) == 0
+    Ks, Vs = _dense_expected(o, w.dtype16)
+    half_ulp = 2.0 ** -8 if w.dtype16 == synth.BF16 else 2.0 ** -11
+    k16, v16 = dense.k16.float().cpu().numpy().astype(np.float64), dense.v16.float().cpu().numpy().astype(np.float64)
+    for b in range(w.B):
+        a, n = int(off[b]), totals[b]
+        for got, want in ((k16[a:a + n], Ks[b]), (v16[a:a + n], Vs[b])):
+            assert got.shape == want.shape
+            assert np.all(np.abs(got - want) <= half_ulp * np.abs(want) * 1.0001 + 2.0 ** -25), "dequantized value off by more than one rounding"
+    # The dense copy holds the values rounded into the 16-bit type (2^-8 relative for bf16), so its attention differs
+    # from the attention over the exact values m + s*code by more than the fused kernel's error: a sanity bound only.
+    assert H.attention_error(out.cpu().numpy(), o.out) <= 2e-2
+    # The bar proper: the textbook attention (fp64) over exactly the rows that were written.
+    for b in range(w.B):
+        a, n = int(off[b]), totals[b]
+        want = O.attention_dense(bt.q[b], k16[a:a + n].astype(np.float32), v16[a:a + n].astype(np.float32), 1.0 / np.sqrt(w.hd))
+        assert H.attention_error(out[b].cpu().numpy()[None], want[None]) <= H.ATTN_TOL
+
+
+def test_dequantize_reports_a_destination_that_is_too_small():
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    bt = synth.batch(synth.workload(0))
+    g_run = H.run_gpu(bt)
+    w = bt.w
+    small = W.PackedKV(w.B, w.Hkv, w.hd, w.group, g_run.pk.dtype16, [0, 0, 0], np.array([0, 40], np.int32), fill=0x11)
+    W.wq_dequantize(g_run.ctx, g_run.pk, small)
+    torch.cuda.synchronize()
+    assert g_run.ctx.device_status() == W.DEV_SEG16_OVERFLOW
+    assert int(small.len16.sum().item()) == 0
+    assert int((small.k16.view(torch.int16) != 0).sum().item()) == 0 and int((small.v16.view(torch.int16) != 0).sum().item()) == 0   # nothing was written
