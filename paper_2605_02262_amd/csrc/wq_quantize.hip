@@ -81,9 +81,10 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
     __shared__ uint32_t s_v[32][HD / 4 + 1];    // V codes, 4 per word, rows padded by one word (conflict-free column reads)
     __shared__ uint32_t s_meta[2][4][32];       // [plane][group][token]
     const int tid = threadIdx.x;
-    const int blk = blockIdx.x;
-    const int kvh = blockIdx.y;
     const int Hkv = pk.Hkv;
+    // consecutive workgroups take the KV heads of one token block: together they read whole source rows
+    const int blk = blockIdx.x / Hkv;
+    const int kvh = blockIdx.x % Hkv;
     const int G = HD / group;
     const int32_t* off = pk.cls_off[C];
     const int64_t tok0 = (int64_t)blk * 32;
@@ -439,13 +440,13 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
                        wq_status_ptr(ctx));
     dim3 blk(256);
     if (pk->cap[0] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 2>), dim3((unsigned)(pk->cap[0] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+        hipLaunchKernelGGL((k_quantize<T, HD, 2>), dim3((unsigned)(pk->cap[0] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
                            kv_off, win_size, win_off, perm, seg_windows, *pk);
     if (pk->cap[1] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 4>), dim3((unsigned)(pk->cap[1] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+        hipLaunchKernelGGL((k_quantize<T, HD, 4>), dim3((unsigned)(pk->cap[1] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
                            kv_off, win_size, win_off, perm, seg_windows, *pk);
     if (pk->cap[2] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 8>), dim3((unsigned)(pk->cap[2] / 32), pk->Hkv), blk, 0, st, K, V, B, pk->group,
+        hipLaunchKernelGGL((k_quantize<T, HD, 8>), dim3((unsigned)(pk->cap[2] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
                            kv_off, win_size, win_off, perm, seg_windows, *pk);
     if (total_rows > 0 && pk->cap16 > 0)
         hipLaunchKernelGGL(k_copy16<T>, dim3((unsigned)(total_rows < pk->cap16 ? total_rows : pk->cap16)), blk, 0, st, K, V, B, pk->Hkv * HD, kv_off, win_size,
