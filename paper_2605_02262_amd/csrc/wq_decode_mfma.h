@@ -180,13 +180,13 @@ constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2
 
 template <int HD>
 struct MfmaSmem {
-    union {
-        struct {
-            uint32_t meta[WQ_WAVES][2][64];              // per wave: K and V metadata words of the current block
-            uint16_t vt[WQ_WAVES][32][HD / 2 + VT_PAD];  // per wave: half the channels of the V rows of a 16-bit block, read back transposed
-        } run;
-        float O[WQ_WAVES][WQ_MAX_REP][HD + 1];           // per-wave numerators for the merge (after the loops); rows one bank apart
-    };
+    struct {
+        uint32_t meta[WQ_WAVES][2][64];                  // per wave: K and V metadata words of the current block
+        uint16_t vt[WQ_WAVES][32][HD / 2 + VT_PAD];      // per wave: half the channels of the V rows of a 16-bit block, read back transposed
+    } run;
+    // per-wave numerators for the merge; rows one bank apart.  A space of its own: a wavefront hands its numerators over
+    // as soon as its loops end, while others still use the run-time part
+    float O[WQ_WAVES][WQ_MAX_REP][HD + 1];
     U4 bq[4][HD / 32][64];                               // query operands of the four classes (index 3 = 16-bit segment), per lane
     float qx[4][2][64];                                  // ... with the head's power of two and the group's query sum
     float ml[WQ_WAVES][WQ_MAX_REP][2];
@@ -837,8 +837,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     l += __shfl_xor(l, 32, 64);
     am += __shfl_xor(am, 16, 64);
     am += __shfl_xor(am, 32, 64);
-    pass_setup_barrier(tk);
-    __syncthreads();                               // every wave is done with the run-time part of LDS
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
@@ -850,6 +848,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         sm.ml[wave][h][0] = st.m;
         sm.ml[wave][h][1] = l;
     }
+    pass_setup_barrier(tk);
     __syncthreads();
     // ---- merge the wavefronts, write the partial (m in natural-log units) ----
     const int64_t pstride = (int64_t)a.rep * (HD + 2);
