@@ -50,8 +50,9 @@ __global__ __launch_bounds__(256) void k_text_norm(const T* __restrict__ txt, in
     if (lane == 0) inv_norm[row] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
 }
 
-// tbar[b][d] = 1/N sum_j t_j[d]/|t_j|.  VEC: thread = (8 columns, one of 8 token slices), slices merged in LDS in
-// slice order; otherwise one thread per column.
+// tbar[b][d] = 1/N sum_j t_j[d]/|t_j|.  VEC: a workgroup takes 64 columns, thread = (8 columns, one of 32 token slices),
+// slices merged in LDS in slice order (many small workgroups: the kernel is bound by the latency of its row loads);
+// otherwise one thread per column.
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void k_text_mean(const T* __restrict__ txt, const float* __restrict__ inv_norm, int D,
                                                    const int32_t* __restrict__ txt_off, float* __restrict__ tbar)
@@ -59,12 +60,12 @@ __global__ __launch_bounds__(256) void k_text_mean(const T* __restrict__ txt, co
     const int b = blockIdx.y;
     const int j0 = txt_off[b], j1 = txt_off[b + 1];
     if (VEC) {
-        __shared__ float s_acc[8][32][9];
-        const int cc = threadIdx.x & 31, ts = threadIdx.x >> 5;
-        const int d0 = (blockIdx.x * 32 + cc) * 8;
+        __shared__ float s_acc[32][8][9];
+        const int cc = threadIdx.x & 7, ts = threadIdx.x >> 3;
+        const int d0 = (blockIdx.x * 8 + cc) * 8;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (d0 < D)
-            for (int j = j0 + ts; j < j1; j += 8) {
+            for (int j = j0 + ts; j < j1; j += 32) {
                 float x[8];
                 wq_ld8(txt + (int64_t)j * D + d0, x);
                 const float w = inv_norm[j];
@@ -74,12 +75,12 @@ __global__ __launch_bounds__(256) void k_text_mean(const T* __restrict__ txt, co
 #pragma unroll
         for (int k = 0; k < 8; k++) s_acc[ts][cc][k] = acc[k];
         __syncthreads();
-        const int c2 = threadIdx.x >> 3, k2 = threadIdx.x & 7;      // 32 chunks x 8 columns
-        const int d = (blockIdx.x * 32 + c2) * 8 + k2;
-        if (d < D) {
+        const int c2 = threadIdx.x >> 3, k2 = threadIdx.x & 7;      // 8 chunks x 8 columns
+        const int d = (blockIdx.x * 8 + c2) * 8 + k2;
+        if (threadIdx.x < 64 && d < D) {
             float s = 0.f;
 #pragma unroll
-            for (int t = 0; t < 8; t++) s += s_acc[t][c2][k2];
+            for (int t = 0; t < 32; t++) s += s_acc[t][c2][k2];
             tbar[(int64_t)b * D + d] = j1 > j0 ? s / (float)(j1 - j0) : 0.f;
         }
     } else {
@@ -441,7 +442,7 @@ int run_pooled(wq_ctx* ctx, const void* vis_, const void* txt_, int B, int D, co
     hipStream_t st = ctx->stream;
     if (total_txt > 0)
         hipLaunchKernelGGL((k_text_norm<T, VEC>), dim3((unsigned)((total_txt + 3) / 4)), dim3(256), 0, st, txt, D, total_txt, inv_norm);
-    hipLaunchKernelGGL((k_text_mean<T, VEC>), dim3((D + 255) / 256, B), dim3(256), 0, st, txt, inv_norm, D, txt_off, tbar);
+    hipLaunchKernelGGL((k_text_mean<T, VEC>), dim3(VEC ? (D + 63) / 64 : (D + 255) / 256, B), dim3(256), 0, st, txt, inv_norm, D, txt_off, tbar);
     if (total_vis > 0) {
         const int64_t rows_per_block = VEC ? 16 : 4;
         hipLaunchKernelGGL((k_token_score<T, VEC>), dim3((unsigned)((total_vis + rows_per_block - 1) / rows_per_block)), dim3(256), 0, st,
