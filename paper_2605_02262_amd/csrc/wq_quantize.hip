@@ -2,11 +2,12 @@
 //
 //   k_plan      one workgroup: per-class padded offsets / lengths of every sequence, 16-bit row counts,
 //               capacity checks (device status word)
-//   k_quantize  one workgroup per (32-token destination block, KV head): gathers the source rows through
+//   k_quantize_all  one launch for the three classes and the 16-bit rows.  A class workgroup takes one
+//               (32-token destination block, KV head): gathers the source rows through
 //               perm (the window reorder is fused into the load), finds each group's min/max with
 //               wavefront shuffles, computes codes with the exact fp32 sequence of the format definition,
 //               stages them in LDS and writes the K tile / V block / metadata images with coalesced stores
-//   k_copy16    16-bit windows, video tail and text rows -> k16/v16
+//               The remaining workgroups copy one row each of the 16-bit windows, video tail and text -> k16/v16
 // HBM-bound: reads 2 x 2 bytes per (K,V) element pair once, writes b/8 + 4/group bytes per element.
 // This file is compiled with floating-point contraction off: the code sequence must round exactly as stated.
 #include <type_traits>
@@ -68,23 +69,28 @@ __global__ __launch_bounds__(256) void k_plan(int B, const int32_t* __restrict__
 // bits -> class index
 __host__ __device__ constexpr int cls_index(int bits) { return bits == 2 ? 0 : (bits == 4 ? 1 : 2); }
 
+template <int HD>
+struct QuantSmem {
+    uint32_t v[32][HD / 4 + 1];                 // V codes, 4 per word, rows padded by one word (conflict-free column reads)
+    uint32_t meta[2][4][32];                    // [plane][group][token]
+};
+
+// one (32-token destination block `blk` of class BITS, KV head `kvh`)
 template <typename T, int HD, int BITS>
-__global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const T* __restrict__ V, int B, int group,
-                                                  const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
-                                                  const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
-                                                  const int32_t* __restrict__ seg_windows, wq_packed_kv pk)
+__device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int kvh, const T* __restrict__ K, const T* __restrict__ V,
+                                               int B, int group, const int32_t* __restrict__ kv_off,
+                                               const int32_t* __restrict__ win_size, const int32_t* __restrict__ win_off,
+                                               const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_windows,
+                                               const wq_packed_kv& pk)
 {
     constexpr int C = cls_index(BITS);
     constexpr int QMAX = (1 << BITS) - 1;
     constexpr int CPT = HD / 8;                 // channels per thread: 8 threads share one token row
     constexpr int PER_DW = 32 / BITS;           // codes per output dword
-    __shared__ uint32_t s_v[32][HD / 4 + 1];    // V codes, 4 per word, rows padded by one word (conflict-free column reads)
-    __shared__ uint32_t s_meta[2][4][32];       // [plane][group][token]
+    auto& s_v = sm.v;
+    auto& s_meta = sm.meta;
     const int tid = threadIdx.x;
     const int Hkv = pk.Hkv;
-    // consecutive workgroups take the KV heads of one token block: together they read whole source rows
-    const int blk = blockIdx.x / Hkv;
-    const int kvh = blockIdx.x % Hkv;
     const int G = HD / group;
     const int32_t* off = pk.cls_off[C];
     const int64_t tok0 = (int64_t)blk * 32;
@@ -213,14 +219,14 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ K, const
     }
 }
 
+// row r of all 16-bit rows of the batch
 template <typename T>
-__global__ __launch_bounds__(256) void k_copy16(const T* __restrict__ K, const T* __restrict__ V, int B, int row_elems,
-                                                const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
-                                                const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
-                                                const int32_t* __restrict__ seg_windows, const int32_t* __restrict__ pre16,
-                                                wq_packed_kv pk)
+__device__ __forceinline__ void copy16_row(int64_t r, const T* __restrict__ K, const T* __restrict__ V, int B, int row_elems,
+                                           const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
+                                           const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
+                                           const int32_t* __restrict__ seg_windows, const int32_t* __restrict__ pre16,
+                                           const wq_packed_kv& pk)
 {
-    const int64_t r = blockIdx.x;               // global index over all 16-bit rows of the batch
     if (r >= pre16[B]) return;
     const int b = wq_find_seq(pre16, B, r);
     const int i = (int)(r - pre16[b]);
@@ -248,6 +254,29 @@ __global__ __launch_bounds__(256) void k_copy16(const T* __restrict__ K, const T
             v16[e] = __half_as_ushort(__float2half_rn(vx));
         }
     }
+}
+
+// The whole call after k_plan in one launch: workgroups [0, n0) take the 2-bit blocks, [n0, n1) the 4-bit blocks,
+// [n1, n2) the 8-bit blocks (consecutive workgroups = the KV heads of one token block: together they read whole source
+// rows), the rest one 16-bit row each.
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void k_quantize_all(const T* __restrict__ K, const T* __restrict__ V, int B, int group,
+                                                      const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
+                                                      const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
+                                                      const int32_t* __restrict__ seg_windows, const int32_t* __restrict__ pre16,
+                                                      wq_packed_kv pk, unsigned n0, unsigned n1, unsigned n2)
+{
+    __shared__ QuantSmem<HD> sm;
+    const unsigned w = blockIdx.x;
+    const unsigned Hkv = (unsigned)pk.Hkv;
+    if (w < n0)
+        quantize_block<T, HD, 2>(sm, (int)(w / Hkv), (int)(w % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+    else if (w < n1)
+        quantize_block<T, HD, 4>(sm, (int)((w - n0) / Hkv), (int)((w - n0) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+    else if (w < n2)
+        quantize_block<T, HD, 8>(sm, (int)((w - n1) / Hkv), (int)((w - n1) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+    else
+        copy16_row<T>((int64_t)(w - n2), K, V, B, pk.Hkv * HD, kv_off, win_size, win_off, perm, seg_windows, pre16, pk);
 }
 
 // one generated token per sequence -> the end of its 16-bit segment
@@ -438,19 +467,12 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
     int32_t* pre16 = reinterpret_cast<int32_t*>(ctx->ws + WQ_WS_HEADER);
     hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 0, st, B, kv_off, win_size, win_off, seg_windows, *pk, pre16,
                        wq_status_ptr(ctx));
-    dim3 blk(256);
-    if (pk->cap[0] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 2>), dim3((unsigned)(pk->cap[0] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
-                           kv_off, win_size, win_off, perm, seg_windows, *pk);
-    if (pk->cap[1] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 4>), dim3((unsigned)(pk->cap[1] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
-                           kv_off, win_size, win_off, perm, seg_windows, *pk);
-    if (pk->cap[2] > 0)
-        hipLaunchKernelGGL((k_quantize<T, HD, 8>), dim3((unsigned)(pk->cap[2] / 32 * pk->Hkv)), blk, 0, st, K, V, B, pk->group,
-                           kv_off, win_size, win_off, perm, seg_windows, *pk);
-    if (total_rows > 0 && pk->cap16 > 0)
-        hipLaunchKernelGGL(k_copy16<T>, dim3((unsigned)(total_rows < pk->cap16 ? total_rows : pk->cap16)), blk, 0, st, K, V, B, pk->Hkv * HD, kv_off, win_size,
-                           win_off, perm, seg_windows, pre16, *pk);
+    const int64_t n0 = pk->cap[0] / 32 * pk->Hkv, n1 = n0 + pk->cap[1] / 32 * pk->Hkv, n2 = n1 + pk->cap[2] / 32 * pk->Hkv;
+    const int64_t rows16 = pk->cap16 > 0 ? (total_rows < pk->cap16 ? total_rows : pk->cap16) : 0;
+    if (n2 + rows16 > 0x7FFFFFFF) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "too many blocks for one launch");
+    if (n2 + rows16 > 0)
+        hipLaunchKernelGGL((k_quantize_all<T, HD>), dim3((unsigned)(n2 + rows16)), dim3(256), 0, st, K, V, B, pk->group, kv_off, win_size,
+                           win_off, perm, seg_windows, pre16, *pk, (unsigned)n0, (unsigned)n1, (unsigned)n2);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }
