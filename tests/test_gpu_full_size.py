@@ -40,6 +40,35 @@ def test_long_video_7b_layer_full():
     if min(s[25] - s[26], s[127] - s[128]) > 4e-4 * abs(s).max():       # tier boundaries well separated
         assert np.array_equal(bits2[:256], o.bits[:256])
 
+    # the literal pairwise form on the matrix cores at this size (workgroups of 128 rows x 512 text columns)
+    import torch
+    from tests import wq_harness as H
+    from paper_2605_02262_amd import binding as W
+    w, t = bt.w, bt.t
+    tv, tt, tw = int(t.vis_off[-1]), int(t.txt_off[-1]), int(t.win_off[-1])
+    s_pair = W.wq_window_scores(g.ctx, H.to_dev(bt.E_v, w.dtype), H.to_dev(bt.E_t, w.dtype), H.i32(t.vis_off), H.i32(t.txt_off),
+                                H.i32(t.win_size), H.i32(t.win_off), tv, tt, tw, algo=W.SCORE_PAIRWISE_MFMA)
+    torch.cuda.synchronize()
+    H.assert_scores_close(s_pair, o.scores)
+
+    # the unfused variant of the operator-fusion ablation at this size: sequence 0 of the dequantized copy against the
+    # textbook attention (fp64) over exactly those rows
+    tot = [int(sum(o.pk.cls_len[c][b] for c in range(3)) + o.pk.len16[b]) for b in range(w.B)]
+    off = np.concatenate([[0], np.cumsum(tot)]).astype(np.int32)
+    dense = W.PackedKV(w.B, w.Hkv, w.hd, w.group, g.pk.dtype16, [0, 0, 0], off)
+    W.wq_dequantize(g.ctx, g.pk, dense)
+    out = W.wq_decode_attention(g.ctx, H.to_dev(bt.q, w.dtype), dense, 1.0 / float(np.sqrt(w.hd)), 0, max(tot))
+    torch.cuda.synchronize()
+    assert g.ctx.device_status() == 0 and dense.len16.cpu().numpy().tolist() == tot
+    k0 = dense.k16[:tot[0]].float().cpu().numpy()
+    v0 = dense.v16[:tot[0]].float().cpu().numpy()
+    want = O.attention_dense(bt.q[0], k0, v0, 1.0 / np.sqrt(w.hd))
+    assert H.attention_error(out[0].cpu().numpy()[None], want[None]) <= H.ATTN_TOL
+    # the copy is rounded into bf16 (2^-8 relative per value): near, not equal to, the attention over the exact values
+    dev = H.attention_error(out.cpu().numpy(), o.out)
+    print(f"unfused (bf16 copy) vs exact dequantized values: {dev:.3e}")
+    assert dev <= 0.1
+
 
 @pytest.mark.parametrize("layer", [0, 27])
 def test_7b_batch8_sampled_layers(layer):
