@@ -148,28 +148,31 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
             sh = __float2half_rn(1.0f);
         }
         const float inv = 1.0f / s;
-        uint32_t cw[CPT / 4];                   // this thread's codes, 4 per word (8 bits each)
+        // This thread's codes: the K plane takes them as consecutive BITS-wide fields of its token's row quarter
+        // (pw, stored below); the V plane as bytes, 4 per word (cw), for the transposition through LDS.
+        // A token past the end has x = 0 everywhere, which gives m = 0, s = 1 and codes 0.
+        constexpr int NB = CPT * BITS / 8;      // bytes of the K fields: 2..16
+        uint32_t cw[CPT / 4], pw[(NB + 3) / 4];
 #pragma unroll
         for (int i = 0; i < CPT / 4; i++) cw[i] = 0;
+#pragma unroll
+        for (int i = 0; i < (NB + 3) / 4; i++) pw[i] = 0;
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
             float t = (x[i] - m) * inv;         // contraction is off: subtract, round, multiply, round
             float q = rintf(t);
             q = fminf(fmaxf(q, 0.0f), (float)QMAX);
-            cw[i >> 2] |= (valid ? (uint32_t)(int)q : 0u) << (8 * (i & 3));
+            const uint32_t code = (uint32_t)(int)q;
+            if (plane == 0)
+                pw[(i * BITS) >> 5] |= code << ((i * BITS) & 31);
+            else
+                cw[i >> 2] |= code << (8 * (i & 3));
         }
         if (plane == 0) {
-            // K plane: the thread's CPT codes are consecutive fields of its token's row quarter: pack and store
             constexpr int Q = HD / 4;
-            constexpr int NB = CPT * BITS / 8;  // bytes: 2..16
             const int j = (p * CPT) / Q, e0 = (p * CPT) % Q;
             uint8_t* out = static_cast<uint8_t*>(pk.codes[C]) + ((int64_t)kvh * pk.cap[C] + tok0) * HD * BITS / 8 +
                            (u >> 4) * (16 * HD * BITS / 8) + ((j * 16 + (u & 15)) * Q + e0) * BITS / 8;
-            uint32_t pw[(NB + 3) / 4];
-#pragma unroll
-            for (int i = 0; i < (NB + 3) / 4; i++) pw[i] = 0;
-#pragma unroll
-            for (int i = 0; i < CPT; i++) pw[(i * BITS) >> 5] |= ((cw[i >> 2] >> (8 * (i & 3))) & 0xFFu) << ((i * BITS) & 31);
             if constexpr (NB == 2) {
                 *reinterpret_cast<uint16_t*>(out) = (uint16_t)pw[0];
             } else if constexpr (NB == 4) {
