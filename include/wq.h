@@ -230,7 +230,7 @@ int wq_decode_times_us(wq_ctx* ctx, float* us, int n);
  * read-only when dst is NULL, a plain copy otherwise.  Gives the achievable HBM rate and the reference that
  * hardware byte counters are scaled by.                                                                       */
 int wq_probe_stream(wq_ctx* ctx, const void* src, void* dst, int64_t bytes, int blocks);
-/* Runs `workgroups` x 8 wavefronts of `iters` x 32 independent v_mfma_f32_16x16x32_bf16 products on register
+/* Runs `workgroups` x 8 wavefronts of `iters` (a multiple of 4) x 32 independent v_mfma_f32_16x16x32_bf16 products on register
  * operands (no memory traffic): all ones when random_operands == 0, else random values that change from product to
  * product.  Gives the matrix-core rate this GPU sustains, which depends on the data (the clock drops under
  * load): the figure the pairwise scoring kernel is to be read against.  *flops (host, may be NULL) receives the

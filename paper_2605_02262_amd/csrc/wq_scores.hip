@@ -554,8 +554,8 @@ __device__ __forceinline__ uint32_t probe_mix(uint32_t x)
     return x;
 }
 
-// 32 independent accumulator tiles per wavefront, operands in registers only; RANDOM: bf16 values in (-2, 2) that
-// move to other products every iteration (a handful of register moves per 32 products), else all ones.
+// 32 independent accumulator tiles per wavefront, operands in registers only; RANDOM: bf16 values in (-2, 2), 8 x 4
+// different operand pairs in a row, moved to other products every 128 products; else all ones.
 template <bool RANDOM>
 __global__ __launch_bounds__(512) void k_probe_mfma(uint32_t* __restrict__ sink, int iters)
 {
@@ -569,12 +569,14 @@ __global__ __launch_bounds__(512) void k_probe_mfma(uint32_t* __restrict__ sink,
     for (int i = 0; i < 8; i++) a[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
 #pragma unroll
     for (int i = 0; i < 4; i++) b[i] = make_uint4(rnd(), rnd(), rnd(), rnd());
-    for (int it = 0; it < iters; it++) {
+    for (int it = 0; it < iters; it += 4) {         // iters is a multiple of 4 (checked by the host)
 #pragma unroll
-        for (int i = 0; i < 8; i++)
+        for (int r = 0; r < 4; r++)
 #pragma unroll
-            for (int j = 0; j < 4; j++) acc[i * 4 + j] = mfma_s<true>(a[i], b[j], acc[i * 4 + j]);
-        if (RANDOM) {
+            for (int i = 0; i < 8; i++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) acc[i * 4 + j] = mfma_s<true>(a[i], b[j], acc[i * 4 + j]);
+        if (RANDOM) {                               // 48 register moves per 128 products
             const uint4 t = a[0];
 #pragma unroll
             for (int i = 0; i < 7; i++) a[i] = a[i + 1];
@@ -593,7 +595,7 @@ __global__ __launch_bounds__(512) void k_probe_mfma(uint32_t* __restrict__ sink,
 
 extern "C" int wq_probe_mfma(wq_ctx* ctx, int random_operands, int workgroups, int iters, double* flops)
 {
-    if (!ctx || workgroups <= 0 || iters <= 0) return WQ_ERR_ARG;
+    if (!ctx || workgroups <= 0 || iters <= 0 || iters % 4 != 0) return WQ_ERR_ARG;
     if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
     if (random_operands)
         hipLaunchKernelGGL(k_probe_mfma<true>, dim3(workgroups), dim3(512), 0, ctx->stream, wq_status_ptr(ctx) + 8, iters);
