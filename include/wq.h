@@ -192,7 +192,7 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * (off16[b]+len16[b] == off16[b+1], or == cap16) is left unchanged and WQ_DEV_SEG16_OVERFLOW is raised.       */
 int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
 
-/* ---- the unfused variant of the operator-fusion ablation (Sec. 4.6, Table "operator fusion") ------------------
+/* ---- the unfused variant of the operator-fusion ablation (operator fusion: Sec. 3.3.3; its ablation: Sec. 4.4, table on the impact of operator fusion) ------------------
  * Dequantizes a packed cache to memory: sequence b's rows off16[b] .. of dst's 16-bit segment receive the values
  * m + s*code (one fp32 fused multiply-add, rounded to nearest even into dtype16) of src's 2-bit, 4-bit and 8-bit
  * tokens, in this order (the order of the cache), followed by src's 16-bit rows; dst's len16 is written, dst's

@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void k_append16(const T* __restrict__ k_new, c
     if (threadIdx.x == 0) pk.len16[b] += 1;
 }
 
-// ---- the unfused variant of the operator-fusion ablation (Sec. 4.6): packed classes back to 16-bit rows -------------
+// ---- the unfused variant of the operator-fusion ablation (Sec. 3.3.3, Sec. 4.4): packed classes back to 16-bit rows -------------
 // dst's 16-bit segment receives, per sequence, the dequantized tokens of src's 2-, 4- and 8-bit classes (in this order,
 // the order of the cache) and then src's 16-bit rows; dst's classes are empty.  Decode attention over dst is then the
 // plain 16-bit attention that a dequantize-to-memory implementation would run.

@@ -155,7 +155,7 @@ def workload(cfg: int, seed: Optional[int] = None) -> Workload:
             seqs.append(SeqSpec(frames, 196, S, 256, quota))
         return Workload("cfg4-ragged", BF16, BF16, 28, 4, 128, 64, 3584, 1.5, seqs, sd, pin_first=0)
     if cfg == 5:
-        # the paper's own operating point (Sec. 4.1 defaults, Sec. 4.4 token counts): batch 1, 100 frames, windows of
+        # the paper's own operating point (Sec. 4.1 defaults, Sec. 4.3 token counts): batch 1, 100 frames, windows of
         # 32 tokens, top tier kept 16-bit.  19600 visual tokens = 612 windows + a tail of 16; 2 / 217 / 393 windows at
         # 16 / 4 / 2 bits and 135 text tokens give 215 / 6944 / 12576 tokens (the paper counts 215 / 6956 / 12564).
         s = SeqSpec(100, 196, 32, 135, (2, 217, 393))

@@ -89,7 +89,7 @@ def test_ragged_batch32():
 
 
 def test_paper_operating_point_16bit_top_tier():
-    """The paper's own setting (Sec. 4.1 defaults, Sec. 4.4 token counts): batch 1, 100 frames, windows of 32 tokens,
+    """The paper's own setting (Sec. 4.1 defaults, Sec. 4.3 token counts): batch 1, 100 frames, windows of 32 tokens,
     top tier (first window and the best-scoring one) kept 16-bit, 217 / 393 windows at 4 / 2 bits, 135 text tokens."""
     bt = synth.batch(synth.workload(5))
     g, o = _full(bt)

@@ -317,7 +317,7 @@ def _dense_expected(o, dtype16):
 
 @pytest.mark.parametrize("dtype,hd,g", [(synth.BF16, 128, 64), (synth.F16, 64, 32)])
 def test_unfused_ablation_dequantize_to_memory_then_16bit_attention(dtype, hd, g):
-    """wq_dequantize (the unfused variant of the operator-fusion ablation, Sec. 4.6): every dequantized value is the
+    """wq_dequantize (the unfused variant of the operator-fusion ablation, Sec. 3.3.3 and Sec. 4.4): every dequantized value is the
     format's m + s*code rounded once into the 16-bit type; decode attention over the dense copy agrees with the fp64
     textbook attention over those rows."""
     H = _h()
