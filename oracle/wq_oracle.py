@@ -233,6 +233,14 @@ def reorder_quantize(K, V, kv_off, win_size, win_off, perm, seg_windows, group: 
     off16 = _i32(off16)
     cap = [int(cls_off[c, B]) for c in range(3)] if cap is None else list(cap)
     cap16 = int((off16 + len16).max()) if cap16 is None and B else (cap16 or 0)
+    # the C routines below trust these sizes (the GPU library reports an overflow instead): refuse what does not fit
+    for c in range(3):
+        if cap[c] < int(cls_off[c, B]):
+            raise ValueError(f"class {CLASS_BITS[c]}-bit needs {int(cls_off[c, B])} token slots, cap is {cap[c]}")
+    if B and int((off16 + len16).max()) > cap16:
+        raise ValueError(f"the 16-bit segment needs {int((off16 + len16).max())} rows, cap16 is {cap16}")
+    if B > 1 and np.any(off16[1:] < off16[:-1] + len16[:-1]):
+        raise ValueError("16-bit segments overlap")
     src = [np.full(max(cap[c], 1), -1, dtype=np.int64) for c in range(3)]
     rows16 = np.full(max(cap16, 1), -1, dtype=np.int64)
     lib().wqo_gather_rows(C.c_int(B), _p(kv_off), _p(win_size), _p(win_off), _p(perm), _p(seg), _p(cls_off),

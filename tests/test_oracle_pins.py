@@ -499,3 +499,21 @@ def test_vote_bits_majority_ties_and_ragged_positions():
                 idx = [int(i) for i in pb if out[off[b] + i] == w]
                 assert idx == sorted(idx)
             assert seg[b].tolist() == [widths.count(w) for w in (2, 4, 8, 16)]
+
+
+def test_reorder_quantize_refuses_buffers_that_are_too_small():
+    """The oracle's C routines trust the capacities they are given: the wrapper refuses what does not fit (a pinned first
+    window takes the top width even when the top quota is zero, so that class then needs room for it)."""
+    w = synth.Workload("guard", synth.BF16, synth.BF16, 14, 2, 64, 32, 64, 1.0, [synth.SeqSpec(4, 16, 16, 8, (0, 2, 2))], 5,
+                       top_bits=8, pin_first=1)
+    bt = synth.batch(w)
+    t = bt.t
+    sc = O.window_scores(bt.E_v, bt.E_t, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pooled").astype(np.float32)
+    bits, perm, seg = O.assign_bits(sc, t.win_off, 0, quota=t.quota, top_bits=8, pin_first=1)
+    assert seg.tolist() == [[2, 1, 1, 0]] and bits[0] == 8              # the pin took one 4-bit slot
+    with pytest.raises(ValueError):
+        O.reorder_quantize(bt.K, bt.V, t.kv_off, t.win_size, t.win_off, perm, seg, w.group, off16=[0], cap=[32, 32, 0], cap16=8)
+    with pytest.raises(ValueError):
+        O.reorder_quantize(bt.K, bt.V, t.kv_off, t.win_size, t.win_off, perm, seg, w.group, off16=[0], cap=[32, 32, 32], cap16=4)
+    pk = O.reorder_quantize(bt.K, bt.V, t.kv_off, t.win_size, t.win_off, perm, seg, w.group, off16=[0], cap=[32, 32, 32], cap16=8)
+    assert pk.cls_len.tolist() == [[32], [16], [16]] and pk.len16.tolist() == [8]

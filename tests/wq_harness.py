@@ -54,6 +54,12 @@ def capacities(w: synth.Workload, slack: int = 0):
     n16 = []
     for s in w.seqs:
         n_top, n4, n2 = s.quota
+        if w.pin_first and s.n_win > 0 and n_top == 0:      # the pinned window gets the top width from the next class's quota
+            n_top = 1
+            if n4 > 0:
+                n4 -= 1
+            elif n2 > 0:
+                n2 -= 1
         per = {2: n2, 4: n4, 8: n_top if w.top_bits == 8 else 0}
         for c, b in enumerate((2, 4, 8)):
             cap[c] += (per[b] * s.win_size + 31) // 32 * 32
