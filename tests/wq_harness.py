@@ -53,13 +53,20 @@ def capacities(w: synth.Workload, slack: int = 0):
     cap = [0, 0, 0]
     n16 = []
     for s in w.seqs:
-        n_top, n4, n2 = s.quota
-        if w.pin_first and s.n_win > 0 and n_top == 0:      # the pinned window gets the top width from the next class's quota
-            n_top = 1
-            if n4 > 0:
+        # the window counts the quota rule gives (the same clipping as the assignment: the pinned window takes one slot of
+        # the first non-zero quota, quotas are clipped to the window count, what is left is 2-bit)
+        n_top, n4, _ = s.quota
+        first = 1 if (w.pin_first and s.n_win > 0) else 0
+        if first:
+            if n_top > 0:
+                n_top -= 1
+            elif n4 > 0:
                 n4 -= 1
-            elif n2 > 0:
-                n2 -= 1
+        m = s.n_win - first
+        n_top = min(max(n_top, 0), m)
+        n4 = min(max(n4, 0), m - n_top)
+        n2 = m - n_top - n4
+        n_top += first
         per = {2: n2, 4: n4, 8: n_top if w.top_bits == 8 else 0}
         for c, b in enumerate((2, 4, 8)):
             cap[c] += (per[b] * s.win_size + 31) // 32 * 32
