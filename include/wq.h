@@ -178,7 +178,8 @@ typedef struct {
  * K, V [total_rows, Hkv, hd] device, element type `dtype`; sequence b owns rows kv_off[b]..kv_off[b+1]-1:
  * its windows first, then tail and text rows (kept 16-bit).  bits/perm/seg_windows as written by
  * wq_assign_bits.  dtype16 must be WQ_BF16 for bf16 input, WQ_F16 for fp16 and fp32 input (fp32 values are
- * rounded to nearest even).  total_rows: host copy of kv_off[B].  Fills every field of *out marked
+ * rounded to nearest even).  total_rows: host copy of kv_off[B]; with total_rows > 0, K, V and perm must not be NULL
+ * (perm is not read when the batch has no window at all: any valid pointer will do).  Fills every field of *out marked
  * "written"; all of out's pointers and capacities are set by the caller.                                    */
 int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
                         const int32_t* win_size, const int32_t* win_off, const int32_t* perm,

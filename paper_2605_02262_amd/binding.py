@@ -235,8 +235,11 @@ def wq_vote_bits(ctx: Context, bits, win_off, max_windows: int):
 
 def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg_windows, total_rows: int, out: PackedKV):
     B = win_size.numel()
+    # a batch without any window has an empty perm: the library still wants a valid pointer (it cannot see the window
+    # count on the host), which is never read then
+    perm_ptr = _ptr(perm) if perm.numel() else _ptr(seg_windows)
     ctx.check(lib().wq_reorder_quantize(ctx.handle, _ptr(K), _ptr(V), _dtype_id(K), B, _ptr(kv_off), _ptr(win_size),
-                                        _ptr(win_off), _ptr(perm), _ptr(seg_windows), total_rows, C.byref(out.desc)))
+                                        _ptr(win_off), perm_ptr, _ptr(seg_windows), total_rows, C.byref(out.desc)))
     return out
 
 
