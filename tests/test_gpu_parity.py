@@ -315,28 +315,19 @@ def _dense_expected(o, dtype16):
     return Ks, Vs
 
 
-@pytest.mark.parametrize("dtype,hd,g", [(synth.BF16, 128, 64), (synth.F16, 64, 32)])
-def test_unfused_ablation_dequantize_to_memory_then_16bit_attention(dtype, hd, g):
-    """wq_dequantize (the unfused variant of the operator-fusion ablation, Sec. 3.3.3 and Sec. 4.4): every dequantized value is the
-    format's m + s*code rounded once into the 16-bit type; decode attention over the dense copy agrees with the fp64
-    textbook attention over those rows."""
-    H = _h()
+def _check_dense(g_run, o, bt, H, splits=2):
+    """wq_dequantize of a finished GPU run into a dense 16-bit copy: tables, every value against m + s*code, attention
+    over the copy against the textbook attention (fp64) over exactly the rows that were written."""
     from oracle import wq_oracle as O
     from paper_2605_02262_amd import binding as W
-    specs = [synth.SeqSpec(9, 21, 21, 13, (2, 3, 4)),             # 189 tokens: blocks of 32 with ragged ends in every class
-             synth.SeqSpec(4, 16, 16, 40, (1, 1, 2)),
-             synth.SeqSpec(0, 10, 4, 5, (0, 0, 0)),               # text only
-             synth.SeqSpec(6, 32, 32, 0, (2, 2, 2), tail=7)]      # video tail, no text
-    bt = _custom(321 + hd, hd, g, 2, 7, dtype, specs)
-    w, t = bt.w, bt.t
-    g_run, o, _ = _check(bt, H, splits=2)
+    w = bt.w
     pk = g_run.pk
     totals = [int(sum(o.pk.cls_len[c][b] for c in range(3)) + o.pk.len16[b]) for b in range(w.B)]
     off = np.concatenate([[0], np.cumsum([n + 3 for n in totals])]).astype(np.int32)      # a little slack per sequence
     dense = W.PackedKV(w.B, w.Hkv, w.hd, w.group, pk.dtype16, [0, 0, 0], off, fill=0xA5)
     W.wq_dequantize(g_run.ctx, pk, dense)
     q = H.to_dev(bt.q, w.dtype)
-    out = W.wq_decode_attention(g_run.ctx, q, dense, 1.0 / float(np.sqrt(w.hd)), 2, max(totals))
+    out = W.wq_decode_attention(g_run.ctx, q, dense, 1.0 / float(np.sqrt(w.hd)), splits, max(totals + [1]))
     torch.cuda.synchronize()
     assert g_run.ctx.device_status() == 0
     assert np.array_equal(dense.len16.cpu().numpy(), np.asarray(totals, np.int32))
@@ -352,12 +343,32 @@ def test_unfused_ablation_dequantize_to_memory_then_16bit_attention(dtype, hd, g
             assert np.all(np.abs(got - want) <= half_ulp * np.abs(want) * 1.0001 + 2.0 ** -25), "dequantized value off by more than one rounding"
     # The dense copy holds the values rounded into the 16-bit type (2^-8 relative for bf16), so its attention differs
     # from the attention over the exact values m + s*code by more than the fused kernel's error: a sanity bound only.
-    assert H.attention_error(out.cpu().numpy(), o.out) <= 2e-2
+    assert H.attention_error(out.cpu().numpy(), o.out) <= 5e-2
     # The bar proper: the textbook attention (fp64) over exactly the rows that were written.
     for b in range(w.B):
         a, n = int(off[b]), totals[b]
+        if n == 0:
+            continue
         want = O.attention_dense(bt.q[b], k16[a:a + n].astype(np.float32), v16[a:a + n].astype(np.float32), 1.0 / np.sqrt(w.hd))
         assert H.attention_error(out[b].cpu().numpy()[None], want[None]) <= H.ATTN_TOL
+
+
+@pytest.mark.parametrize("dtype,hd,g", [(synth.BF16, 128, 64), (synth.F16, 64, 32)])
+def test_unfused_ablation_dequantize_to_memory_then_16bit_attention(dtype, hd, g):
+    """wq_dequantize (the unfused variant of the operator-fusion ablation, Sec. 3.3.3 and Sec. 4.4): every dequantized value is the
+    format's m + s*code rounded once into the 16-bit type; decode attention over the dense copy agrees with the fp64
+    textbook attention over those rows."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(9, 21, 21, 13, (2, 3, 4)),             # 189 tokens: blocks of 32 with ragged ends in every class
+             synth.SeqSpec(4, 16, 16, 40, (1, 1, 2)),
+             synth.SeqSpec(0, 10, 4, 5, (0, 0, 0)),               # text only
+             synth.SeqSpec(6, 32, 32, 0, (2, 2, 2), tail=7)]      # video tail, no text
+    bt = _custom(321 + hd, hd, g, 2, 7, dtype, specs)
+    w, t = bt.w, bt.t
+    g_run, o, _ = _check(bt, H, splits=2)
+    _check_dense(g_run, o, bt, H)
 
 
 def test_dequantize_reports_a_destination_that_is_too_small():
@@ -372,3 +383,37 @@ def test_dequantize_reports_a_destination_that_is_too_small():
     assert g_run.ctx.device_status() == W.DEV_SEG16_OVERFLOW
     assert int(small.len16.sum().item()) == 0
     assert int((small.k16.view(torch.int16) != 0).sum().item()) == 0 and int((small.v16.view(torch.int16) != 0).sum().item()) == 0   # nothing was written
+
+
+@pytest.mark.parametrize("seed", [7, 2024])
+def test_random_ragged_workloads(seed):
+    """Seeded random batches: 1-5 sequences, windows of 3-69 tokens, 0-13 windows, tails, text of 0-59 tokens, any shape,
+    dtype, quota split (also quotas that leave windows over, and pins with a zero top quota), split count and kernel."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for it in range(25):
+        hd, g = [(64, 32), (64, 64), (128, 32), (128, 64), (128, 128)][rng.integers(5)]
+        dtype = [synth.BF16, synth.F16, synth.F32][rng.integers(3)]
+        specs = []
+        for _ in range(int(rng.integers(1, 6))):
+            S, nw, nt, tail = int(rng.integers(3, 70)), int(rng.integers(0, 14)), int(rng.integers(0, 60)), int(rng.integers(0, 5))
+            a = int(rng.integers(0, nw + 1))
+            c = int(rng.integers(0, nw - a + 1))
+            specs.append(synth.SeqSpec(nw, S, S, nt, (a, c, nw - a - c), tail=tail) if nw > 0 else
+                         synth.SeqSpec(0, 10, 4, max(nt, 1), (0, 0, 0)))
+        top = 16 if rng.integers(4) == 0 else 8
+        w = synth.Workload(f"random-{seed}-{it}", dtype, synth.BF16 if dtype == synth.BF16 else synth.F16, 2 * int(rng.integers(1, 8)), 2,
+                           hd, g, 64, 1.0, specs, 1000 * seed + it, top_bits=top, pin_first=int(rng.integers(2)))
+        bt = synth.batch(w)
+        kw = dict(splits=int(rng.integers(0, 5)),
+                  algo=[W.DECODE_AUTO, W.DECODE_GENERIC, W.DECODE_MFMA][rng.integers(3)] if hd // g == 2 else W.DECODE_AUTO)
+        if top == 16:       # any window may end up in any class or in the 16-bit segment
+            kw["cap"] = [sum((s.n_win * s.win_size + 31) // 32 * 32 for s in w.seqs)] * 3
+            kw["off16"] = np.concatenate([[0], np.cumsum([s.n_vis + s.n_text + 4 for s in w.seqs])]).astype(np.int32)
+        g_run, o, err = _check(bt, H, **kw)
+        worst = max(worst, err)
+        if it % 3 == 0:
+            _check_dense(g_run, o, bt, H, splits=kw["splits"])
+    assert worst <= H.ATTN_TOL
