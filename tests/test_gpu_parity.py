@@ -141,6 +141,38 @@ def test_scores_pairwise_on_matrix_cores(dtype):
     H.assert_scores_close(s_pool, want)
 
 
+def test_scores_random_shapes_both_forms():
+    """Seeded random batches through both scoring forms against the oracle's literal pairwise form: text lengths on both
+    sides of the matrix-core kernel's tile and pass edges (16, 64, 128, 256, 512 columns; more than one pass), ragged rows."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(5)
+    for it in range(16):
+        dtype = [synth.BF16, synth.F16][rng.integers(2)]
+        D = int(rng.choice([128, 256, 384, 640]))
+        specs = []
+        for _ in range(int(rng.integers(1, 5))):
+            S, nw, tail = int(rng.integers(1, 50)), int(rng.integers(0, 20)), int(rng.integers(0, 5))
+            nt = int(rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513, 700, 1100]))
+            specs.append(synth.SeqSpec(nw, S, S, nt, (0, 0, nw), tail=tail) if nw > 0 else synth.SeqSpec(0, 10, 4, max(nt, 1), (0, 0, 0)))
+        w = synth.Workload(f"scores-random-{it}", dtype, dtype, 14, 2, 64, 32, D, 1.0, specs, 500 + it)
+        t = synth.tables(w)
+        if int(t.win_off[-1]) == 0:
+            continue
+        ets, evs = zip(*[synth.embeddings(w, b) for b in range(w.B)])
+        Et, Ev = np.concatenate(ets), np.concatenate(evs)
+        ctx = W.Context(W.workspace_bytes(w.B, 0, 0, 0, Ev.shape[0], Et.shape[0], w.D))
+        args = (H.to_dev(Ev, dtype), H.to_dev(Et, dtype), H.i32(t.vis_off), H.i32(t.txt_off), H.i32(t.win_size), H.i32(t.win_off),
+                Ev.shape[0], Et.shape[0], int(t.win_off[-1]))
+        s_mfma = W.wq_window_scores(ctx, *args, algo=W.SCORE_PAIRWISE_MFMA)
+        s_pool = W.wq_window_scores(ctx, *args, algo=W.SCORE_POOLED)
+        torch.cuda.synchronize()
+        want = O.window_scores(Ev, Et, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pairwise")
+        H.assert_scores_close(s_mfma, want)
+        H.assert_scores_close(s_pool, want)
+
+
 def test_decode_fixed_shares_is_reproducible_and_agrees_with_block_pool():
     """WQ_DECODE_FIXED_SHARES: the same bits on every run; the default (blocks handed out as wavefronts get free)
     sums in a run-dependent order and agrees to rounding.  Both are checked against the oracle."""
