@@ -449,3 +449,36 @@ def test_random_ragged_workloads(seed):
         if it % 3 == 0:
             _check_dense(g_run, o, bt, H, splits=kw["splits"])
     assert worst <= H.ATTN_TOL
+
+
+def test_random_medium_caches_through_the_matrix_core_decode_kernel():
+    """Seeded random caches of a few thousand tokens per sequence (many 32-token blocks per workgroup, 1-16 splits, 1-8 query
+    heads per KV head, both block hand-out modes): quantization bit-exact, attention within the tolerance."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(3)
+    for it in range(12):
+        hd, g = [(64, 32), (128, 64)][rng.integers(2)]
+        dtype = [synth.BF16, synth.F16][rng.integers(2)]
+        specs = []
+        for _ in range(int(rng.integers(1, 5))):
+            S, nw, nt, tail = int(rng.integers(16, 200)), int(rng.integers(1, 60)), int(rng.integers(0, 300)), int(rng.integers(0, 9))
+            a = int(rng.integers(0, nw + 1))
+            c = int(rng.integers(0, nw - a + 1))
+            specs.append(synth.SeqSpec(nw, S, S, nt, (a, c, nw - a - c), tail=tail))
+        rep, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 4))
+        w = synth.Workload(f"medium-{it}", dtype, dtype, rep * Hkv, Hkv, hd, g, 64, 1.5, specs, 900 + it,
+                           top_bits=[8, 16][rng.integers(2)], pin_first=1)
+        bt = synth.batch(w, with_embeddings=False)
+        sc = rng.standard_normal(int(bt.t.win_off[-1])).astype(np.float32)
+        kw = dict(splits=int(rng.integers(0, 17)), algo=[W.DECODE_AUTO, W.DECODE_MFMA | W.DECODE_FIXED_SHARES][rng.integers(2)],
+                  with_scores=False, scores_override=sc)
+        if w.top_bits == 16:
+            kw["cap"] = [sum((s.n_win * s.win_size + 31) // 32 * 32 for s in w.seqs)] * 3
+            kw["off16"] = np.concatenate([[0], np.cumsum([s.n_vis + s.n_text + 4 for s in w.seqs])]).astype(np.int32)
+        g_run = H.run_gpu(bt, **kw)
+        o = H.run_oracle(bt, scores_override=sc, with_scores=False, **{k: v for k, v in kw.items() if k in ("cap", "off16")})
+        assert np.array_equal(g_run.bits.cpu().numpy(), o.bits) and np.array_equal(g_run.perm.cpu().numpy(), o.perm)
+        H.assert_packed_equal(g_run, o)
+        assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL
+        assert g_run.ctx.device_status() == 0
