@@ -53,7 +53,8 @@ def measured_traffic():
 def decode_loop(args):
     """The 7B-shaped decoder loop (28 layers, 8 sequences of 64 frames x 196 + 256 text tokens, bit mix 20/50/30 %):
     every decode step appends one generated token per sequence to every layer's 16-bit segment and attends over that
-    layer's packed cache.  One step (28 appends + 28 decode calls) is captured in a HIP graph and replayed.
+    layer's packed cache.  One step (28 wq_decode_append_attention calls, one kernel launch each) is captured in a HIP
+    graph and replayed.
     K, V, queries and scores are drawn on the device (torch generator, same distributions as the host generator)."""
     import torch
     from paper_2605_02262_amd import binding as W
@@ -105,8 +106,12 @@ def decode_loop(args):
 
     def one_step():
         for layer in range(L):
-            W.wq_append_kv(ctx, kn[layer], vn[layer], caches[layer])
-            W.wq_decode_attention(ctx, qs[layer], caches[layer], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=outs[layer])
+            if args.separate_append:
+                W.wq_append_kv(ctx, kn[layer], vn[layer], caches[layer])
+                W.wq_decode_attention(ctx, qs[layer], caches[layer], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=outs[layer])
+            else:
+                W.wq_decode_append_attention(ctx, qs[layer], caches[layer], kn[layer], vn[layer], sm_scale, nsplit, max_tok,
+                                             W.DECODE_AUTO, out=outs[layer])
 
     bytes0 = sum(pk.bytes_algorithmic() for pk in caches)
     row_bytes = L * B * w.Hkv * w.hd * 2 * 2                                 # 16-bit rows added per step, all layers
@@ -155,6 +160,7 @@ def decode_loop(args):
                       "bit_mix_windows_8_4_2": list(map(int, w.seqs[0].quota)), "splits": nsplit},
            "us_per_step_graph": round(us, 1), "us_per_layer": round(us / L, 2), "us_per_step_eager": round(us_eager, 1),
            "bytes_per_step": int(bytes_step), "pct_hbm_peak": round(100 * bytes_step / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 1),
+           "launches_per_layer": 2 if args.separate_append else 1,
            "rows_appended_per_sequence": int(len16[0] - w.seqs[0].n_text), "device_status": status, "outputs_finite": finite}
     print(json.dumps(res), flush=True)
 
@@ -167,6 +173,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload id (3 = long-video 7B-shaped layer)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="with --decode-loop: wq_append_kv + wq_decode_attention per layer instead of the one-call step")
     ap.add_argument("--decode-loop", action="store_true",
                     help="time the 28-layer decode loop of the 7B-shaped batch-8 workload (one step = one HIP graph replay)")
     args = ap.parse_args()

@@ -193,6 +193,18 @@ int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, in
  * (off16[b]+len16[b] == off16[b+1], or == cap16) is left unchanged and WQ_DEV_SEG16_OVERFLOW is raised.       */
 int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
 
+/* ---- a decode step in one call (Sec. 2.2): append the generated token's keys and values, then attend over the
+ * cache that now includes them.  Same arguments and results as wq_append_kv(k_new, v_new, new_dtype) followed by
+ * wq_decode_attention(...).  When the matrix-core kernel handles the whole launch (what WQ_DECODE_AUTO picks for
+ * hd/group == 2 with a query of the cache's 16-bit type family) and k_new, v_new have the cache's own 16-bit type, it is
+ * ONE kernel launch: the new row is read from k_new / v_new by the workgroup that walks its block, copied into the cache
+ * by another, and len16[b] is raised by the sequence's last workgroup to finish; otherwise the two launches are made.
+ * A sequence whose 16-bit segment is full is attended without the new token and raises WQ_DEV_SEG16_OVERFLOW.
+ * WQ_DECODE_PARTIALS_ONLY is not accepted here.                                                                  */
+int wq_decode_append_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
+                               const void* k_new, const void* v_new, int new_dtype, float sm_scale, int num_splits,
+                               int64_t max_seq_tokens, int algo, float* out, float* lse);
+
 /* ---- the unfused variant of the operator-fusion ablation (operator fusion: Sec. 3.3.3; its ablation: Sec. 4.4, table on the impact of operator fusion) ------------------
  * Dequantizes a packed cache to memory: sequence b's rows off16[b] .. of dst's 16-bit segment receive the values
  * m + s*code (one fp32 fused multiply-add, rounded to nearest even into dtype16) of src's 2-bit, 4-bit and 8-bit

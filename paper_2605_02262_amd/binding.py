@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_append_kv.argtypes = [vp, vp, vp, i32, i32, C.POINTER(_PackedKV)]
         L.wq_dequantize.argtypes = [vp, i32, C.POINTER(_PackedKV), C.POINTER(_PackedKV)]
+        L.wq_decode_append_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), vp, vp, i32, f32, i32, i64, i32, vp, vp]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
         L.wq_probe_mfma.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_double)]
@@ -246,6 +247,17 @@ def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg
 def wq_append_kv(ctx: Context, k_new, v_new, kv: PackedKV):
     B = k_new.shape[0]
     ctx.check(lib().wq_append_kv(ctx.handle, _ptr(k_new), _ptr(v_new), _dtype_id(k_new), B, C.byref(kv.desc)))
+
+
+def wq_decode_append_attention(ctx: Context, q, kv: PackedKV, k_new, v_new, sm_scale: float, num_splits: int = 0,
+                               max_seq_tokens: int = 0, algo: int = DECODE_AUTO, out: Optional[torch.Tensor] = None,
+                               lse: Optional[torch.Tensor] = None):
+    B, Hq, hd = q.shape
+    if out is None:
+        out = torch.empty(B, Hq, hd, dtype=torch.float32, device=ctx.device)
+    ctx.check(lib().wq_decode_append_attention(ctx.handle, _ptr(q), _dtype_id(q), B, Hq, C.byref(kv.desc), _ptr(k_new), _ptr(v_new),
+                                               _dtype_id(k_new), sm_scale, num_splits, max_seq_tokens, algo, _ptr(out), _ptr(lse)))
+    return out
 
 
 def wq_dequantize(ctx: Context, src: PackedKV, dst: PackedKV):

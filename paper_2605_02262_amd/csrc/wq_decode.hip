@@ -33,6 +33,10 @@ struct DecodeArgs {
     float* part;            // [B][Hkv][nparts][rep][hd + 2]
     float* out;
     float* lse;
+    // appending one generated token per sequence in the same launch (matrix-core kernel, merged splits only):
+    const uint16_t* k_new;  // [B][Hkv][hd] in the cache's 16-bit type, or NULL
+    const uint16_t* v_new;
+    uint32_t* status;       // device status word (a full 16-bit segment is reported there)
 #ifdef WQ_TIMELINE
     long long* dbg;
 #endif
@@ -367,8 +371,22 @@ size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
     return wq_align256(sizeof(float) * (size_t)B * Hq * (splits + 32) * (hd + 2));
 }
 
+// Can wq_launch_decode append k_new, v_new (element type new_dtype) itself with these arguments?  Only the matrix-core
+// kernel that walks every segment and merges its splits does: it needs the new rows in the cache's own 16-bit type
+// and one more counter per sequence in the workspace header.
+bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, int num_splits, int algo, int new_dtype)
+{
+    if (algo & WQ_DECODE_PARTIALS_ONLY) return false;
+    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
+    const bool use_mfma = (balgo == WQ_DECODE_MFMA) || (balgo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
+    const bool mfma16 = use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
+    const int rep = Hq / kv->Hkv;
+    return mfma16 && new_dtype == kv->dtype16 && (int64_t)B * kv->Hkv + B <= WQ_MAX_ARRIVE &&
+           2 * num_splits * rep <= WQ_WAVES * WQ_MAX_REP * kv->hd;
+}
+
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
-                     int num_splits, int algo, float* out, float* lse)
+                     int num_splits, int algo, float* out, float* lse, const void* k_new, const void* v_new)
 {
     const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
     const bool fixed_shares = (algo & WQ_DECODE_FIXED_SHARES) != 0;
@@ -405,6 +423,10 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     for (int c = 0; c < 4; c++) a.inv_wgt[c] = 1.0f / a.wgt[c];
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
     a.out = out;
+    a.k_new = static_cast<const uint16_t*>(k_new);
+    a.v_new = static_cast<const uint16_t*>(v_new);
+    a.status = wq_status_ptr(ctx);
+    if (k_new && !a.fused) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "this decode launch cannot append");
 #ifdef WQ_TIMELINE
     a.dbg = getenv("WQ_TIMELINE") ? reinterpret_cast<long long*>(ctx->ws + ctx->ws_bytes - (8 << 20)) : nullptr;
 #endif

@@ -577,8 +577,11 @@ __device__ __forceinline__ floatx4 mfma16(uint32_t a0, uint32_t a1, uint32_t a2,
 // the bf16 instruction with the exact bf16 query and the weights split into two bf16 terms (p = hi + lo);
 // fp16 caches use the f16 instruction.  Accumulators are in true units here (no 2^-24).
 template <int HD, bool BF>
+// new_row >= 0: row new_row (= len - 1) is not in the cache yet: it is read from knew / vnew, this (sequence, KV head)'s
+// [hd] slices of the token that the launch appends.
 __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD>& sm, int b, int kvh, int len, int first_row, BlockSrc& src,
-                                                Tickets& tk, float c_log2, WaveState<HD>& st)
+                                                Tickets& tk, float c_log2, WaveState<HD>& st, int new_row, const uint16_t* knew,
+                                                const uint16_t* vnew)
 {
     constexpr int NK = HD / 32, CT = HD / 16, PITCH = HD / 2 + VT_PAD, KDW = HD / 8;
     if (!has_blocks(src, tk, 1u)) return;
@@ -606,7 +609,8 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
 #pragma unroll
         for (int t = 0; t < 2; t++) {
             const int tok = min(blk * 32 + 16 * t + col, len - 1);      // rows past the end re-read the last row, masked below
-            load_dwords<KDW>(reinterpret_cast<const uint32_t*>(k16 + (row0 + tok) * rstride + j * (HD / 4)), kd[t]);
+            const uint16_t* src_k = tok == new_row ? knew : k16 + (row0 + tok) * rstride;
+            load_dwords<KDW>(reinterpret_cast<const uint32_t*>(src_k + j * (HD / 4)), kd[t]);
         }
         constexpr int VIT = (32 * (HD / 2) * 2) / (16 * 64);          // 16-byte pieces per lane and channel half
         uint4 vd[2][VIT];
@@ -617,7 +621,8 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
                 const int chunk = it * 64 + lane;
                 const int row = chunk / (HD / 16), c16 = chunk % (HD / 16);
                 const int tok = min(blk * 32 + row, len - 1);
-                vd[half][it] = *reinterpret_cast<const uint4*>(v16 + (row0 + tok) * rstride + half * (HD / 2) + c16 * 8);
+                const uint16_t* src_v = tok == new_row ? vnew : v16 + (row0 + tok) * rstride;
+                vd[half][it] = *reinterpret_cast<const uint4*>(src_v + half * (HD / 2) + c16 * 8);
             }
         // ---- logits ----
         float x[8];
@@ -749,6 +754,27 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     cls_len[3] = a.kv.len16[b];
     cls_off[3] = a.kv.off16[b];
+    // a token appended by this launch becomes the last row of the 16-bit segment: read from k_new / v_new by whoever
+    // walks its block, copied into the cache by the first split's workgroup, counted in len16 by the last workgroup of
+    // the sequence to finish (every workgroup of the sequence has read len16 by then)
+    int new_row = -1;
+    const uint16_t *knew = nullptr, *vnew = nullptr;
+    if (a.k_new) {
+        const int64_t row = (int64_t)cls_off[3] + cls_len[3];
+        if (row < a.kv.off16[b + 1] && row < a.kv.cap16) {
+            new_row = cls_len[3];
+            cls_len[3] += 1;
+            knew = a.k_new + ((int64_t)b * a.kv.Hkv + kvh) * HD;
+            vnew = a.v_new + ((int64_t)b * a.kv.Hkv + kvh) * HD;
+            if (split == 0 && tid < 2 * (HD / 8)) {
+                const int plane = tid / (HD / 8), piece = tid % (HD / 8);
+                uint16_t* dst = static_cast<uint16_t*>(plane ? a.kv.v16 : a.kv.k16) + (row * a.kv.Hkv + kvh) * HD + piece * 8;
+                *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>((plane ? vnew : knew) + piece * 8);
+            }
+        } else if (split == 0 && kvh == 0 && tid == 0) {
+            atomicOr(a.status, WQ_DEV_SEG16_OVERFLOW);      // the segment is full: nothing is appended
+        }
+    }
     if (tid == 0) sm.next_ticket = (unsigned)(WQ_FIRST_TICKETS * WQ_WAVES);
     // ---- the query operands of all classes, one class per wavefront ----
     stage_q_operands<HD>(a, sm, b, kvh, wave, bf16seg);
@@ -813,9 +839,9 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
     WQ_WSTAMP(0, wall_clock64());
     if (bf16seg)
-        walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st);
+        walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
     else
-        walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st);
+        walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
     // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
@@ -890,6 +916,15 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     __syncthreads();
     if (!sm.last) return;
     if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    if (a.k_new && tid == 0) {
+        // the last (sequence, KV head) unit of the sequence to get here bumps the sequence's row count
+        unsigned* seq_ctr = a.arrive + (units + b) * WQ_ARRIVE_STRIDE;
+        const unsigned old = __hip_atomic_fetch_add(seq_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == (unsigned)a.kv.Hkv - 1u) {
+            __hip_atomic_store(seq_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (new_row >= 0) a.kv.len16[b] = new_row + 1;
+        }
+    }
     const int np = a.nparts;
     float* wts = &sm.O[0][0][0];                   // [rep][np]: m_s, then the weights e^{m_s - M}
     float* lsum = wts + a.rep * np;                // [rep][np]: l_s

@@ -88,14 +88,24 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert lib.wq_dequantize(h, 1, C.byref(d), C.byref(d2)) == -1 and b"differ" in lib.wq_last_error(h)
         assert lib.wq_dequantize(h, 1, C.byref(d), None) == -1
         assert lib.wq_probe_mfma(h, 1, 0, 10, None) == -1
+        # the one-call decode step: new rows must match the cache's 16-bit type family, no partials-only, same checks as decode
+        app = lambda new_dt, algo=0, Hq=28, kn=one: lib.wq_decode_append_attention(h, one, W.BF16, 1, Hq, C.byref(d), kn, one, new_dt,
+                                                                                  0.1, 0, 100, algo, one, None)
+        assert app(W.F16) == -1 and b"dtype16" in lib.wq_last_error(h)
+        assert app(W.BF16, W.DECODE_PARTIALS_ONLY) == -1
+        assert app(W.BF16, 0, 30) == -2
+        assert app(W.BF16, 0, 28, None) == -1 and b"k_new" in lib.wq_last_error(h)
+        assert app(9) == -1
         # workspace too small
         h2 = C.c_void_p()
         assert lib.wq_create(C.byref(h2), None, fake_ws, 512) == 0
         assert lib.wq_decode_attention(h2, one, W.BF16, 1, 28, C.byref(d), 0.1, 64, 100, 0, one, None) == -4
+        assert lib.wq_decode_append_attention(h2, one, W.BF16, 1, 28, C.byref(d), one, one, W.BF16, 0.1, 64, 100, 0, one, None) == -4
         lib.wq_destroy(h2)
         # empty batch is a no-op
         d.B = 0
         assert lib.wq_decode_attention(h, one, W.BF16, 0, 28, C.byref(d), 0.1, 0, 0, 0, None, None) == 0
+        assert lib.wq_decode_append_attention(h, one, W.BF16, 0, 28, C.byref(d), None, None, W.BF16, 0.1, 0, 0, 0, None, None) == 0
     finally:
         lib.wq_destroy(h)
 

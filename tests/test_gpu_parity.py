@@ -279,9 +279,102 @@ def test_append_generated_tokens_then_decode():
     assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
 
 
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16])
+def test_decode_step_in_one_call_equals_append_then_decode(dtype):
+    """Sec. 2.2: a decode step appends the generated token and attends over the grown cache.  The one-call form must
+    leave the same rows and row counts in the cache and give, with fixed shares, bit for bit the same attention as
+    wq_append_kv followed by wq_decode_attention; both are also held to the oracle.  The last step finds one segment
+    full: that sequence is attended without the new token and the flag is raised."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(6, 21, 21, 9, (1, 3, 2)), synth.SeqSpec(4, 16, 16, 30, (1, 2, 1)), synth.SeqSpec(5, 32, 20, 3, (1, 1, 3))]
+    bt = _custom(33, 128, 64, 2, 7, dtype, specs)
+    w = bt.w
+    cap, off16 = H.capacities(w, slack=4)
+    off16 = np.array(off16).copy()
+    off16[2:] += 1                                              # one more row for sequence 1: sequence 0 and 2 fill up first
+    g = H.run_gpu(bt, cap=cap, off16=off16, splits=3)
+    o = H.run_oracle(bt, scores_override=g.scores.cpu().numpy(), cap=cap, off16=off16)
+    H.assert_packed_equal(g, o)
+    rnd = synth.round_bf16 if dtype == synth.BF16 else synth.round_f16
+    rng = np.random.default_rng(10)
+    sm = 1.0 / float(np.sqrt(w.hd))
+    algo = W.DECODE_AUTO | W.DECODE_FIXED_SHARES
+    for step in range(4):
+        kn = rnd(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        vn = rnd(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        qn = rnd(rng.standard_normal((w.B, w.Hq, w.hd)).astype(np.float32))
+        kd, vd, qd = H.to_dev(kn, w.dtype), H.to_dev(vn, w.dtype), H.to_dev(qn, w.dtype)
+        saved = g.pk.k16.clone(), g.pk.v16.clone(), g.pk.len16.clone()
+        W.wq_append_kv(g.ctx, kd, vd, g.pk)
+        two = W.wq_decode_attention(g.ctx, qd, g.pk, sm, 3, 400, algo).clone()
+        torch.cuda.synchronize()
+        want = g.pk.k16.clone(), g.pk.v16.clone(), g.pk.len16.clone()
+        st_two = g.ctx.device_status()
+        for dst, src in zip((g.pk.k16, g.pk.v16, g.pk.len16), saved):
+            dst.copy_(src)
+        lse = torch.empty(w.B, w.Hq, dtype=torch.float32, device="cuda")
+        one = W.wq_decode_append_attention(g.ctx, qd, g.pk, kd, vd, sm, 3, 400, algo, lse=lse)
+        torch.cuda.synchronize()
+        assert g.ctx.device_status() == st_two == (2 if step == 3 else 0)
+        for got, exp in zip((g.pk.k16, g.pk.v16, g.pk.len16), want):
+            assert torch.equal(got, exp)
+        assert torch.equal(one, two)
+        for b in range(w.B):                                   # the same append on the oracle's arrays
+            r = int(o.pk.off16[b] + o.pk.len16[b])
+            if r < off16[b + 1]:
+                o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+                o.pk.len16[b] += 1
+        assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+        ref, ref_lse = O.decode_attention(qn, o.pk, sm, want_lse=True)
+        assert H.attention_error(one.cpu().numpy(), ref) <= H.ATTN_TOL
+        assert np.abs(lse.cpu().numpy() - ref_lse).max() <= 1e-3
+        free = W.wq_decode_append_attention(g.ctx, qd, g.pk, kd, vd, sm, 2, 400) if step == 0 else None    # free shares, other split count
+        if free is not None:
+            torch.cuda.synchronize()
+            for b in range(w.B):
+                r = int(o.pk.off16[b] + o.pk.len16[b])
+                o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+                o.pk.len16[b] += 1
+            assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+            assert H.attention_error(free.cpu().numpy(), O.decode_attention(qn, o.pk, sm)) <= H.ATTN_TOL
+
+
+def test_decode_step_in_one_call_falls_back_to_two_launches():
+    """The generic kernel and a query or new rows of another element type cannot append in the launch: the call then
+    makes the two launches itself, with the same result."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(3, 16, 16, 5, (1, 1, 1)), synth.SeqSpec(4, 8, 8, 12, (1, 2, 1))]
+    bt = _custom(34, 128, 64, 2, 4, synth.F16, specs)
+    w = bt.w
+    cap, off16 = H.capacities(w, slack=4)
+    g = H.run_gpu(bt, cap=cap, off16=off16, splits=2)
+    o = H.run_oracle(bt, scores_override=g.scores.cpu().numpy(), cap=cap, off16=off16)
+    rng = np.random.default_rng(11)
+    sm = 1.0 / float(np.sqrt(w.hd))
+    for step, (algo, new_dt, q_dt) in enumerate([(W.DECODE_GENERIC, synth.F16, synth.F16), (W.DECODE_AUTO, synth.F32, synth.F16),
+                                                 (W.DECODE_AUTO, synth.F16, synth.F32)]):
+        kn = synth.round_f16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        vn = synth.round_f16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        qn = synth.round_f16(rng.standard_normal((w.B, w.Hq, w.hd)).astype(np.float32))
+        out = W.wq_decode_append_attention(g.ctx, H.to_dev(qn, q_dt), g.pk, H.to_dev(kn, new_dt), H.to_dev(vn, new_dt), sm, 2, 400, algo)
+        torch.cuda.synchronize()
+        for b in range(w.B):
+            r = int(o.pk.off16[b] + o.pk.len16[b])
+            o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+            o.pk.len16[b] += 1
+        assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+        assert H.attention_error(out.cpu().numpy(), O.decode_attention(qn, o.pk, sm)) <= H.ATTN_TOL
+    assert g.ctx.device_status() == 0
+
+
 def test_decode_step_in_a_hip_graph_replays_like_eager():
-    """append + decode of two layers captured in one HIP graph: every replay (with eager work and synchronisation in
-    between) gives what the same steps give when launched one by one on an identical second cache."""
+    """A decode step of two layers (the one-call form: one launch per layer, which also resets its arrival counters for
+    the next replay) captured in one HIP graph: every replay (with eager work and synchronisation in between) gives
+    what append and decode give when launched one by one on an identical second cache."""
     H = _h()
     from paper_2605_02262_amd import binding as W
     specs = [synth.SeqSpec(6, 21, 21, 9, (1, 3, 2)), synth.SeqSpec(4, 16, 16, 30, (1, 2, 1))]
@@ -299,6 +392,9 @@ def test_decode_step_in_a_hip_graph_replays_like_eager():
     def step(which):
         for layer in range(2):
             g = runs[which][layer]
+            if which == 1:
+                W.wq_decode_append_attention(g.ctx, qn[layer], g.pk, kn[layer], vn[layer], sm, 2, 400, algo, out=outs[which][layer])
+                continue
             W.wq_append_kv(g.ctx, kn[layer], vn[layer], g.pk)
             W.wq_decode_attention(g.ctx, qn[layer], g.pk, sm, 2, 400, algo, out=outs[which][layer])
 
@@ -319,6 +415,7 @@ def test_decode_step_in_a_hip_graph_replays_like_eager():
         for layer in range(2):
             assert torch.equal(outs[0][layer], outs[1][layer]), f"replay {rep}, layer {layer}"
             assert torch.equal(runs[0][layer].pk.len16, runs[1][layer].pk.len16)
+            assert torch.equal(runs[0][layer].pk.k16, runs[1][layer].pk.k16) and torch.equal(runs[0][layer].pk.v16, runs[1][layer].pk.v16)
         assert float(outs[1][0].abs().max()) > 0
     assert runs[1][0].ctx.device_status() == 0
 
