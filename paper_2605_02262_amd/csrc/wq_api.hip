@@ -272,6 +272,32 @@ int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, i
     return wq_launch_append(ctx, k_new, v_new, dtype, B, kv);
 }
 
+// What both decode entry points check before anything is enqueued; resolves num_splits == 0.
+static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
+                        int* num_splits, int64_t max_seq_tokens, int algo, const float* out)
+{
+    if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
+    if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
+    int rc = check_packed(ctx, kv, B, true);
+    if (rc != WQ_OK) return rc;
+    if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
+                       Hq, kv->Hkv, WQ_MAX_REP);
+    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
+    if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
+        return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
+    if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
+    if (*num_splits < 0 || *num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
+    if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
+    if (B == 0) return WQ_OK;
+    if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
+    if (*num_splits == 0) *num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
+    if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, *num_splits))
+        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for %d splits", *num_splits);
+    return WQ_OK;
+}
+
 int wq_decode_append_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                                const void* k_new, const void* v_new, int new_dtype, float sm_scale, int num_splits,
                                int64_t max_seq_tokens, int algo, float* out, float* lse)
@@ -282,32 +308,12 @@ int wq_decode_append_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, i
         return wq_fail(ctx, WQ_ERR_ARG, "dtype16 must be bf16 for bf16 input and fp16 for fp16/fp32 input");
     if (B > 0 && (!k_new || !v_new)) return wq_fail(ctx, WQ_ERR_ARG, "NULL k_new or v_new");
     if (algo & WQ_DECODE_PARTIALS_ONLY) return wq_fail(ctx, WQ_ERR_ARG, "partials-only launches do not append");
-    // everything wq_decode_attention checks, before anything is enqueued
-    {
-        if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
-        if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
-        int rc = check_packed(ctx, kv, B, true);
-        if (rc != WQ_OK) return rc;
-        if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
-            return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
-                           Hq, kv->Hkv, WQ_MAX_REP);
-        const int balgo = algo & ~WQ_DECODE_FIXED_SHARES;
-        if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
-            return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
-        if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
-            return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
-        if (num_splits < 0 || num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
-        if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
-        if (B == 0) return WQ_OK;
-        if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
-    }
-    if (num_splits == 0) num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
-    if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, num_splits))
-        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for %d splits", num_splits);
+    int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out);
+    if (rc != WQ_OK || B == 0) return rc;
     if (wq_decode_can_append(q_dtype, B, Hq, kv, num_splits, algo, new_dtype))
         return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, k_new, v_new);
     // other kernels, other element types: two launches
-    int rc = wq_launch_append(ctx, k_new, v_new, new_dtype, B, kv);
+    rc = wq_launch_append(ctx, k_new, v_new, new_dtype, B, kv);
     if (rc != WQ_OK) return rc;
     return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse);
 }
@@ -332,25 +338,8 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
 {
     if (!ctx) return WQ_ERR_ARG;
-    if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
-    if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
-    int rc = check_packed(ctx, kv, B, true);
-    if (rc != WQ_OK) return rc;
-    if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
-        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
-                       Hq, kv->Hkv, WQ_MAX_REP);
-    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
-    if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
-        return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
-    if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
-        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel needs hd/group == 2");
-    if (num_splits < 0 || num_splits > 1024) return wq_fail(ctx, WQ_ERR_ARG, "num_splits out of range");
-    if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
-    if (B == 0) return WQ_OK;
-    if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
-    if (num_splits == 0) num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
-    if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, num_splits))
-        return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for %d splits", num_splits);
+    const int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out);
+    if (rc != WQ_OK || B == 0) return rc;
     return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse);
 }
 
