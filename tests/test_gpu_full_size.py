@@ -15,7 +15,7 @@ def _full(bt, **kw):
     g = H.run_gpu(bt, **kw)
     ov = kw.get("scores_override")
     o = H.run_oracle(bt, scores_override=ov if ov is not None else g.scores.cpu().numpy(),
-                     with_scores=kw.get("with_scores", True))
+                     with_scores=kw.get("with_scores", True), cap=kw.get("cap"), off16=kw.get("off16"))
     if g.scores is not None:
         H.assert_scores_close(g.scores, o.scores)
     assert np.array_equal(g.bits.cpu().numpy(), o.bits)
@@ -77,6 +77,35 @@ def test_7b_batch8_sampled_layers(layer):
     bt = synth.batch(w, layer=layer, with_embeddings=(layer == 0))
     _full(bt, with_scores=(layer == 0), scores_override=None if layer == 0 else
           np.random.default_rng(layer).standard_normal(int(bt.t.win_off[-1])).astype(np.float32))
+
+
+def test_7b_batch8_decode_steps_in_one_call():
+    """The decode loop's step at full size, as bench.py --decode-loop launches it (automatic split count, one launch that
+    appends the generated token and attends): two steps on layer 13's cache, each against the oracle over the grown cache."""
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    from tests import wq_harness as H
+    w = synth.workload(2)
+    bt = synth.batch(w, layer=13, with_embeddings=False)
+    cap, off16 = H.capacities(w, slack=2)
+    g, o = _full(bt, with_scores=False, cap=cap, off16=off16,
+                 scores_override=np.random.default_rng(13).standard_normal(int(bt.t.win_off[-1])).astype(np.float32))
+    rng = np.random.default_rng(14)
+    sm = 1.0 / float(np.sqrt(w.hd))
+    max_tok = int(np.diff(bt.t.kv_off).max()) + 2
+    for step in range(2):
+        kn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        vn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        qn = synth.round_bf16(bt.q * (1.0 + 0.1 * rng.standard_normal(bt.q.shape).astype(np.float32)))
+        out = W.wq_decode_append_attention(g.ctx, H.to_dev(qn, w.dtype), g.pk, H.to_dev(kn, w.dtype), H.to_dev(vn, w.dtype), sm, 0, max_tok)
+        for b in range(w.B):
+            r = int(o.pk.off16[b] + o.pk.len16[b])
+            o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+            o.pk.len16[b] += 1
+        assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16)
+        err = H.attention_error(out.cpu().numpy(), O.decode_attention(qn, o.pk, sm))
+        assert err <= H.ATTN_TOL, f"step {step}: attention error {err:.3e}"
+    assert g.ctx.device_status() == 0
 
 
 def test_ragged_batch32():
