@@ -726,8 +726,7 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
 // first block of a class (n blocks of cost w each, starting at cost `base`) at or after cost x
 __device__ __forceinline__ int range_edge(float x, float base, float inv_w, int n)
 {
-    const float v = ceilf((x - base) * inv_w);
-    return v <= 0.f ? 0 : (v >= (float)n ? n : (int)v);
+    return (int)fminf(fmaxf(ceilf((x - base) * inv_w), 0.f), (float)n);      // no branches: every wavefront runs this before its first load
 }
 
 template <int HD>
@@ -799,25 +798,32 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #pragma unroll
         for (int c = 0; c < 4; c++) total += (float)nb[c] * a.wgt[c];
         const int S = a.splits;
-        const float rS = 1.0f / (float)S, rnw = 1.0f / (float)WQ_WAVES;
-        const float G0 = total * ((float)split * rS), G1 = total * ((float)(split + 1) * rS);     // the workgroup's range
-        const float Gs = a.fixed_shares ? G1 : G0;                                                // [Gs, G1) is its pool
-        const float x0 = G0 + (Gs - G0) * ((float)wave * rnw), x1 = G0 + (Gs - G0) * ((float)(wave + 1) * rnw);
+        const float rS = 1.0f / (float)S;
+        // the workgroup's range [G0, G1): the first one starts at cost 0 (every class's edge is then block 0), the last one
+        // ends behind everything, whatever the rounding
+        const float G0 = total * ((float)split * rS), G1 = split == S - 1 ? 3.0e38f : total * ((float)(split + 1) * rS);
         float base = 0.f;
         unsigned t = 0;
 #pragma unroll
         for (int c = 3; c >= 0; c--) {
             const float iw = a.inv_wgt[c];
-            const int e0 = split == 0 ? 0 : range_edge(G0, base, iw, nb[c]);
-            const int e1 = split == S - 1 ? nb[c] : range_edge(G1, base, iw, nb[c]);
-            const int pl = a.fixed_shares ? e1 : e0;
-            src[c].cur = wave == 0 ? e0 : range_edge(x0, base, iw, nb[c]);
-            src[c].end = wave == WQ_WAVES - 1 ? pl : range_edge(x1, base, iw, nb[c]);
-            if (!a.fixed_shares) src[c].cur = src[c].end = 0;
-            src[c].pool_first = pl;
-            src[c].tk_lo = t;
-            t += (unsigned)(e1 - pl);
-            src[c].tk_hi = t;
+            const int e0 = range_edge(G0, base, iw, nb[c]);
+            const int e1 = range_edge(G1, base, iw, nb[c]);
+            if (a.fixed_shares) {                  // the range is divided among the wavefronts by cost; no pool
+                const float rnw = 1.0f / (float)WQ_WAVES;
+                const float Ge = split == S - 1 ? total : G1;
+                const float x0 = G0 + (Ge - G0) * ((float)wave * rnw), x1 = G0 + (Ge - G0) * ((float)(wave + 1) * rnw);
+                src[c].cur = wave == 0 ? e0 : range_edge(x0, base, iw, nb[c]);
+                src[c].end = wave == WQ_WAVES - 1 ? e1 : range_edge(x1, base, iw, nb[c]);
+                src[c].pool_first = e1;
+                src[c].tk_lo = src[c].tk_hi = t;
+            } else {                               // the whole range is the pool
+                src[c].cur = src[c].end = 0;
+                src[c].pool_first = e0;
+                src[c].tk_lo = t;
+                t += (unsigned)(e1 - e0);
+                src[c].tk_hi = t;
+            }
             base += (float)nb[c] * a.wgt[c];
         }
     }
