@@ -277,6 +277,7 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
                         int* num_splits, int64_t max_seq_tokens, int algo, const float* out)
 {
     if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
+    if (B > 65535) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "more than 65535 sequences in one call");      // a grid dimension
     if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
     int rc = check_packed(ctx, kv, B, true);
     if (rc != WQ_OK) return rc;

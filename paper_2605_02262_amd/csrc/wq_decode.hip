@@ -434,7 +434,7 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     const dim3 blk(256);
     const dim3 grid_q(a.splits, kv->Hkv, B), grid_16(a.splits16 > 0 ? a.splits16 : 1, kv->Hkv, B);
     // the matrix-core kernel maps workgroups (of WQ_WAVES wavefronts) to units itself
-    const dim3 grid_m((unsigned)a.splits * (unsigned)kv->Hkv * (unsigned)B), blk_m(64 * WQ_WAVES);
+    const dim3 grid_m((unsigned)kv->Hkv, (unsigned)B, (unsigned)a.splits), blk_m(64 * WQ_WAVES);
     const int tslot = (int)(ctx->ev_calls % WQ_TIMING_RING);
     if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * tslot], ctx->stream);
     if (kv->hd == 128) {

@@ -28,8 +28,9 @@
 #pragma once
 
 #ifdef WQ_TIMELINE   // development aid: per-workgroup phase time stamps (100 MHz clock) at the end of the workspace
-#define WQ_STAMP(k) do { if (a.dbg && threadIdx.x == 0) a.dbg[(int64_t)blockIdx.x * 64 + (k)] = wall_clock64(); } while (0)
-#define WQ_WSTAMP(k, val) do { if (a.dbg && (threadIdx.x & 63) == 0) a.dbg[(int64_t)blockIdx.x * 64 + 8 + (threadIdx.x >> 6) * 6 + (k)] = (val); } while (0)
+#define WQ_WG ((int64_t)(blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x)
+#define WQ_STAMP(k) do { if (a.dbg && threadIdx.x == 0) a.dbg[WQ_WG * 64 + (k)] = wall_clock64(); } while (0)
+#define WQ_WSTAMP(k, val) do { if (a.dbg && (threadIdx.x & 63) == 0) a.dbg[WQ_WG * 64 + 8 + (threadIdx.x >> 6) * 6 + (k)] = (val); } while (0)
 #else
 #define WQ_STAMP(k) do { } while (0)
 #define WQ_WSTAMP(k, val) do { } while (0)
@@ -735,9 +736,10 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     MfmaSmem<HD>& sm = *reinterpret_cast<MfmaSmem<HD>*>(smem_raw);
     // consecutive workgroups go to different (sequence, KV head) units: the units' tables and queries are then
     // read by all XCDs alike, and the workgroups of one unit do not start in a burst on neighbouring compute units
+    // (the grid is (KV heads, sequences, splits): workgroups are dispatched with x fastest, and nothing here has to divide)
     const int units = a.B * a.kv.Hkv;
-    const int unit = (int)(blockIdx.x % (unsigned)units), split = (int)(blockIdx.x / (unsigned)units);
-    const int kvh = unit % a.kv.Hkv, b = unit / a.kv.Hkv;
+    const int kvh = (int)blockIdx.x, b = (int)blockIdx.y, split = (int)blockIdx.z;
+    const int unit = b * a.kv.Hkv + kvh;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int j = lane >> 4, col = lane & 15, g = col >> 3, h = col & 7;
     constexpr int CT = HD / 16;
@@ -831,8 +833,8 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     WQ_STAMP(1);
 #ifdef WQ_TIMELINE
     if (a.dbg && threadIdx.x == 0) {
-        a.dbg[(int64_t)blockIdx.x * 64 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
-        a.dbg[(int64_t)blockIdx.x * 64 + 7] = -(long long)__builtin_readcyclecounter();
+        a.dbg[WQ_WG * 64 + 6] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
+        a.dbg[WQ_WG * 64 + 7] = -(long long)__builtin_readcyclecounter();
     }
 #endif
 
@@ -861,7 +863,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 
     WQ_STAMP(4);
 #ifdef WQ_TIMELINE
-    if (a.dbg && threadIdx.x == 0) a.dbg[(int64_t)blockIdx.x * 64 + 7] += (long long)__builtin_readcyclecounter();
+    if (a.dbg && threadIdx.x == 0) a.dbg[WQ_WG * 64 + 7] += (long long)__builtin_readcyclecounter();
 #endif
     // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
     float l = st.l, am = st.accM;
