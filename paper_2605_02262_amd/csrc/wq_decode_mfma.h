@@ -846,13 +846,15 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     st.accM = 0.f;
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
     WQ_WSTAMP(0, wall_clock64());
-    if (bf16seg)
-        walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
-    else
-        walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
-    // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
+    if (has_blocks(src[3], tk, 1u)) {              // (most wavefronts have no block of the 16-bit segment and go straight on)
+        if (bf16seg)
+            walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
+        else
+            walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
+        // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
 #pragma unroll
-    for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
+        for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
+    }
     WQ_WSTAMP(1, wall_clock64());
     walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, cls_len[2], cls_off[2], src[2], tk, c_log2, st);
     WQ_WSTAMP(2, wall_clock64());
