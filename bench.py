@@ -227,9 +227,6 @@ def main():
     total_rows = int(t.kv_off[-1])
     max_tok = int(np.diff(t.kv_off).max())
     max_win = int(np.diff(t.win_off).max())
-    nsplit = args.splits or W.auto_splits(B, w.Hkv, max_tok)
-    ctx = W.Context(W.workspace_bytes(B, w.Hq, w.hd, nsplit, total_vis, total_txt, w.D))
-
     cap = [0, 0, 0]
     n16 = []
     for s in w.seqs:
@@ -238,6 +235,10 @@ def main():
             cap[c] += (n * s.win_size + 31) // 32 * 32
         n16.append((n_top if w.top_bits == 16 else 0) * s.win_size + (s.n_vis - s.n_win * s.win_size) + s.n_text + 64)
     off16 = np.concatenate([[0], np.cumsum(n16)]).astype(np.int32)
+    # the decode calls get num_splits = args.splits (0: the library picks, by length where the sequences differ a lot);
+    # nsplit is the count it will pick, for the workspace and the report
+    nsplit = args.splits or W.auto_splits_ragged(B, w.Hkv, max_tok, sum(cap) + int(off16[-1]))
+    ctx = W.Context(W.workspace_bytes(B, w.Hq, w.hd, nsplit, total_vis, total_txt, w.D))
     copies = [W.PackedKV(B, w.Hkv, w.hd, w.group, TD[w.dtype16], cap, off16) for _ in range(N_COPIES)]
     sm_scale = 1.0 / float(np.sqrt(w.hd))
     out = torch.empty(B, w.Hq, w.hd, dtype=torch.float32, device="cuda")
@@ -261,7 +262,7 @@ def main():
         W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
         bits_, perm_, seg_ = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
         W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm_, seg_, total_rows, pk_w)
-        W.wq_decode_attention(ctx, q, pk_r, sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)
+        W.wq_decode_attention(ctx, q, pk_r, sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
@@ -286,7 +287,7 @@ def main():
     # ---- its stages, each over the same number of back-to-back calls (a pair of events per call would add
     #      several microseconds of marker overhead to a 30 us kernel) ---------------------------------------
     n = max(args.steps, 2 * N_COPIES)
-    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, nsplit, max_tok, algo, out=out, lse=lse))
+    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo, out=out, lse=lse))
     for i in range(N_COPIES):
         dec(W.DECODE_AUTO)(i)
     dec_us = timed(dec(W.DECODE_AUTO), n)                                     # the whole call: one kernel
@@ -307,12 +308,12 @@ def main():
     dense = [W.PackedKV(B, w.Hkv, w.hd, w.group, TD[w.dtype16], [0, 0, 0], dense_off) for _ in range(2)]
     for i in range(2):
         W.wq_dequantize(ctx, copies[i], dense[i])
-        W.wq_decode_attention(ctx, q, dense[i], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)
+        W.wq_decode_attention(ctx, q, dense[i], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)
     nd = max(8, n // 4)
     deq_us = timed(lambda i: W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]), nd)
-    att16_us = timed(lambda i: W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse), nd)
+    att16_us = timed(lambda i: W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse), nd)
     unf_us = timed(lambda i: (W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]),
-                              W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out, lse=lse)), nd)
+                              W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)), nd)
     dense_bytes = sum(tot) * w.Hkv * w.hd * 2 * 2
     del dense
     gbs = alg_bytes / (dec_us * 1e-6) / 1e9
@@ -401,7 +402,7 @@ def main():
                 break
         dt1 = (time.perf_counter() - t1) / reps1
         gomp.omp_set_num_threads(nthreads)
-        W.wq_decode_attention(ctx, q, copies[0], sm_scale, nsplit, max_tok, W.DECODE_AUTO, out=out)
+        W.wq_decode_attention(ctx, q, copies[0], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out)
         torch.cuda.synchronize()
         got = out[0].cpu().numpy().astype(np.float64)
         err = float((np.abs(got - ref[0]).max(axis=-1) / np.abs(ref[0]).max(axis=-1)).max())

@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.wq_packed_bytes.argtypes = [i32, i64, i32, i32, i32, C.POINTER(C.c_size_t)]
         L.wq_packed_bytes.restype = C.c_size_t
         L.wq_auto_splits.argtypes = [i32, i32, i64]
+        L.wq_auto_splits_ragged.argtypes = [i32, i32, i64, i64]
         L.wq_window_scores.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.wq_assign_bits.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.wq_layer_thresholds.argtypes = [C.POINTER(C.c_double), i32, C.c_double, C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -97,6 +98,10 @@ def packed_bytes(bits: int, cap_tokens: int, Hkv: int, hd: int, group: int):
 
 def auto_splits(B: int, Hkv: int, max_seq_tokens: int) -> int:
     return int(lib().wq_auto_splits(B, Hkv, max_seq_tokens))
+
+
+def auto_splits_ragged(B: int, Hkv: int, max_seq_tokens: int, total_tokens: int) -> int:
+    return int(lib().wq_auto_splits_ragged(B, Hkv, max_seq_tokens, total_tokens))
 
 
 class Context:

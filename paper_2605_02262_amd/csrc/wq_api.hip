@@ -150,6 +150,25 @@ size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group,
     return (size_t)2 * Hkv * cap * hd * bits / 8;
 }
 
+// total_tokens well below B * max_seq_tokens: the sequences differ in length, and the launch gives a sequence splits in
+// proportion to its length (the longest gets them all): more splits, so that about as many workgroups as for equal
+// lengths have work
+int wq_auto_splits_ragged(int B, int Hkv, int64_t max_seq_tokens, int64_t total_tokens)
+{
+    const int s0 = wq_auto_splits(B, Hkv, max_seq_tokens);
+    if (B <= 0 || max_seq_tokens <= 0 || total_tokens <= 0) return s0;
+    const double fill = (double)total_tokens / ((double)B * (double)max_seq_tokens);
+    if (fill >= 0.75) return s0;
+    // twice the count that would give as many busy workgroups as equal lengths do: with lengths this uneven the launch is as
+    // long as its longest sequences take, and more, smaller workgroups on them end earlier (measured on 32 sequences of
+    // 8 to 128 frames: 84.7 us with 2 splits for all, 77.4 with 4 by length, 72.5 with 8 by length, 82.6 with 12)
+    int64_t s = (int64_t)(2.0 * (double)s0 / fill + 0.5);
+    const int64_t most = (max_seq_tokens + 1023) / 1024;
+    if (s > most) s = most;
+    if (s > 256) s = 256;
+    return s > s0 ? (int)s : s0;
+}
+
 int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens)
 {
     if (B <= 0 || Hkv <= 0) return 1;
@@ -274,8 +293,9 @@ int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, i
 
 // What both decode entry points check before anything is enqueued; resolves num_splits == 0.
 static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
-                        int* num_splits, int64_t max_seq_tokens, int algo, const float* out)
+                        int* num_splits, int64_t max_seq_tokens, int algo, const float* out, int64_t* longest)
 {
+    *longest = 0;
     if (B < 0 || Hq <= 0) return wq_fail(ctx, WQ_ERR_ARG, "bad B or Hq");
     if (B > 65535) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "more than 65535 sequences in one call");      // a grid dimension
     if (!dtype_ok(q_dtype)) return wq_fail(ctx, WQ_ERR_ARG, "unknown q dtype %d", q_dtype);
@@ -293,7 +313,16 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
     if (B == 0) return WQ_OK;
     if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
-    if (*num_splits == 0) *num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
+    if (*num_splits == 0) {
+        *num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
+        // sequences of different lengths (the caches' capacities stand in for the tokens): splits by length, if the
+        // workspace has room for them
+        const int more = wq_auto_splits_ragged(B, kv->Hkv, max_seq_tokens, kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16);
+        if (more > *num_splits && ctx->ws_bytes >= WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, more)) {
+            *num_splits = more;
+            *longest = max_seq_tokens;
+        }
+    }
     if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, *num_splits))
         return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for %d splits", *num_splits);
     return WQ_OK;
@@ -309,14 +338,15 @@ int wq_decode_append_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, i
         return wq_fail(ctx, WQ_ERR_ARG, "dtype16 must be bf16 for bf16 input and fp16 for fp16/fp32 input");
     if (B > 0 && (!k_new || !v_new)) return wq_fail(ctx, WQ_ERR_ARG, "NULL k_new or v_new");
     if (algo & WQ_DECODE_PARTIALS_ONLY) return wq_fail(ctx, WQ_ERR_ARG, "partials-only launches do not append");
-    int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out);
+    int64_t longest = 0;
+    int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out, &longest);
     if (rc != WQ_OK || B == 0) return rc;
     if (wq_decode_can_append(q_dtype, B, Hq, kv, num_splits, algo, new_dtype))
-        return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, k_new, v_new);
+        return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, k_new, v_new, longest);
     // other kernels, other element types: two launches
     rc = wq_launch_append(ctx, k_new, v_new, new_dtype, B, kv);
     if (rc != WQ_OK) return rc;
-    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse);
+    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, nullptr, nullptr, longest);
 }
 
 int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst)
@@ -339,9 +369,10 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
 {
     if (!ctx) return WQ_ERR_ARG;
-    const int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out);
+    int64_t longest = 0;
+    const int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out, &longest);
     if (rc != WQ_OK || B == 0) return rc;
-    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse);
+    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, nullptr, nullptr, longest);
 }
 
 }  // extern "C"

@@ -37,6 +37,7 @@ struct DecodeArgs {
     const uint16_t* k_new;  // [B][Hkv][hd] in the cache's 16-bit type, or NULL
     const uint16_t* v_new;
     uint32_t* status;       // device status word (a full 16-bit segment is reported there)
+    float len_scale;        // > 0: a (sequence, KV head) with n tokens uses ceil(n * len_scale) of the launch's splits (at least one)
 #ifdef WQ_TIMELINE
     long long* dbg;
 #endif
@@ -386,7 +387,8 @@ bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, in
 }
 
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
-                     int num_splits, int algo, float* out, float* lse, const void* k_new, const void* v_new)
+                     int num_splits, int algo, float* out, float* lse, const void* k_new, const void* v_new,
+                     int64_t longest_tokens)
 {
     const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
     const bool fixed_shares = (algo & WQ_DECODE_FIXED_SHARES) != 0;
@@ -427,6 +429,8 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.v_new = static_cast<const uint16_t*>(v_new);
     a.status = wq_status_ptr(ctx);
     if (k_new && !a.fused) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "this decode launch cannot append");
+    // splits by length: only where the kernel merges the splits itself (the separate merge kernel reads every partial)
+    a.len_scale = (a.fused && longest_tokens > 0) ? (float)a.splits / (float)longest_tokens : 0.f;
 #ifdef WQ_TIMELINE
     a.dbg = getenv("WQ_TIMELINE") ? reinterpret_cast<long long*>(ctx->ws + ctx->ws_bytes - (8 << 20)) : nullptr;
 #endif

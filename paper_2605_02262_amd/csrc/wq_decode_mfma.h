@@ -776,6 +776,14 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             atomicOr(a.status, WQ_DEV_SEG16_OVERFLOW);      // the segment is full: nothing is appended
         }
     }
+    // ---- splits of this (sequence, KV head): all of the launch's, or, in a launch for sequences of different lengths,
+    //      as many as the sequence's share of the longest one asks for; the workgroups beyond them have nothing to do ----
+    int S = a.splits;
+    if (a.len_scale > 0.f) {
+        const int tokens = cls_len[0] + cls_len[1] + cls_len[2] + cls_len[3];
+        S = max(1, min(a.splits, (int)ceilf((float)tokens * a.len_scale)));
+        if (split >= S) return;
+    }
     if (tid == 0) sm.next_ticket = (unsigned)(WQ_FIRST_TICKETS * WQ_WAVES);
     // ---- the query operands of all classes, one class per wavefront ----
     stage_q_operands<HD>(a, sm, b, kvh, wave, bf16seg);
@@ -799,7 +807,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         float total = 0.f;
 #pragma unroll
         for (int c = 0; c < 4; c++) total += (float)nb[c] * a.wgt[c];
-        const int S = a.splits;
         const float rS = 1.0f / (float)S;
         // the workgroup's range [G0, G1): the first one starts at cost 0 (every class's edge is then block 0), the last one
         // ends behind everything, whatever the rounding
@@ -921,7 +928,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     __syncthreads();
     if (tid == 0) {
         const unsigned old = __hip_atomic_fetch_add(a.arrive + unit * WQ_ARRIVE_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm.last = old == (unsigned)a.splits - 1u;
+        sm.last = old == (unsigned)S - 1u;
     }
     __syncthreads();
     if (!sm.last) return;
@@ -935,7 +942,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             if (new_row >= 0) a.kv.len16[b] = new_row + 1;
         }
     }
-    const int np = a.nparts;
+    const int np = S;                              // (the splits are all the partials there are in a launch that merges them itself)
     float* wts = &sm.O[0][0][0];                   // [rep][np]: m_s, then the weights e^{m_s - M}
     float* lsum = wts + a.rep * np;                // [rep][np]: l_s
     // all loads first (one round trip): this thread's channels of the first PRE splits, then the (m, l) pairs

@@ -117,7 +117,8 @@ int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int
 int wq_launch_append(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, int B, const wq_packed_kv* kv);
 int wq_launch_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_kv* dst);
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
-                     int num_splits, int algo, float* out, float* lse, const void* k_new = nullptr, const void* v_new = nullptr);
+                     int num_splits, int algo, float* out, float* lse, const void* k_new = nullptr, const void* v_new = nullptr,
+                     int64_t longest_tokens = 0);
 bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, int num_splits, int algo, int new_dtype);
 size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits);
 size_t wq_scores_ws_bytes(int B, int64_t total_vis, int64_t total_txt, int D);

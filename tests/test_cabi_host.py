@@ -39,6 +39,14 @@ def test_pure_size_helpers(lib):
     assert W.workspace_bytes(4, 28, 128, 64) >= 256 + 4 * 28 * 64 * 130 * 4
     assert 1 <= W.auto_splits(4, 4, 50688) <= 256
     assert W.auto_splits(1, 2, 100) == 1
+    # sequences of about equal length: the same count; very different lengths: more splits (used by length), never fewer,
+    # never so many that the longest sequence's splits get under 1024 tokens
+    assert W.auto_splits_ragged(4, 4, 50688, 4 * 50688) == W.auto_splits(4, 4, 50688)
+    assert W.auto_splits_ragged(4, 4, 50688, 3 * 50688 + 1000) == W.auto_splits(4, 4, 50688)
+    assert W.auto_splits_ragged(32, 4, 25344, 32 * 25344 // 2) == 4 * W.auto_splits(32, 4, 25344) == 8
+    assert W.auto_splits_ragged(32, 4, 25344, 32 * 25344 // 100) == 25
+    assert W.auto_splits_ragged(32, 4, 2000, 32 * 200) == W.auto_splits(32, 4, 2000) == 2
+    assert W.auto_splits_ragged(0, 4, 100, 0) == 1 and W.auto_splits_ragged(4, 4, 0, 100) == W.auto_splits(4, 4, 0)
 
 
 def test_argument_errors_are_reported_without_a_gpu(lib):

@@ -548,6 +548,41 @@ def test_random_ragged_workloads(seed):
     assert worst <= H.ATTN_TOL
 
 
+def test_splits_by_length_for_sequences_of_different_lengths():
+    """24 sequences of 64 to 5760 visual tokens: the automatic split count is raised and every sequence uses its share of the
+    splits by length (the workgroups beyond them leave at once).  Parity with the oracle; the same with a workspace that
+    only has room for the plain count (the call falls back to it); fixed shares give the same bits twice."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(77)
+    specs = []
+    for i in range(24):
+        nw = int([1, 2, 3, 5, 8, 90][i % 6] if i < 18 else rng.integers(1, 40))
+        a = int(rng.integers(0, nw + 1))
+        c = int(rng.integers(0, nw - a + 1))
+        specs.append(synth.SeqSpec(nw, 64, 64, int(rng.integers(1, 40)), (a, c, nw - a - c)))
+    bt = _custom(77, 128, 64, 4, 2, synth.BF16, specs, pin=0)
+    w = bt.w
+    cap, off16 = H.capacities(w)
+    max_tok = int(np.diff(bt.t.kv_off).max())
+    total = sum((int(c) + 31) // 32 * 32 for c in cap) + int(off16[-1])
+    plain, more = W.auto_splits(w.B, w.Hkv, max_tok), W.auto_splits_ragged(w.B, w.Hkv, max_tok, total)
+    assert more > plain, (plain, more)
+    g, o, err = _check(bt, H, splits=0)
+    assert err <= H.ATTN_TOL
+    sm = 1.0 / float(np.sqrt(w.hd))
+    q = H.to_dev(bt.q, w.dtype)
+    small = W.Context(W.workspace_bytes(w.B, w.Hq, w.hd, plain))
+    out = W.wq_decode_attention(small, q, g.pk, sm, 0, max_tok)
+    torch.cuda.synchronize()
+    assert H.attention_error(out.cpu().numpy(), o.out) <= H.ATTN_TOL
+    fixed = [W.wq_decode_attention(g.ctx, q, g.pk, sm, 0, max_tok, W.DECODE_AUTO | W.DECODE_FIXED_SHARES).clone() for _ in range(2)]
+    torch.cuda.synchronize()
+    assert torch.equal(fixed[0], fixed[1])
+    assert H.attention_error(fixed[0].cpu().numpy(), o.out) <= H.ATTN_TOL
+    assert g.ctx.device_status() == 0 and small.device_status() == 0
+
+
 def test_random_medium_caches_through_the_matrix_core_decode_kernel():
     """Seeded random caches of a few thousand tokens per sequence (many 32-token blocks per workgroup, 1-16 splits, 1-8 query
     heads per KV head, both block hand-out modes): quantization bit-exact, attention within the tolerance."""

@@ -100,7 +100,13 @@ def run_gpu(bt: synth.Batch, scores_override: Optional[np.ndarray] = None, mode:
     total_vis, total_txt, total_win = int(t.vis_off[-1]), int(t.txt_off[-1]), int(t.win_off[-1])
     total_rows = int(t.kv_off[-1])
     max_tok = int(np.diff(t.kv_off).max()) if B else 0
-    nsplit = splits or W.auto_splits(B, w.Hkv, max_tok)
+    if cap is None or off16 is None:
+        c2, o2 = capacities(w)
+        cap = cap if cap is not None else c2
+        off16 = off16 if off16 is not None else o2
+    # splits = 0: the library picks (more splits, used by length, when the sequences differ a lot in length)
+    padded = sum((int(c) + 31) // 32 * 32 for c in cap) + int(off16[-1])
+    nsplit = splits or W.auto_splits_ragged(B, w.Hkv, max_tok, padded)
     ws = W.workspace_bytes(B, w.Hq, w.hd, max(nsplit, 1), total_vis, total_txt, w.D)
     ctx = W.Context(ws)
     vis_off, txt_off, kv_off = i32(t.vis_off), i32(t.txt_off), i32(t.kv_off)
@@ -114,16 +120,12 @@ def run_gpu(bt: synth.Batch, scores_override: Optional[np.ndarray] = None, mode:
     th = None if thresholds is None else torch.from_numpy(np.asarray(thresholds, np.float32)).cuda()
     max_w = int(np.diff(t.win_off).max()) if B else 0
     bits, perm, seg = W.wq_assign_bits(ctx, use, win_off, max_w, mode, quota, th, w.top_bits, w.pin_first)
-    if cap is None or off16 is None:
-        c2, o2 = capacities(w)
-        cap = cap if cap is not None else c2
-        off16 = off16 if off16 is not None else o2
     pk = W.PackedKV(B, w.Hkv, w.hd, w.group, TORCH_DT[w.dtype16], cap, off16, fill=fill)
     K, V = to_dev(bt.K, w.dtype), to_dev(bt.V, w.dtype)
     W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, pk)
     q = to_dev(bt.q, w.dtype)
     lse = torch.empty(B, w.Hq, dtype=torch.float32, device="cuda")
-    out = W.wq_decode_attention(ctx, q, pk, 1.0 / float(np.sqrt(w.hd)), nsplit, max_tok, algo, lse=lse)
+    out = W.wq_decode_attention(ctx, q, pk, 1.0 / float(np.sqrt(w.hd)), splits, max_tok, algo, lse=lse)
     torch.cuda.synchronize()
     return GpuRun(scores, bits, perm, seg, pk, out, lse, ctx)
 
