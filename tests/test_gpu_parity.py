@@ -549,7 +549,7 @@ def test_random_ragged_workloads(seed):
 
 
 def test_splits_by_length_for_sequences_of_different_lengths():
-    """24 sequences of 64 to 5760 visual tokens: the automatic split count is raised and every sequence uses its share of the
+    """25 sequences of 1 to 5760 tokens and more: the automatic split count is raised and every sequence uses its share of the
     splits by length (the workgroups beyond them leave at once).  Parity with the oracle; the same with a workspace that
     only has room for the plain count (the call falls back to it); fixed shares give the same bits twice."""
     H = _h()
@@ -561,6 +561,7 @@ def test_splits_by_length_for_sequences_of_different_lengths():
         a = int(rng.integers(0, nw + 1))
         c = int(rng.integers(0, nw - a + 1))
         specs.append(synth.SeqSpec(nw, 64, 64, int(rng.integers(1, 40)), (a, c, nw - a - c)))
+    specs.append(synth.SeqSpec(0, 10, 4, 1, (0, 0, 0)))          # and one sequence of a single text token
     bt = _custom(77, 128, 64, 4, 2, synth.BF16, specs, pin=0)
     w = bt.w
     cap, off16 = H.capacities(w)
