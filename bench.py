@@ -235,9 +235,12 @@ def main():
             cap[c] += (n * s.win_size + 31) // 32 * 32
         n16.append((n_top if w.top_bits == 16 else 0) * s.win_size + (s.n_vis - s.n_win * s.win_size) + s.n_text + 64)
     off16 = np.concatenate([[0], np.cumsum(n16)]).astype(np.int32)
-    # the decode calls get num_splits = args.splits (0: the library picks, by length where the sequences differ a lot);
-    # nsplit is the count it will pick, for the workspace and the report
-    nsplit = args.splits or W.auto_splits_ragged(B, w.Hkv, max_tok, sum(cap) + int(off16[-1]))
+    # sequences of very different lengths (workload 4): splits by length, the library's count for them; nsplit is the count
+    # the decode calls end up with, for the workspace and the report
+    plain = W.auto_splits(B, w.Hkv, max_tok)
+    ragged = W.auto_splits_ragged(B, w.Hkv, max_tok, sum(cap) + int(off16[-1]))
+    by_length = W.DECODE_BY_LENGTH if (ragged > plain and not args.splits) else 0
+    nsplit = args.splits or (ragged if by_length else plain)
     ctx = W.Context(W.workspace_bytes(B, w.Hq, w.hd, nsplit, total_vis, total_txt, w.D))
     copies = [W.PackedKV(B, w.Hkv, w.hd, w.group, TD[w.dtype16], cap, off16) for _ in range(N_COPIES)]
     sm_scale = 1.0 / float(np.sqrt(w.hd))
@@ -262,7 +265,7 @@ def main():
         W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
         bits_, perm_, seg_ = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
         W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm_, seg_, total_rows, pk_w)
-        W.wq_decode_attention(ctx, q, pk_r, sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)
+        W.wq_decode_attention(ctx, q, pk_r, sm_scale, args.splits, max_tok, W.DECODE_AUTO | by_length, out=out, lse=lse)
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
@@ -287,7 +290,7 @@ def main():
     # ---- its stages, each over the same number of back-to-back calls (a pair of events per call would add
     #      several microseconds of marker overhead to a 30 us kernel) ---------------------------------------
     n = max(args.steps, 2 * N_COPIES)
-    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo, out=out, lse=lse))
+    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo | by_length, out=out, lse=lse))
     for i in range(N_COPIES):
         dec(W.DECODE_AUTO)(i)
     dec_us = timed(dec(W.DECODE_AUTO), n)                                     # the whole call: one kernel
@@ -308,12 +311,12 @@ def main():
     dense = [W.PackedKV(B, w.Hkv, w.hd, w.group, TD[w.dtype16], [0, 0, 0], dense_off) for _ in range(2)]
     for i in range(2):
         W.wq_dequantize(ctx, copies[i], dense[i])
-        W.wq_decode_attention(ctx, q, dense[i], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)
+        W.wq_decode_attention(ctx, q, dense[i], sm_scale, args.splits, max_tok, W.DECODE_AUTO | by_length, out=out, lse=lse)
     nd = max(8, n // 4)
     deq_us = timed(lambda i: W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]), nd)
-    att16_us = timed(lambda i: W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse), nd)
+    att16_us = timed(lambda i: W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO | by_length, out=out, lse=lse), nd)
     unf_us = timed(lambda i: (W.wq_dequantize(ctx, copies[i % N_COPIES], dense[i % 2]),
-                              W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out, lse=lse)), nd)
+                              W.wq_decode_attention(ctx, q, dense[i % 2], sm_scale, args.splits, max_tok, W.DECODE_AUTO | by_length, out=out, lse=lse)), nd)
     dense_bytes = sum(tot) * w.Hkv * w.hd * 2 * 2
     del dense
     gbs = alg_bytes / (dec_us * 1e-6) / 1e9
@@ -342,7 +345,7 @@ def main():
         "config": {"workload": w.name, "B": B, "Hq": w.Hq, "Hkv": w.Hkv, "head_dim": w.hd, "group": w.group,
                    "visual_tokens_per_seq": w.seqs[0].n_vis, "text_tokens_per_seq": w.seqs[0].n_text,
                    "window": w.seqs[0].win_size, "bit_mix_windows_8_4_2": list(map(int, w.seqs[0].quota)),
-                   "splits": nsplit, "kv_copies_rotated": N_COPIES, "calls_per_stage_timing": n},
+                   "splits": nsplit, "splits_by_length": bool(by_length), "kv_copies_rotated": N_COPIES, "calls_per_stage_timing": n},
         "decode_us_per_step": round(dec_us, 2),
         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
         "stage_us": {"window_scores": round(float(st_mean[0]), 1), "assign_bits": round(float(st_mean[1]), 1),
@@ -402,7 +405,7 @@ def main():
                 break
         dt1 = (time.perf_counter() - t1) / reps1
         gomp.omp_set_num_threads(nthreads)
-        W.wq_decode_attention(ctx, q, copies[0], sm_scale, args.splits, max_tok, W.DECODE_AUTO, out=out)
+        W.wq_decode_attention(ctx, q, copies[0], sm_scale, args.splits, max_tok, W.DECODE_AUTO | by_length, out=out)
         torch.cuda.synchronize()
         got = out[0].cpu().numpy().astype(np.float64)
         err = float((np.abs(got - ref[0]).max(axis=-1) / np.abs(ref[0]).max(axis=-1)).max())

@@ -82,6 +82,12 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
  * workgroup take the blocks of the workgroup's share one by one as they get free (faster; results agree to
  * rounding).                                                                                                   */
 #define WQ_DECODE_FIXED_SHARES 0x200
+/* or-ed into algo, for batches whose sequences differ a lot in length: a sequence uses ceil(num_splits * tokens /
+ * max_seq_tokens) of the launch's splits (at least one; the workgroups beyond them return at once), and num_splits = 0 picks
+ * wq_auto_splits_ragged instead of wq_auto_splits.  Needs max_seq_tokens > 0: the length of the longest sequence (a value
+ * below it only makes more sequences use all splits).  Has an effect only where the matrix-core kernel merges its splits
+ * itself (the launches that can also append); elsewhere every sequence uses all splits.                              */
+#define WQ_DECODE_BY_LENGTH 0x400
 
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
@@ -109,11 +115,11 @@ size_t wq_workspace_bytes(int B, int Hq, int hd, int max_splits, int64_t total_v
 size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group, size_t* meta_bytes);
 /* Host-only, pure.  Split count wq_decode_attention picks for num_splits = 0 when the sequences are about equally long. */
 int wq_auto_splits(int B, int Hkv, int64_t max_seq_tokens);
-/* Host-only, pure.  ... and when they are not: total_tokens (all sequences together; the decode calls take the sum of the
- * cache's capacities for it) below 3/4 of B * max_seq_tokens gives more splits, of which a sequence then uses its share by
- * length (the longest all of them, a short one perhaps one): about twice as many workgroups have work as for equal lengths.
- * Never less than wq_auto_splits; a workspace sized for this count lets the decode calls use it, one sized for
- * wq_auto_splits makes them fall back to that count.                                                               */
+/* Host-only, pure.  ... and what it picks under WQ_DECODE_BY_LENGTH: total_tokens (all sequences together; the decode calls
+ * take the sum of the cache's capacities for it) below 3/4 of B * max_seq_tokens gives more splits, of which a sequence
+ * then uses its share by length: about twice as many workgroups have work as for equal lengths.  Never less than
+ * wq_auto_splits; a workspace sized for this count lets the decode calls use it, one sized for wq_auto_splits makes them
+ * fall back to that count.                                                                                          */
 int wq_auto_splits_ragged(int B, int Hkv, int64_t max_seq_tokens, int64_t total_tokens);
 
 /* ---- a1: window scores (Sec. 3.2.1) ----------------------------------------------------------------------
@@ -229,9 +235,9 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
  * and merged by log-sum-exp in a fixed order (no float atomics).  Which wavefront sums which tokens is fixed
  * only under WQ_DECODE_FIXED_SHARES.
  * q [B,Hq,hd] device, element type q_dtype; out [B,Hq,hd] device fp32; lse [B,Hq] device fp32 or NULL
- * (natural-log sum of exp of the scaled logits).  num_splits 0 = automatic (wq_auto_splits, or wq_auto_splits_ragged
- * with splits by length, see there).  max_seq_tokens: host bound on tokens of any one sequence (used only by the
- * automatic split: a bound that is too small costs speed, not correctness).  algo: WQ_DECODE_AUTO picks the
+ * (natural-log sum of exp of the scaled logits).  num_splits 0 = automatic (wq_auto_splits).  max_seq_tokens: host
+ * bound on tokens of any one sequence (used by the automatic split and by WQ_DECODE_BY_LENGTH; a wrong value costs speed,
+ * not correctness).  algo: WQ_DECODE_AUTO picks the
  * matrix-core kernel when hd/group == 2, else the generic one.                                               */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);

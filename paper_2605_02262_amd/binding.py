@@ -18,6 +18,7 @@ MODE_QUOTA, MODE_THRESHOLD = 0, 1
 DECODE_AUTO, DECODE_GENERIC, DECODE_MFMA = 0, 1, 2
 DECODE_PARTIALS_ONLY = 0x100
 DECODE_FIXED_SHARES = 0x200
+DECODE_BY_LENGTH = 0x400
 CLASS_BITS = (2, 4, 8)
 DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW = 1, 2
 

@@ -304,7 +304,9 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
                        Hq, kv->Hkv, WQ_MAX_REP);
-    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
+    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
+    const bool by_length = (algo & WQ_DECODE_BY_LENGTH) != 0;
+    if (by_length && max_seq_tokens <= 0) return wq_fail(ctx, WQ_ERR_ARG, "WQ_DECODE_BY_LENGTH needs max_seq_tokens");
     if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)
         return wq_fail(ctx, WQ_ERR_ARG, "unknown decode algorithm %d", algo);
     if (balgo == WQ_DECODE_MFMA && kv->hd / kv->group != 2)
@@ -313,14 +315,12 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (!(sm_scale > 0.0f) || sm_scale > 3.0e38f) return wq_fail(ctx, WQ_ERR_ARG, "sm_scale must be positive and finite");
     if (B == 0) return WQ_OK;
     if (!q || !out) return wq_fail(ctx, WQ_ERR_ARG, "NULL q or out");
+    if (by_length) *longest = max_seq_tokens;
     if (*num_splits == 0) {
         *num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
-        // sequences of different lengths (the caches' capacities stand in for the tokens): splits by length, if the
-        // workspace has room for them
-        const int more = wq_auto_splits_ragged(B, kv->Hkv, max_seq_tokens, kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16);
-        if (more > *num_splits && ctx->ws_bytes >= WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, more)) {
-            *num_splits = more;
-            *longest = max_seq_tokens;
+        if (by_length) {    // more splits (the caches' capacities stand in for the tokens), if the workspace has room for them
+            const int more = wq_auto_splits_ragged(B, kv->Hkv, max_seq_tokens, kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16);
+            if (more > *num_splits && ctx->ws_bytes >= WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, more)) *num_splits = more;
         }
     }
     if (ctx->ws_bytes < WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, *num_splits))

@@ -378,7 +378,7 @@ size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
 bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, int num_splits, int algo, int new_dtype)
 {
     if (algo & WQ_DECODE_PARTIALS_ONLY) return false;
-    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
+    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
     const bool use_mfma = (balgo == WQ_DECODE_MFMA) || (balgo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
     const bool mfma16 = use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
     const int rep = Hq / kv->Hkv;
@@ -392,7 +392,7 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
 {
     const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
     const bool fixed_shares = (algo & WQ_DECODE_FIXED_SHARES) != 0;
-    algo &= ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES);
+    algo &= ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
     DecodeArgs a;
     a.q = q;
     a.q_dtype = q_dtype;

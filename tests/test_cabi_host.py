@@ -104,6 +104,9 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
         assert app(W.BF16, 0, 30) == -2
         assert app(W.BF16, 0, 28, None) == -1 and b"k_new" in lib.wq_last_error(h)
         assert app(9) == -1
+        # splits by length need the longest sequence's length
+        assert lib.wq_decode_attention(h, one, W.BF16, 1, 28, C.byref(d), 0.1, 0, 0, W.DECODE_BY_LENGTH, one, None) == -1
+        assert b"max_seq_tokens" in lib.wq_last_error(h)
         # workspace too small
         h2 = C.c_void_p()
         assert lib.wq_create(C.byref(h2), None, fake_ws, 512) == 0

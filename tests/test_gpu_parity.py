@@ -569,18 +569,23 @@ def test_splits_by_length_for_sequences_of_different_lengths():
     total = sum((int(c) + 31) // 32 * 32 for c in cap) + int(off16[-1])
     plain, more = W.auto_splits(w.B, w.Hkv, max_tok), W.auto_splits_ragged(w.B, w.Hkv, max_tok, total)
     assert more > plain, (plain, more)
-    g, o, err = _check(bt, H, splits=0)
+    by_len = W.DECODE_AUTO | W.DECODE_BY_LENGTH
+    g, o, err = _check(bt, H, splits=0, algo=by_len)
     assert err <= H.ATTN_TOL
     sm = 1.0 / float(np.sqrt(w.hd))
     q = H.to_dev(bt.q, w.dtype)
     small = W.Context(W.workspace_bytes(w.B, w.Hq, w.hd, plain))
-    out = W.wq_decode_attention(small, q, g.pk, sm, 0, max_tok)
+    out = W.wq_decode_attention(small, q, g.pk, sm, 0, max_tok, by_len)
     torch.cuda.synchronize()
     assert H.attention_error(out.cpu().numpy(), o.out) <= H.ATTN_TOL
-    fixed = [W.wq_decode_attention(g.ctx, q, g.pk, sm, 0, max_tok, W.DECODE_AUTO | W.DECODE_FIXED_SHARES).clone() for _ in range(2)]
+    fixed = [W.wq_decode_attention(g.ctx, q, g.pk, sm, 0, max_tok, by_len | W.DECODE_FIXED_SHARES).clone() for _ in range(2)]
     torch.cuda.synchronize()
     assert torch.equal(fixed[0], fixed[1])
     assert H.attention_error(fixed[0].cpu().numpy(), o.out) <= H.ATTN_TOL
+    for splits, longest in ((5, max_tok), (more, max_tok // 3), (more, 4 * max_tok)):      # a given count; wrong lengths of the longest
+        out = W.wq_decode_attention(g.ctx, q, g.pk, sm, splits, longest, by_len)
+        torch.cuda.synchronize()
+        assert H.attention_error(out.cpu().numpy(), o.out) <= H.ATTN_TOL
     assert g.ctx.device_status() == 0 and small.device_status() == 0
 
 

@@ -104,7 +104,7 @@ def run_gpu(bt: synth.Batch, scores_override: Optional[np.ndarray] = None, mode:
         c2, o2 = capacities(w)
         cap = cap if cap is not None else c2
         off16 = off16 if off16 is not None else o2
-    # splits = 0: the library picks (more splits, used by length, when the sequences differ a lot in length)
+    # splits = 0: the library picks (under DECODE_BY_LENGTH more splits, used by length; the workspace has room for them)
     padded = sum((int(c) + 31) // 32 * 32 for c in cap) + int(off16[-1])
     nsplit = splits or W.auto_splits_ragged(B, w.Hkv, max_tok, padded)
     ws = W.workspace_bytes(B, w.Hq, w.hd, max(nsplit, 1), total_vis, total_txt, w.D)
