@@ -965,18 +965,25 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         lsum[idx] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    if (tid < a.rep) {                             // per head: max, then weights, then the denominator (split order)
+    if (wave < a.rep) {                            // head `wave`, a split per lane: max, weights, denominator (a fixed tree of sums)
+        static_assert(WQ_WAVES >= WQ_MAX_REP, "one wavefront per head");
         float M = -INFINITY;
-        for (int s = 0; s < np; s++) M = fmaxf(M, wts[tid * np + s]);
+        for (int s = lane; s < np; s += 64) M = fmaxf(M, wts[wave * np + s]);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
         float L = 0.f;
-        for (int s = 0; s < np; s++) {
-            const float ms = wts[tid * np + s];
+        for (int s = lane; s < np; s += 64) {
+            const float ms = wts[wave * np + s];
             const float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
-            wts[tid * np + s] = w;
-            L = fmaf(lsum[tid * np + s], w, L);
+            wts[wave * np + s] = w;
+            L = fmaf(lsum[wave * np + s], w, L);
         }
-        sm.ml[0][tid][0] = M;
-        sm.ml[0][tid][1] = L;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) L += __shfl_xor(L, o, 64);
+        if (lane == 0) {
+            sm.ml[0][wave][0] = M;
+            sm.ml[0][wave][1] = L;
+        }
     }
     __syncthreads();
 #pragma unroll
