@@ -548,6 +548,56 @@ def test_random_ragged_workloads(seed):
     assert worst <= H.ATTN_TOL
 
 
+def test_random_decode_steps_in_one_call():
+    """Seeded random caches of a few thousand tokens (1-8 sequences, 1-4 KV heads, 1-8 query heads each, both 16-bit types,
+    any split count, with and without splits by length and fixed shares): decode steps in one call until every 16-bit
+    segment is full, each against the oracle over the grown cache; the last step raises the flag and appends nothing."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(21)
+    for it in range(10):
+        hd, g = [(64, 32), (128, 64)][rng.integers(2)]
+        dtype = [synth.BF16, synth.F16][rng.integers(2)]
+        specs = []
+        for _ in range(int(rng.integers(1, 9))):
+            S, nw, nt, tail = int(rng.integers(16, 200)), int(rng.integers(1, 60)), int(rng.integers(0, 300)), int(rng.integers(0, 9))
+            a = int(rng.integers(0, nw + 1))
+            c = int(rng.integers(0, nw - a + 1))
+            specs.append(synth.SeqSpec(nw, S, S, nt, (a, c, nw - a - c), tail=tail))
+        rep, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        w = synth.Workload(f"steps-{it}", dtype, dtype, rep * Hkv, Hkv, hd, g, 64, 1.5, specs, 2100 + it, top_bits=8, pin_first=0)
+        bt = synth.batch(w, with_embeddings=False)
+        sc = rng.standard_normal(int(bt.t.win_off[-1])).astype(np.float32)
+        slack = int(rng.integers(1, 4))
+        cap, off16 = H.capacities(w, slack=slack)
+        splits = int(rng.integers(0, 13))
+        algo = W.DECODE_AUTO | (W.DECODE_BY_LENGTH if rng.integers(2) else 0) | (W.DECODE_FIXED_SHARES if rng.integers(3) == 0 else 0)
+        g_run = H.run_gpu(bt, splits=splits, algo=algo, with_scores=False, scores_override=sc, cap=cap, off16=off16)
+        o = H.run_oracle(bt, scores_override=sc, with_scores=False, cap=cap, off16=off16)
+        H.assert_packed_equal(g_run, o)
+        assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL
+        rnd = synth.round_bf16 if dtype == synth.BF16 else synth.round_f16
+        sm = 1.0 / float(np.sqrt(hd))
+        max_tok = int(np.diff(bt.t.kv_off).max()) + slack + 1
+        for step in range(slack + 1):
+            kn = rnd(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+            vn = rnd(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+            qn = rnd(bt.q * (1.0 + 0.2 * rng.standard_normal(bt.q.shape).astype(np.float32)))
+            out = W.wq_decode_append_attention(g_run.ctx, H.to_dev(qn, w.dtype), g_run.pk, H.to_dev(kn, w.dtype), H.to_dev(vn, w.dtype),
+                                               sm, splits, max_tok, algo)
+            torch.cuda.synchronize()
+            assert g_run.ctx.device_status() == (2 if step == slack else 0), (it, step)
+            if step < slack:
+                for b in range(w.B):
+                    r = int(o.pk.off16[b] + o.pk.len16[b])
+                    o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+                    o.pk.len16[b] += 1
+            assert np.array_equal(g_run.pk.len16.cpu().numpy(), o.pk.len16), (it, step)
+            err = H.attention_error(out.cpu().numpy(), O.decode_attention(qn, o.pk, sm))
+            assert err <= H.ATTN_TOL, (it, step, err)
+
+
 def test_splits_by_length_for_sequences_of_different_lengths():
     """25 sequences of 1 to 5760 tokens and more: the automatic split count is raised and every sequence uses its share of the
     splits by length (the workgroups beyond them leave at once).  Parity with the oracle; the same with a workspace that
