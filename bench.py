@@ -327,6 +327,11 @@ def main():
     big.zero_()
     W.wq_probe_stream(ctx, big)
     read_gbs = big.numel() / (timed(lambda i: W.wq_probe_stream(ctx, big), 5) * 1e-6) / 1e9
+    # ... and how long a plain read of just this job's bytes takes (slices of the big buffer in turn, so each one is cold):
+    # launch, first round trips and the last blocks weigh more at 100 MB than at 2 GiB
+    job = (alg_bytes + 4095) // 4096 * 4096
+    nslice = big.numel() // job
+    same_us = timed(lambda i: W.wq_probe_stream(ctx, big[(i % nslice) * job:(i % nslice + 1) * job]), 40)
     half = big.numel() // 2
     W.wq_probe_stream(ctx, big[:half], big[half:])      # plain copy of 1 GiB: the reference for byte counters
     torch.cuda.synchronize()
@@ -350,7 +355,7 @@ def main():
         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
         "stage_us": {"window_scores": round(float(st_mean[0]), 1), "assign_bits": round(float(st_mean[1]), 1),
                      "reorder_quantize": round(float(st_mean[2]), 1), "decode_attention": round(dec_us, 2)},
-        "stream_read_GBs": round(read_gbs, 0),
+        "stream_read_GBs": round(read_gbs, 0), "plain_read_of_the_same_bytes_us": round(same_us, 2),
         "ablation_operator_fusion": {"fused_decode_us": round(dec_us, 2), "unfused_decode_us": round(unf_us, 2),
                                      "dequantize_to_memory_us": round(deq_us, 2), "attention_16bit_us": round(att16_us, 2),
                                      "bytes_16bit_cache": dense_bytes, "speedup_of_fusion": round(unf_us / dec_us, 2),
