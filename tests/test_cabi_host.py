@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -47,6 +49,26 @@ def test_pure_size_helpers(lib):
     assert W.auto_splits_ragged(32, 4, 25344, 32 * 25344 // 100) == 25
     assert W.auto_splits_ragged(32, 4, 2000, 32 * 200) == W.auto_splits(32, 4, 2000) == 2
     assert W.auto_splits_ragged(0, 4, 100, 0) == 1 and W.auto_splits_ragged(4, 4, 0, 100) == W.auto_splits(4, 4, 0)
+
+
+def test_split_count_helpers_over_random_batches(lib):
+    """Properties that hold for any batch: at least one split and at most 256; never more splits than 1024-token pieces of the
+    longest sequence; the count for sequences of different lengths is never below the plain one, equal to it when the batch
+    is at least three quarters full, and does not shrink when the batch gets emptier."""
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(5)
+    for _ in range(2000):
+        B, Hkv = int(rng.integers(1, 200)), int(rng.integers(1, 9))
+        longest = int(rng.integers(1, 300000))
+        plain = W.auto_splits(B, Hkv, longest)
+        most = (longest + 1023) // 1024
+        assert 1 <= plain <= min(256, most)
+        assert plain == min(most, 256, -(-256 // (B * Hkv)))
+        totals = sorted(int(rng.integers(1, B * longest + 1)) for _ in range(3))
+        counts = [W.auto_splits_ragged(B, Hkv, longest, t) for t in totals]
+        assert all(plain <= c <= min(256, max(most, plain)) for c in counts)
+        assert counts[0] >= counts[1] >= counts[2]
+        assert W.auto_splits_ragged(B, Hkv, longest, (3 * B * longest + 3) // 4) == plain
 
 
 def test_argument_errors_are_reported_without_a_gpu(lib):
