@@ -239,8 +239,8 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
  * bound on tokens of any one sequence (used by the automatic split and by WQ_DECODE_BY_LENGTH; a wrong value costs speed,
  * not correctness).  algo: WQ_DECODE_AUTO picks the
  * matrix-core kernel when hd/group == 2, else the generic one.  Limits (WQ_ERR_UNSUPPORTED beyond them): Hq a
- * multiple of Hkv with at most 8 query heads per KV head, hd 64 or 128, group 32, 64 or 128, B at most 65535,
- * num_splits at most 1024.                                               */
+ * multiple of Hkv with at most 8 query heads per KV head, hd 64 or 128, group 32, 64 or 128, B at most 65535;
+ * num_splits above 1024 is WQ_ERR_ARG.                                                                          */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
 
