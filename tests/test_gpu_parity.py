@@ -548,6 +548,29 @@ def test_random_ragged_workloads(seed):
     assert worst <= H.ATTN_TOL
 
 
+@pytest.mark.parametrize("hd,g", [(128, 64), (64, 32)])
+def test_extreme_split_counts(hd, g):
+    """Split counts from 1 to the largest allowed (1024: most workgroups get no block at all; beyond 585 partials per
+    sequence the separate merge kernel takes over from the in-kernel merge), with and without fixed shares."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(40, 50, 50, 70, (6, 14, 20)), synth.SeqSpec(3, 64, 64, 5, (1, 1, 1))]
+    bt = _custom(55, hd, g, 2, 7, synth.BF16, specs)
+    w = bt.w
+    g_run, o, err = _check(bt, H, splits=1)
+    q = H.to_dev(bt.q, w.dtype)
+    sm = 1.0 / float(np.sqrt(w.hd))
+    big = W.Context(W.workspace_bytes(w.B, w.Hq, w.hd, 1024))
+    for splits in (2, 37, 300, 585, 586, 1024):
+        for algo in (W.DECODE_AUTO, W.DECODE_AUTO | W.DECODE_FIXED_SHARES):
+            lse = torch.empty(w.B, w.Hq, dtype=torch.float32, device="cuda")
+            out = W.wq_decode_attention(big, q, g_run.pk, sm, splits, 2100, algo, lse=lse)
+            torch.cuda.synchronize()
+            assert H.attention_error(out.cpu().numpy(), o.out) <= H.ATTN_TOL, (splits, algo)
+            assert np.abs(lse.cpu().numpy() - o.lse).max() <= 2e-3, (splits, algo)
+    assert big.device_status() == 0
+
+
 def test_random_decode_steps_in_one_call():
     """Seeded random caches of a few thousand tokens (1-8 sequences, 1-4 KV heads, 1-8 query heads each, both 16-bit types,
     any split count, with and without splits by length and fixed shares): decode steps in one call until every 16-bit
