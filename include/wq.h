@@ -88,10 +88,17 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
  * below it only makes more sequences use all splits).  Has an effect only where the matrix-core kernel merges its splits
  * itself (the launches that can also append); elsewhere every sequence uses all splits.                              */
 #define WQ_DECODE_BY_LENGTH 0x400
+/* or-ed into algo: the splits are merged by a second kernel instead of by the decode kernel's last workgroup per
+ * (sequence, KV head) (what the library does by itself when a launch's split count is too large for the in-kernel merge).
+ * Both merges do the same arithmetic in the same order: with WQ_DECODE_FIXED_SHARES their results agree bit for bit.   */
+#define WQ_DECODE_SEPARATE_MERGE 0x800
 
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
 #define WQ_DEV_SEG16_OVERFLOW 2u /* 16-bit rows of a sequence exceeded off16[b+1]-off16[b] or cap16        */
+#define WQ_DEV_APPEND_TIMEOUT 4u /* wq_decode_append_attention: the workgroup that raises len16[b] gave up waiting (4 s) for
+                                  * the sequence's other workgroups to start; len16[b] was raised all the same, the
+                                  * workspace header may hold a stale count and must be zeroed before its next use     */
 
 /* ---- context ----------------------------------------------------------------------------------------------
  * hip_stream   : a hipStream_t (NULL = the default stream); all work of this context is enqueued on it.

@@ -198,8 +198,8 @@ int wq_window_scores(wq_ctx* ctx, const void* vis_emb, const void* txt_emb, int 
     if ((total_vis > 0 && !vis_emb) || (total_txt > 0 && !txt_emb)) return wq_fail(ctx, WQ_ERR_ARG, "NULL embeddings");
     if (algo == WQ_SCORE_PAIRWISE_MFMA && dtype == WQ_F32)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path takes bf16 or fp16 embeddings");
-    if (algo == WQ_SCORE_PAIRWISE_MFMA && D % 8 != 0)
-        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path needs D %% 8 == 0");
+    if (algo == WQ_SCORE_PAIRWISE_MFMA && D % 128 != 0)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core scoring path needs D %% 128 == 0");
     if (ctx->ws_bytes < WQ_WS_HEADER + wq_scores_ws_bytes(B, total_vis, total_txt, D))
         return wq_fail(ctx, WQ_ERR_WORKSPACE, "workspace too small for scoring");
     return wq_launch_scores(ctx, vis_emb, txt_emb, dtype, B, D, vis_off, txt_off, win_size, win_off, total_vis,
@@ -304,7 +304,7 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (Hq % kv->Hkv != 0 || Hq / kv->Hkv > WQ_MAX_REP)
         return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "Hq=%d must be a multiple of Hkv=%d, at most %d query heads per KV head",
                        Hq, kv->Hkv, WQ_MAX_REP);
-    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
+    const int balgo = algo & ~WQ_DECODE_FLAGS;
     const bool by_length = (algo & WQ_DECODE_BY_LENGTH) != 0;
     if (by_length && max_seq_tokens <= 0) return wq_fail(ctx, WQ_ERR_ARG, "WQ_DECODE_BY_LENGTH needs max_seq_tokens");
     if (balgo != WQ_DECODE_AUTO && balgo != WQ_DECODE_GENERIC && balgo != WQ_DECODE_MFMA)

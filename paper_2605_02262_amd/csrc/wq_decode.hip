@@ -43,6 +43,30 @@ struct DecodeArgs {
 #endif
 };
 
+// One wavefront turns the m_s of n splits (in w) into the weights e^{m_s - M} in place and returns M and the sum of l_s
+// times the weights.  The sums are taken in one fixed order (lane i takes the splits i, i + 64, ..., then a butterfly
+// over the lanes).  Both merges (the one inside the matrix-core kernel and k_combine) go through this function and sum
+// the numerators in split order, which is why their results agree bit for bit.
+__device__ __forceinline__ void merge_weights(float* w, const float* l, int n, float& M, float& L)
+{
+    const int lane = threadIdx.x & 63;
+    float mx = -INFINITY;
+    for (int s = lane; s < n; s += 64) mx = fmaxf(mx, w[s]);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float sum = 0.f;
+    for (int s = lane; s < n; s += 64) {
+        const float ms = w[s];
+        const float e = (ms == -INFINITY) ? 0.f : __expf(ms - mx);
+        w[s] = e;
+        sum = fmaf(l[s], e, sum);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    M = mx;
+    L = sum;
+}
+
 __device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
 {
     if (dtype == WQ_F32) return static_cast<const float*>(q)[i];
@@ -302,8 +326,9 @@ __global__ __launch_bounds__(64 * WQ_WAVES) void k_decode_mfma(DecodeArgs a)
 }
 
 // out[b,h,:] = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M},  M = max_s m_s;  lse = M + log(sum).
-// One workgroup per (b, h); the weights e^{m_s - M} are computed once in parallel, the sums run in split order
-// with all loads of a thread independent of each other (no data-dependent control flow around them).
+// One workgroup per (b, h); the weights come from merge_weights (first wavefront), the numerators are summed in split
+// order with all loads of a thread independent of each other (no data-dependent control flow around them): the same
+// arithmetic in the same order as the merge inside the matrix-core kernel.
 __global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part, int Hq, int rep, int nparts, int hd,
                                                  float* __restrict__ out, float* __restrict__ lse)
 {
@@ -317,28 +342,24 @@ __global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part,
     const int64_t stride = (int64_t)rep * (hd + 2);
     const float* base = part + (((int64_t)b * Hkv + kvh) * nparts) * stride + (int64_t)r * (hd + 2);
     constexpr int CHUNK = 32;
-    float pre[CHUNK];                      // this channel's numerators of the first CHUNK splits: in flight while M is found
+    float pre[CHUNK];                      // this channel's numerators of the first CHUNK splits: in flight while the weights are found
 #pragma unroll
     for (int k = 0; k < CHUNK; k++) pre[k] = (k < nparts && tid < hd) ? base[(int64_t)k * stride + tid] : 0.f;
-    float mx = -INFINITY;
     for (int s = tid; s < nparts; s += 128) {
-        const float ms = base[s * stride + hd];
-        s_w[s] = ms;
+        s_w[s] = base[s * stride + hd];
         s_l[s] = base[s * stride + hd + 1];
-        mx = fmaxf(mx, ms);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-    if ((tid & 63) == 0) s_red[tid >> 6] = mx;
-    __syncthreads();
-    const float M = fmaxf(s_red[0], s_red[1]);
-    for (int s = tid; s < nparts; s += 128) {
-        const float ms = s_w[s];
-        s_w[s] = (ms == -INFINITY) ? 0.f : __expf(ms - M);
     }
     __syncthreads();
-    float L = 0.f;
-    for (int s = 0; s < nparts; s++) L = fmaf(s_l[s], s_w[s], L);
+    if (tid < 64) {
+        float M, L;
+        merge_weights(s_w, s_l, nparts, M, L);
+        if (tid == 0) {
+            s_red[0] = M;
+            s_red[1] = L;
+        }
+    }
+    __syncthreads();
+    const float M = s_red[0], L = s_red[1];
     float acc = 0.f;
 #pragma unroll
     for (int k = 0; k < CHUNK; k++) acc = fmaf(pre[k], k < nparts ? s_w[k] : 0.f, acc);
@@ -377,8 +398,8 @@ size_t wq_decode_ws_bytes(int B, int Hq, int hd, int splits)
 // and one more counter per sequence in the workspace header.
 bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, int num_splits, int algo, int new_dtype)
 {
-    if (algo & WQ_DECODE_PARTIALS_ONLY) return false;
-    const int balgo = algo & ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
+    if (algo & (WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_SEPARATE_MERGE)) return false;
+    const int balgo = algo & ~WQ_DECODE_FLAGS;
     const bool use_mfma = (balgo == WQ_DECODE_MFMA) || (balgo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
     const bool mfma16 = use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
     const int rep = Hq / kv->Hkv;
@@ -392,7 +413,8 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
 {
     const bool partials_only = (algo & WQ_DECODE_PARTIALS_ONLY) != 0;
     const bool fixed_shares = (algo & WQ_DECODE_FIXED_SHARES) != 0;
-    algo &= ~(WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH);
+    const bool separate_merge = (algo & WQ_DECODE_SEPARATE_MERGE) != 0;
+    algo &= ~WQ_DECODE_FLAGS;
     DecodeArgs a;
     a.q = q;
     a.q_dtype = q_dtype;
@@ -412,17 +434,12 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.arrive = reinterpret_cast<unsigned*>(ctx->ws + 256);
     // one launch does it all when the matrix-core kernel walks every segment, the counters fit the workspace
     // header and the splits' weights fit the merge buffer in LDS
-    a.fused = a.use_mfma && a.mfma16 && !partials_only && (int64_t)B * kv->Hkv <= WQ_MAX_ARRIVE &&
+    a.fused = a.use_mfma && a.mfma16 && !partials_only && !separate_merge && (int64_t)B * kv->Hkv <= WQ_MAX_ARRIVE &&
               2 * a.nparts * a.rep <= WQ_WAVES * WQ_MAX_REP * kv->hd;
-#ifdef WQ_TUNE
-    if (getenv("WQ_FUSE")) a.fused = a.fused && atoi(getenv("WQ_FUSE"));
-#endif
-    for (int c = 0; c < 4; c++) a.wgt[c] = (float)WQ_BLOCK_COST[c];
-#ifdef WQ_TUNE
-    if (getenv("WQ_WGT")) sscanf(getenv("WQ_WGT"), "%f,%f,%f,%f", &a.wgt[0], &a.wgt[1], &a.wgt[2], &a.wgt[3]);
-    if (getenv("WQ_FIXED")) a.fixed_shares = atoi(getenv("WQ_FIXED"));
-#endif
-    for (int c = 0; c < 4; c++) a.inv_wgt[c] = 1.0f / a.wgt[c];
+    for (int c = 0; c < 4; c++) {
+        a.wgt[c] = (float)WQ_BLOCK_COST[c];
+        a.inv_wgt[c] = 1.0f / a.wgt[c];
+    }
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
     a.out = out;
     a.k_new = static_cast<const uint16_t*>(k_new);

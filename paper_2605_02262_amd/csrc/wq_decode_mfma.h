@@ -721,6 +721,40 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
     }
 }
 
+// ---- a launch that appends a token (k_new != NULL) must not change len16[b] while a workgroup of sequence b may still
+// read it (under WQ_DECODE_BY_LENGTH the split count of a sequence depends on its length).  Every workgroup of the
+// sequence, also one that has nothing to do, counts itself on the sequence's counter once the tables are in its registers
+// (an add that returns nothing: nobody waits for it).  The sequence's last workgroup in dispatch order (highest KV head,
+// highest split; every other one of the sequence was dispatched before it and waits for nobody before it counts itself)
+// waits at its very end until the count is complete, clears the counter for the next launch and writes the new length.
+constexpr long long WQ_APPEND_WAIT_TICKS = 400000000ll;   // 4 s of the 100 MHz clock: far beyond any launch; a wait that long gives up
+
+__device__ __forceinline__ void note_tables_read(const DecodeArgs& a, int b, int len16_read)
+{
+    if (a.k_new && threadIdx.x == 0) {
+        unsigned one = 1u;
+        asm volatile("; the count follows the read of len16 %1" : "+s"(one) : "s"(len16_read));
+        __hip_atomic_fetch_add(a.arrive + (a.B * a.kv.Hkv + b) * WQ_ARRIVE_STRIDE, one, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int kvh, int split, int new_row)
+{
+    if (!a.k_new || threadIdx.x != 0 || kvh != a.kv.Hkv - 1 || split != a.splits - 1) return;
+    unsigned* ctr = a.arrive + (a.B * a.kv.Hkv + b) * WQ_ARRIVE_STRIDE;
+    const unsigned all = (unsigned)a.kv.Hkv * (unsigned)a.splits;
+    const long long t_start = wall_clock64();
+    while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != all) {
+        if (wall_clock64() - t_start > WQ_APPEND_WAIT_TICKS) {
+            atomicOr(a.status, WQ_DEV_APPEND_TIMEOUT);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (new_row >= 0) a.kv.len16[b] = new_row + 1;
+}
+
 // Shares are laid out on a cost axis in float arithmetic: every wavefront evaluates the same expressions for the
 // same boundary, so neighbouring shares meet exactly whatever the rounding, and a division-free float mapping is
 // monotone, which is all that the partition needs.
@@ -737,7 +771,6 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     // consecutive workgroups go to different (sequence, KV head) units: the units' tables and queries are then
     // read by all XCDs alike, and the workgroups of one unit do not start in a burst on neighbouring compute units
     // (the grid is (KV heads, sequences, splits): workgroups are dispatched with x fastest, and nothing here has to divide)
-    const int units = a.B * a.kv.Hkv;
     const int kvh = (int)blockIdx.x, b = (int)blockIdx.y, split = (int)blockIdx.z;
     const int unit = b * a.kv.Hkv + kvh;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -755,9 +788,10 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     cls_len[3] = a.kv.len16[b];
     cls_off[3] = a.kv.off16[b];
+    note_tables_read(a, b, cls_len[3]);
     // a token appended by this launch becomes the last row of the 16-bit segment: read from k_new / v_new by whoever
-    // walks its block, copied into the cache by the first split's workgroup, counted in len16 by the last workgroup of
-    // the sequence to finish (every workgroup of the sequence has read len16 by then)
+    // walks its block, copied into the cache by the first split's workgroup, counted in len16 once every workgroup of
+    // the sequence has read len16 (finish_append)
     int new_row = -1;
     const uint16_t *knew = nullptr, *vnew = nullptr;
     if (a.k_new) {
@@ -776,13 +810,17 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             atomicOr(a.status, WQ_DEV_SEG16_OVERFLOW);      // the segment is full: nothing is appended
         }
     }
+    WQ_WSTAMP(5, wall_clock64() + (long long)((cls_len[0] + cls_len[1] + cls_len[2] + cls_len[3] + cls_off[0] + cls_off[1] + cls_off[2] + cls_off[3]) & 0));   // the tables have arrived
     // ---- splits of this (sequence, KV head): all of the launch's, or, in a launch for sequences of different lengths,
     //      as many as the sequence's share of the longest one asks for; the workgroups beyond them have nothing to do ----
     int S = a.splits;
     if (a.len_scale > 0.f) {
         const int tokens = cls_len[0] + cls_len[1] + cls_len[2] + cls_len[3];
         S = max(1, min(a.splits, (int)ceilf((float)tokens * a.len_scale)));
-        if (split >= S) return;
+        if (split >= S) {
+            finish_append(a, b, kvh, split, new_row);
+            return;
+        }
     }
     if (tid == 0) sm.next_ticket = (unsigned)(WQ_FIRST_TICKETS * WQ_WAVES);
     // ---- the query operands of all classes, one class per wavefront ----
@@ -922,8 +960,12 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     if (!a.fused) return;
 
     // ---- the last workgroup of (b, kvh) to get here merges the partials of all splits, in split order ----
-    // Every thread waits until its part of the partial has reached memory before the workgroup reports in; the
-    // last one reads the others' partials from memory as well.
+    // The partial was stored with device-scope stores, which go through to memory.  Every thread waits here until the
+    // memory system has acknowledged its stores (vmcnt(0): what a workgroup-scope fence does not make the compiler emit);
+    // only after the barrier that follows does one thread report the workgroup in, so a workgroup that finds itself last
+    // reads partials that have arrived, with device-scope loads that do not stop at a cache.  This costs one memory round
+    // trip; a device-scope release fence would add a write-back of the whole L2 (measured: 19 us per call).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {
@@ -931,17 +973,11 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         sm.last = old == (unsigned)S - 1u;
     }
     __syncthreads();
-    if (!sm.last) return;
-    if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-    if (a.k_new && tid == 0) {
-        // the last (sequence, KV head) unit of the sequence to get here bumps the sequence's row count
-        unsigned* seq_ctr = a.arrive + (units + b) * WQ_ARRIVE_STRIDE;
-        const unsigned old = __hip_atomic_fetch_add(seq_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old == (unsigned)a.kv.Hkv - 1u) {
-            __hip_atomic_store(seq_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (new_row >= 0) a.kv.len16[b] = new_row + 1;
-        }
+    if (!sm.last) {
+        finish_append(a, b, kvh, split, new_row);
+        return;
     }
+    if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
     const int np = S;                              // (the splits are all the partials there are in a launch that merges them itself)
     float* wts = &sm.O[0][0][0];                   // [rep][np]: m_s, then the weights e^{m_s - M}
     float* lsum = wts + a.rep * np;                // [rep][np]: l_s
@@ -965,21 +1001,10 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         lsum[idx] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    if (wave < a.rep) {                            // head `wave`, a split per lane: max, weights, denominator (a fixed tree of sums)
+    if (wave < a.rep) {                            // head `wave`: largest m, weights and denominator, the same way as the merge kernel
         static_assert(WQ_WAVES >= WQ_MAX_REP, "one wavefront per head");
-        float M = -INFINITY;
-        for (int s = lane; s < np; s += 64) M = fmaxf(M, wts[wave * np + s]);
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
-        float L = 0.f;
-        for (int s = lane; s < np; s += 64) {
-            const float ms = wts[wave * np + s];
-            const float w = (ms == -INFINITY) ? 0.f : __expf(ms - M);
-            wts[wave * np + s] = w;
-            L = fmaf(lsum[wave * np + s], w, L);
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) L += __shfl_xor(L, o, 64);
+        float M, L;
+        merge_weights(wts + wave * np, lsum + wave * np, np, M, L);
         if (lane == 0) {
             sm.ml[0][wave][0] = M;
             sm.ml[0][wave][1] = L;
@@ -1001,6 +1026,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         a.out[((int64_t)b * a.Hq + hq) * HD + ch] = L > 0.f ? acc / L : 0.f;
         if (a.lse && ch == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? sm.ml[0][r][0] + logf(L) : -INFINITY;
     }
+    finish_append(a, b, kvh, split, new_row);
 }
 
 }  // namespace

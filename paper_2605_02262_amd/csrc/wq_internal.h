@@ -23,6 +23,7 @@ struct wq_ctx {
 constexpr size_t WQ_WS_HEADER = 16384; // zero-initialised: status word (first 256 bytes), then the decode kernel's arrival counters
 constexpr int WQ_ARRIVE_STRIDE = 16;   // 32-bit words between arrival counters (one 64-byte piece each)
 constexpr int WQ_MAX_ARRIVE = (16384 - 256) / (4 * WQ_ARRIVE_STRIDE);
+constexpr int WQ_DECODE_FLAGS = WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH | WQ_DECODE_SEPARATE_MERGE;
 constexpr int WQ_TIMING_RING = 64;
 constexpr int WQ_MAX_REP = 8;          // query heads per KV head
 // wall time of one 32-token block of the 2-, 4-, 8- and 16-bit class in the decode kernel, relative to each other

@@ -693,3 +693,81 @@ def test_random_medium_caches_through_the_matrix_core_decode_kernel():
         H.assert_packed_equal(g_run, o)
         assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL
         assert g_run.ctx.device_status() == 0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("cfg,splits", [(1, 7), (1, 16), (3, 16)])
+def test_both_merges_of_the_splits_agree_bit_for_bit(cfg, splits):
+    """Alg. 2 takes one softmax over all segments; the split over tokens is merged either by the decode kernel's last
+    workgroup per (sequence, KV head) or by the merge kernel.  With fixed shares the partials are the same on every run, and
+    both merges weigh and sum them with the same arithmetic in the same order: every bit of out and lse must agree (the
+    0.5B-shaped layer and a cache of the long-video size)."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    w = synth.workload(cfg)
+    bt = synth.batch(w, with_embeddings=False)
+    sc = np.random.default_rng(5).standard_normal(int(bt.t.win_off[-1])).astype(np.float32)
+    g = H.run_gpu(bt, splits=splits, with_scores=False, scores_override=sc)
+    q = H.to_dev(bt.q, w.dtype)
+    max_tok = int(np.diff(bt.t.kv_off).max())
+    sm = 1.0 / float(np.sqrt(w.hd))
+    res = []
+    for extra in (0, W.DECODE_SEPARATE_MERGE, 0):
+        lse = torch.empty(w.B, w.Hq, dtype=torch.float32, device="cuda")
+        out = W.wq_decode_attention(g.ctx, q, g.pk, sm, splits, max_tok, W.DECODE_AUTO | W.DECODE_FIXED_SHARES | extra, lse=lse)
+        torch.cuda.synchronize()
+        res.append((out.clone(), lse.clone()))
+    assert torch.equal(res[0][0], res[2][0]) and torch.equal(res[0][1], res[2][1]), "fixed shares are not reproducible"
+    assert torch.equal(res[0][0], res[1][0]), "out differs between the in-kernel merge and the merge kernel"
+    assert torch.equal(res[0][1], res[1][1]), "lse differs between the in-kernel merge and the merge kernel"
+    if cfg == 1:
+        o = H.run_oracle(bt, scores_override=sc, with_scores=False)
+        assert H.attention_error(res[1][0].cpu().numpy(), o.out) <= H.ATTN_TOL
+
+
+@pytest.mark.gpu
+def test_decode_steps_by_length_while_the_split_count_of_a_sequence_changes():
+    """Sec. 2.2 (the cache grows by one row per step) under WQ_DECODE_BY_LENGTH with more workgroups than compute units:
+    a sequence uses ceil(splits * tokens / longest) splits, and tokens grows by one per step, so the count of a sequence
+    changes between two steps.  Every workgroup of a launch must see the length the launch started with: the late
+    workgroups of a short sequence start after its early ones have finished.  Lengths are chosen so that sequence 1 goes
+    from 3 to 4 splits at the third step; outputs and len16 are checked against the oracle at every step."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    splits, steps = 24, 6
+    longest = 4800                                  # tokens per split: 200
+    specs = [synth.SeqSpec(23, 196, 196, 4800 - 23 * 196, (3, 8, 12))]                  # 4800 tokens: all 24 splits
+    specs += [synth.SeqSpec(2, 196, 196, 598 - 2 * 196, (1, 1, 0))]                     # 598 tokens: 3 splits until it has 601
+    specs += [synth.SeqSpec(int(n), 196, 196, 100 + 7 * i, (1, int(n) // 2, int(n) - 1 - int(n) // 2)) for i, n in enumerate([4, 9, 14, 19, 3, 8, 12, 20, 6, 11, 16, 5])]
+    w = synth.Workload("by-length-steps", synth.BF16, synth.BF16, 28, 4, 128, 64, 64, 1.5, specs, 7100, top_bits=8, pin_first=0)
+    assert w.B * w.Hkv * splits > 256
+    bt = synth.batch(w, with_embeddings=False)
+    sc = np.random.default_rng(8).standard_normal(int(bt.t.win_off[-1])).astype(np.float32)
+    cap, off16 = H.capacities(w, slack=steps)
+    algo = W.DECODE_AUTO | W.DECODE_BY_LENGTH
+    g = H.run_gpu(bt, splits=splits, algo=algo, with_scores=False, scores_override=sc, cap=cap, off16=off16)
+    o = H.run_oracle(bt, scores_override=sc, with_scores=False, cap=cap, off16=off16)
+    assert H.attention_error(g.out.cpu().numpy(), o.out) <= H.ATTN_TOL
+    sm = 1.0 / float(np.sqrt(w.hd))
+    rng = np.random.default_rng(9)
+    used = lambda n: max(1, min(splits, int(np.ceil(np.float32(n) * (np.float32(splits) / np.float32(longest))))))
+    counts = []
+    for step in range(steps):
+        kn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        vn = synth.round_bf16(rng.standard_normal((w.B, w.Hkv, w.hd)).astype(np.float32))
+        qn = synth.round_bf16(bt.q * (1.0 + 0.2 * rng.standard_normal(bt.q.shape).astype(np.float32)))
+        tokens1 = int(sum(o.pk.cls_len[c][1] for c in range(3)) + o.pk.len16[1]) + 1       # what the launch counts for sequence 1
+        counts.append(used(tokens1))
+        out = W.wq_decode_append_attention(g.ctx, H.to_dev(qn, w.dtype), g.pk, H.to_dev(kn, w.dtype), H.to_dev(vn, w.dtype), sm, splits,
+                                           longest, algo)
+        torch.cuda.synchronize()
+        assert g.ctx.device_status() == 0, step
+        for b in range(w.B):
+            r = int(o.pk.off16[b] + o.pk.len16[b])
+            o.pk.k16[r], o.pk.v16[r] = kn[b], vn[b]
+            o.pk.len16[b] += 1
+        assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16), step
+        err = H.attention_error(out.cpu().numpy(), O.decode_attention(qn, o.pk, sm))
+        assert err <= H.ATTN_TOL, (step, err)
+    assert counts[0] == 3 and counts[-1] == 4, counts      # the change of the split count happened inside the loop
