@@ -251,6 +251,24 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
 
+/* ---- decode attention for callers that cannot allocate -------------------------------------------------------
+ * For code that must not call hipMalloc: kernels enqueued under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, results and limits as wq_decode_attention, without a context and without
+ * a workspace: the split-K partials, the decode kernel's counters and the device status word live in a device array
+ * of WQ_STATIC_SCRATCH_BYTES that is part of the library's code object (one copy per GPU, held until the process
+ * ends).  hip_stream: a hipStream_t (NULL = the default stream) of the current device.  The call allocates nothing
+ * (no hipMalloc, no hipFree, no allocating library routine) and does not synchronise.
+ * A call that needs more than the array holds (wq_workspace_bytes(B, Hq, hd, num_splits, 0, 0, 0) bytes: more sequences,
+ * heads or splits) returns WQ_ERR_WORKSPACE and enqueues nothing; wq_static_last_error() says how much it asked for.
+ * Every call on a GPU shares that GPU's array and the array keeps what the last call left in it: the decode kernel leaves
+ * its counters zero when it ends and reads no partial that it has not written, so calls in stream order need no clearing in between;
+ * calls that overlap on one GPU (two streams, two threads) race on it and must not be made.                          */
+#define WQ_STATIC_SCRATCH_BYTES (8u << 20)
+int wq_decode_attention_static(void* hip_stream, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
+                               float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
+/* message of the last wq_decode_attention_static error on the current device (host string, valid until the next call) */
+const char* wq_static_last_error(void);
+
 /* ---- timing of the dominant kernel (measurement aid) ---------------------------------------------------------
  * With timing enabled every wq_decode_attention records a HIP event right before and right after its main
  * kernel (the one that streams the cache) on the context's stream, in a ring of 64 event pairs created once by

@@ -70,6 +70,9 @@ def lib() -> C.CDLL:
         L.wq_dequantize.argtypes = [vp, i32, C.POINTER(_PackedKV), C.POINTER(_PackedKV)]
         L.wq_decode_append_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), vp, vp, i32, f32, i32, i64, i32, vp, vp]
         L.wq_decode_attention.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
+        L.wq_decode_attention_static.argtypes = [vp, vp, i32, i32, i32, C.POINTER(_PackedKV), f32, i32, i64, i32, vp, vp]
+        L.wq_static_last_error.argtypes = []
+        L.wq_static_last_error.restype = C.c_char_p
         L.wq_probe_stream.argtypes = [vp, vp, vp, i64, i32]
         L.wq_probe_mfma.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_double)]
         L.wq_decode_timing.argtypes = [vp, i32]
@@ -278,6 +281,21 @@ def wq_decode_attention(ctx: Context, q, kv: PackedKV, sm_scale: float, num_spli
         out = torch.empty(B, Hq, hd, dtype=torch.float32, device=ctx.device)
     ctx.check(lib().wq_decode_attention(ctx.handle, _ptr(q), _dtype_id(q), B, Hq, C.byref(kv.desc), sm_scale, num_splits,
                                         max_seq_tokens, algo, _ptr(out), _ptr(lse)))
+    return out
+
+
+def wq_decode_attention_static(q, kv: PackedKV, sm_scale: float, num_splits: int = 0, max_seq_tokens: int = 0,
+                               algo: int = DECODE_AUTO, out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                               stream: Optional[torch.cuda.Stream] = None):
+    """wq_decode_attention without a context: the library's own static scratch array is the workspace."""
+    B, Hq, hd = q.shape
+    if out is None:
+        out = torch.empty(B, Hq, hd, dtype=torch.float32, device=q.device)
+    st = (stream or torch.cuda.current_stream(q.device)).cuda_stream
+    rc = lib().wq_decode_attention_static(C.c_void_p(st), _ptr(q), _dtype_id(q), B, Hq, C.byref(kv.desc), sm_scale, num_splits,
+                                          max_seq_tokens, algo, _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise WQError(rc, lib().wq_static_last_error().decode())
     return out
 
 

@@ -1,6 +1,7 @@
 // C-ABI entry points of libwq: context handling, host-side argument validation, dispatch.
 // Every check that needs only host data happens here, before anything is enqueued.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -373,6 +374,73 @@ int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     const int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &num_splits, max_seq_tokens, algo, out, &longest);
     if (rc != WQ_OK || B == 0) return rc;
     return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, num_splits, algo, out, lse, nullptr, nullptr, longest);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------------------
+// Its workspace is this array, part of the code object: every GPU that loads the library holds its own copy at its own
+// address.  The name is a host-side stand-in for the symbol; the device address comes from hipGetSymbolAddress, once per
+// device, and only that address is handed to kernels.  Zero-initialised when the code object is loaded, which is the
+// state a workspace header has to start in.
+static __device__ __align__(256) unsigned char scratch[WQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int WQ_MAX_DEVICES = 64;
+struct StaticSlot {
+    bool ready = false;
+    wq_ctx ctx;
+};
+StaticSlot g_static[WQ_MAX_DEVICES];
+std::mutex g_static_mu;
+char g_static_err[256] = "";
+}  // namespace
+
+const char* wq_static_last_error(void)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= WQ_MAX_DEVICES) return g_static_err;
+    return g_static[dev].ready ? g_static[dev].ctx.err : g_static_err;
+}
+
+int wq_decode_attention_static(void* hip_stream, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
+                               float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= WQ_MAX_DEVICES) {
+        snprintf(g_static_err, sizeof(g_static_err), "no current device (%s)", e != hipSuccess ? hipGetErrorString(e) : "index out of range");
+        return WQ_ERR_HIP;
+    }
+    StaticSlot& slot = g_static[dev];
+    {
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        if (!slot.ready) {
+            void* ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) {
+                snprintf(g_static_err, sizeof(g_static_err), "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+                return WQ_ERR_HIP;
+            }
+            slot.ctx.stream = nullptr;
+            slot.ctx.ws = static_cast<char*>(ptr);
+            slot.ctx.ws_bytes = WQ_STATIC_SCRATCH_BYTES;
+            slot.ctx.owns_ws = false;
+            slot.ctx.timing = false;
+            for (int i = 0; i < 2 * WQ_TIMING_RING; i++) slot.ctx.ev[i] = nullptr;
+            slot.ctx.ev_calls = 0;
+            slot.ctx.err[0] = 0;
+            slot.ready = true;
+        }
+    }
+    wq_ctx* ctx = &slot.ctx;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    int64_t longest = 0;
+    int splits = num_splits;
+    const int rc = check_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, &splits, max_seq_tokens, algo, out, &longest);
+    if (rc == WQ_ERR_WORKSPACE)
+        return wq_fail(ctx, WQ_ERR_WORKSPACE, "B=%d Hq=%d hd=%d with %d splits needs %zu bytes of scratch, the static array holds %u", B, Hq,
+                       kv->hd, splits, WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, splits), (unsigned)WQ_STATIC_SCRATCH_BYTES);
+    if (rc != WQ_OK || B == 0) return rc;
+    return wq_launch_decode(ctx, q, q_dtype, B, Hq, kv, sm_scale, splits, algo, out, lse, nullptr, nullptr, longest);
 }
 
 }  // extern "C"
