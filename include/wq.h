@@ -96,6 +96,8 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
 #define WQ_DEV_SEG16_OVERFLOW 2u /* 16-bit rows of a sequence exceeded off16[b+1]-off16[b] or cap16        */
+#define WQ_DEV_V_RANGE 8u        /* wq_reorder_quantize stored a value (V) group whose scale exceeds 16: the matrix-core
+                                  * decode kernel is not laid out for it (see wq_decode_attention)                     */
 #define WQ_DEV_APPEND_TIMEOUT 4u /* wq_decode_append_attention: the workgroup that raises len16[b] gave up waiting (4 s) for
                                   * the sequence's other workgroups to start; len16[b] was raised all the same, the
                                   * workspace header may hold a stale count and must be zeroed before its next use     */
@@ -247,7 +249,12 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
  * not correctness).  algo: WQ_DECODE_AUTO picks the
  * matrix-core kernel when hd/group == 2, else the generic one.  Limits (WQ_ERR_UNSUPPORTED beyond them): Hq a
  * multiple of Hkv with at most 8 query heads per KV head, hd 64 or 128, group 32, 64 or 128, B at most 65535;
- * num_splits above 1024 is WQ_ERR_ARG.                                                                          */
+ * num_splits above 1024 is WQ_ERR_ARG.
+ * Value range: the matrix-core kernel multiplies the softmax weights (at most 32 relative to its running reference) with
+ * the scales of the value groups in fp16; that product cannot overflow for scales up to 16, i.e. value groups spanning at
+ * most 16 * (2^b - 1) (48 / 240 / 4080 at 2 / 4 / 8 bits), and a weight is lost only when it is below 2^-31 of the largest
+ * one per unit of scale.  wq_reorder_quantize raises WQ_DEV_V_RANGE when it stores a wider group; such a cache decodes
+ * correctly with WQ_DECODE_GENERIC, while the matrix-core kernel may then return infinities.  Keys have no such limit.  */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
 

@@ -287,7 +287,9 @@ void wqo_quantize_group(const float *x, int n, int bits, uint8_t *codes, uint16_
             hi = x[i];
     }
     if (lo == 0.0f)
-        lo = 0.0f;                                /* a zero minimum is stored as +0 */
+        lo = 0.0f;                                /* a zero minimum is stored as +0: -0 == +0, so which of the two a search
+                                                     for the minimum ends with depends on the order of its comparisons,
+                                                     and the stored bits must not */
     int qmax = (1 << bits) - 1;
     uint16_t mb = wqo_f32_to_f16_bits(lo);
     volatile float m = (float)wqo_f16_bits_to_f64(mb);

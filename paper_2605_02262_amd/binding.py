@@ -21,7 +21,7 @@ DECODE_FIXED_SHARES = 0x200
 DECODE_BY_LENGTH = 0x400
 DECODE_SEPARATE_MERGE = 0x800
 CLASS_BITS = (2, 4, 8)
-DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT = 1, 2, 4
+DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT, DEV_V_RANGE = 1, 2, 4, 8
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libwq.so")
 _lib = None

@@ -176,7 +176,12 @@ struct WaveState {
 constexpr int WQ_D2 = 4, WQ_D4 = 3, WQ_D8 = 2;
 constexpr int WQ_FIRST_TICKETS = 4;    // blocks every wavefront starts with (the deepest pipeline's fill)
 constexpr int WQ_WAVES = 8;            // wavefronts per workgroup: one workgroup per compute unit, two wavefronts per SIMD
-constexpr float WQ_MAX_SLACK = 8.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
+constexpr float WQ_MAX_SLACK = 5.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
+// The weights meet the value scales in fp16 (P' = p * s_v).  They are formed 2^WQ_P_UP too large (for free, in the exponent
+// of the exp2), which the sums undo exactly at the end: with p <= 2^WQ_MAX_SLACK and s_v <= WQ_MAX_V_SCALE = 2^4 the product
+// stays below 2^15, and a weight has to be 2^-(24 + WQ_P_UP) of the largest one, per unit of s_v, before it is lost.
+constexpr float WQ_P_UP = 6.0f;
+constexpr float WQ_O_UNIT = 262144.0f; // 2^(24 - WQ_P_UP): what an accumulator of the value product counts in units of
 constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
 
 template <int HD>
@@ -456,7 +461,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
     // partial sums per slot register v: its weights carry 2^-shift(v) (folded into the exponent), undone after the loop
     float lv[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f}, ms[4];
 #pragma unroll
-    for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v);
+    for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v) - WQ_P_UP;
 
     auto compute = [&](int blk, const F& f) {
         const bool redraw = tk.spent;
@@ -514,7 +519,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
             for (int v = 0; v < 4; v++) {
                 lv[v] *= alpha;
                 av[v] *= alpha;
-                ms[v] = mn + v_slot_shift<BITS>(v);
+                ms[v] = mn + v_slot_shift<BITS>(v) - WQ_P_UP;
             }
 #pragma unroll
             for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
@@ -555,8 +560,8 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
     }
 #pragma unroll
     for (int v = 0; v < 4; v++) {
-        st.l = fmaf(lv[v], 1.0f / v_slot_scale<BITS>(v), st.l);
-        st.accM = fmaf(av[v], 1.0f / v_slot_scale<BITS>(v), st.accM);
+        st.l = fmaf(lv[v], 0.015625f / v_slot_scale<BITS>(v), st.l);        // (2^-WQ_P_UP)
+        st.accM = fmaf(av[v], 0.015625f / v_slot_scale<BITS>(v), st.accM);
     }
 }
 
@@ -896,9 +901,9 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
         else
             walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
-        // the quantized classes accumulate 2^-24 * (p s_v code); bring the 16-bit part to the same unit (exact)
+        // the quantized classes accumulate 2^(WQ_P_UP-24) * (p s_v code); bring the 16-bit part to the same unit (exact)
 #pragma unroll
-        for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / 16777216.0f);
+        for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / WQ_O_UNIT);
     }
     WQ_WSTAMP(1, wall_clock64());
     walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, cls_len[2], cls_off[2], src[2], tk, c_log2, st);
@@ -922,7 +927,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
 #pragma unroll
-            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], 16777216.0f, am);
+            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], WQ_O_UNIT, am);
         }
     }
     if (j == 0 && g == 0) {

@@ -29,6 +29,7 @@ constexpr int WQ_MAX_REP = 8;          // query heads per KV head
 // wall time of one 32-token block of the 2-, 4-, 8- and 16-bit class in the decode kernel, relative to each other
 // (measured on MI355X with the whole chip streaming): the fixed shares of the token axis are balanced by it
 constexpr int WQ_BLOCK_COST[4] = {100, 130, 230, 500};
+constexpr float WQ_MAX_V_SCALE = 16.0f; // largest scale of a value group that the decode kernel's fp16 weights are laid out for
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 
 inline int wq_fail(wq_ctx* ctx, int code, const char* fmt, ...)

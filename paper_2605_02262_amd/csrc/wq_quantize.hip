@@ -81,7 +81,7 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
                                                int B, int group, const int32_t* __restrict__ kv_off,
                                                const int32_t* __restrict__ win_size, const int32_t* __restrict__ win_off,
                                                const int32_t* __restrict__ perm, const int32_t* __restrict__ seg_windows,
-                                               const wq_packed_kv& pk)
+                                               const wq_packed_kv& pk, uint32_t* __restrict__ status)
 {
     constexpr int C = cls_index(BITS);
     constexpr int QMAX = (1 << BITS) - 1;
@@ -147,6 +147,9 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
             s = 1.0f;
             sh = __float2half_rn(1.0f);
         }
+        // the decode kernel forms (softmax weight) x (value scale) in fp16 and keeps both factors' product below 2^15 for
+        // scales up to WQ_MAX_V_SCALE; a value group with a larger scale is stored like any other and reported
+        if (plane == 1 && s > WQ_MAX_V_SCALE) atomicOr(status, WQ_DEV_V_RANGE);
         const float inv = 1.0f / s;
         // This thread's codes: the K plane takes them as consecutive BITS-wide fields of its token's row quarter
         // (pw, stored below); the V plane as bytes, 4 per word (cw), for the transposition through LDS.
@@ -267,17 +270,17 @@ __global__ __launch_bounds__(256) void k_quantize_all(const T* __restrict__ K, c
                                                       const int32_t* __restrict__ kv_off, const int32_t* __restrict__ win_size,
                                                       const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
                                                       const int32_t* __restrict__ seg_windows, const int32_t* __restrict__ pre16,
-                                                      wq_packed_kv pk, unsigned n0, unsigned n1, unsigned n2)
+                                                      wq_packed_kv pk, unsigned n0, unsigned n1, unsigned n2, uint32_t* __restrict__ status)
 {
     __shared__ QuantSmem<HD> sm;
     const unsigned w = blockIdx.x;
     const unsigned Hkv = (unsigned)pk.Hkv;
     if (w < n0)
-        quantize_block<T, HD, 2>(sm, (int)(w / Hkv), (int)(w % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+        quantize_block<T, HD, 2>(sm, (int)(w / Hkv), (int)(w % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk, status);
     else if (w < n1)
-        quantize_block<T, HD, 4>(sm, (int)((w - n0) / Hkv), (int)((w - n0) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+        quantize_block<T, HD, 4>(sm, (int)((w - n0) / Hkv), (int)((w - n0) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk, status);
     else if (w < n2)
-        quantize_block<T, HD, 8>(sm, (int)((w - n1) / Hkv), (int)((w - n1) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk);
+        quantize_block<T, HD, 8>(sm, (int)((w - n1) / Hkv), (int)((w - n1) % Hkv), K, V, B, group, kv_off, win_size, win_off, perm, seg_windows, pk, status);
     else
         copy16_row<T>((int64_t)(w - n2), K, V, B, pk.Hkv * HD, kv_off, win_size, win_off, perm, seg_windows, pre16, pk);
 }
@@ -475,7 +478,7 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
     if (n2 + rows16 > 0x7FFFFFFF) return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "too many blocks for one launch");
     if (n2 + rows16 > 0)
         hipLaunchKernelGGL((k_quantize_all<T, HD>), dim3((unsigned)(n2 + rows16)), dim3(256), 0, st, K, V, B, pk->group, kv_off, win_size,
-                           win_off, perm, seg_windows, pre16, *pk, (unsigned)n0, (unsigned)n1, (unsigned)n2);
+                           win_off, perm, seg_windows, pre16, *pk, (unsigned)n0, (unsigned)n1, (unsigned)n2, wq_status_ptr(ctx));
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

@@ -771,3 +771,149 @@ def test_decode_steps_by_length_while_the_split_count_of_a_sequence_changes():
         err = H.attention_error(out.cpu().numpy(), O.decode_attention(qn, o.pk, sm))
         assert err <= H.ATTN_TOL, (step, err)
     assert counts[0] == 3 and counts[-1] == 4, counts      # the change of the split count happened inside the loop
+
+
+def _edge_groups(g: int, bits: int, dtype: int, rng) -> list:
+    """Groups of g values (float32 holding values of the storage type `dtype`) that reach the corners of the quantizer of
+    Sec. 3.3.3: constant groups, zero minima of either sign, a range so small that the stored scale is 0 (-> 1) or an fp16
+    subnormal, the largest storable magnitudes, exact ties of the rounding, data that 8 bits hold without loss."""
+    qmax = 2 ** bits - 1
+    big = {synth.BF16: 65280.0, synth.F16: 65504.0, synth.F32: 65504.0}[dtype]
+    tiny = {synth.BF16: 2.0 ** -30, synth.F16: 2.0 ** -24, synth.F32: 2.0 ** -30}[dtype]     # a value whose range/qmax rounds to an fp16 zero
+    f = lambda v: np.asarray(v, dtype=np.float32)
+    pad = lambda head, fill: f(list(head) + [fill] * (g - len(head)))
+    out = [np.full(g, 1.5, np.float32), np.full(g, 0.0, np.float32), np.full(g, -0.0, np.float32), np.full(g, big, np.float32),
+           np.full(g, -big, np.float32),
+           pad([-0.0, float(qmax)], 1.0), pad([0.0, -0.0, float(qmax)], 2.0), pad([float(qmax), -0.0, 0.0], 1.0), pad([-0.0, 0.0], 0.0),
+           pad([-3.0, -0.0], -1.0),
+           pad([0.0, tiny], 0.0), pad([1.0, 1.0 + 2.0 ** -7], 1.0) if dtype != synth.F32 else pad([1.0, 1.0 + 2.0 ** -20], 1.0),
+           pad([0.0, qmax * 2.0 ** -20], 2.0 ** -21), pad([-2.0 ** -16, qmax * 2.0 ** -17], 0.0),
+           pad([-big, big], 0.0), pad([big, big / 2], big / 4), pad([-big, -big / 2, 0.0], -1.0),
+           pad([0.0, float(qmax)] + [k + 0.5 for k in range(min(qmax, g - 2))], 1.0),
+           pad([-8.0, -8.0 + 2.0 * qmax] + [-8.0 + 2.0 * (k + 0.5) for k in range(min(qmax, g - 2))], -8.0)]
+    ints = rng.integers(-100, -100 + qmax + 1, g).astype(np.float32)
+    ints[0], ints[1] = -100.0, -100.0 + qmax
+    out.append(ints)                                      # integers spanning exactly qmax: lossless
+    out.append(synth.round_to(rng.standard_normal(g).astype(np.float32), dtype))
+    return [synth.round_to(x, dtype) if dtype != synth.F32 else x for x in out]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16, synth.F32])
+@pytest.mark.parametrize("hd,g", [(64, 32), (128, 64)])
+def test_quantizer_edge_cases(dtype, hd, g):
+    """Sec. 3.3.3 on the groups a normal-distributed cache never contains, bit-exact against the oracle (codes, scales,
+    minima, 16-bit rows) in all three classes: every window row of K and V is filled, group by group, from the list of
+    _edge_groups, shifted per token so that every class and both planes meet every kind of group."""
+    H = _h()
+    Hkv, S, nw = 2, 16, 12
+    dt16 = synth.BF16 if dtype == synth.BF16 else synth.F16
+    sq = synth.SeqSpec(nw, S, S, 8, (4, 4, 4))
+    w = synth.Workload("edges", dtype, dt16, 2 * Hkv, Hkv, hd, g, 64, 1.0, [sq], 8100 + dtype, top_bits=8, pin_first=0)
+    bt = synth.batch(w, with_embeddings=False)
+    rng = np.random.default_rng(81 + dtype)
+    sc = np.arange(nw, dtype=np.float32)                  # windows 8..11 -> 8 bits, 4..7 -> 4 bits, 0..3 -> 2 bits
+    G = hd // g
+    for win in range(nw):
+        bits = 2 if win < 4 else (4 if win < 8 else 8)
+        groups = _edge_groups(g, bits, dtype, rng)
+        for t in range(S):
+            row = win * S + t
+            for h in range(Hkv):
+                for j in range(G):
+                    k = (t * Hkv * G + h * G + j)
+                    bt.K[row, h, j * g:(j + 1) * g] = groups[k % len(groups)]
+                    bt.V[row, h, j * g:(j + 1) * g] = groups[(k + 7) % len(groups)]
+    g_run = H.run_gpu(bt, splits=2, with_scores=False, scores_override=sc)
+    o = H.run_oracle(bt, scores_override=sc, with_scores=False)
+    assert o.seg[0].tolist() == [4, 4, 4, 0]
+    H.assert_packed_equal(g_run, o)
+    # the corners were really there: zero minima stored as +0, scales that fell back to 1, subnormal and large scales
+    for c in range(3):
+        sb, mb = o.pk.sbits[c][:, :, :4 * S], o.pk.mbits[c][:, :, :4 * S]
+        assert (mb == 0x0000).any() and not ((mb == 0x8000) & (sb == 0x3C00)).all()
+        assert ((sb > 0) & (sb < 0x0400)).any(), "no fp16-subnormal scale"
+        assert (sb >= 0x6000).any(), "no large scale"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("hd,g", [(128, 64), (64, 32)])
+def test_adversarial_softmax(hd, g):
+    """Alg. 2 takes ONE softmax over the concatenation of all segments; the kernel keeps a running reference exponent and
+    forms (weight x value scale) in fp16.  Cases built to stress exactly that, each against the fp64 oracle over the same
+    dequantized values: logits that rise along the stream (the reference keeps moving), one token far above all others in
+    each of the four segments (the rest of the mass sits 14 nats lower and must not be lost), a zero query and identical
+    keys (uniform softmax), value groups with the largest scale the kernel is specified for, and all of it once more with
+    every window in the 8-bit class, whose value scales are the smallest."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    nw, S, nt = 32, 196, 128
+    rep, Hkv = 7, 2
+    sm = 1.0 / float(np.sqrt(hd))
+    worst = {}
+    for mix_name, quota in (("mixed", (8, 16, 8)), ("all-8-bit", (32, 0, 0)), ("all-2-bit", (0, 0, 32))):
+        sq = synth.SeqSpec(nw, S, S, nt, quota)
+        w = synth.Workload("adv", synth.BF16, synth.BF16, rep * Hkv, Hkv, hd, g, 64, 1.0, [sq], 9100, top_bits=8, pin_first=0)
+        base = synth.batch(w, with_embeddings=False)
+        sc = np.random.default_rng(3).standard_normal(nw).astype(np.float32)
+        n_tok = nw * S + nt
+        rng = np.random.default_rng(17)
+        qdir = base.q[0] / np.linalg.norm(base.q[0], axis=-1, keepdims=True)          # [Hq, hd]
+        cases = {}
+        # (a) the size of the keys, and with it of the logits, grows twentyfold along the stream and the query is long: the
+        #     largest logit so far is overtaken again and again, by dozens of nats in all
+        K = base.K * np.linspace(0.05, 1.0, n_tok, dtype=np.float32)[:, None, None]
+        cases["rising"] = (synth.round_bf16(K), base.V, synth.round_bf16(base.q * 12.0))
+        # (b) one token whose key points along the queries of its KV head, about 14 nats above everything else, placed in a
+        #     2-bit, a 4-bit, an 8-bit window (by score rank) and in the text rows
+        order = np.argsort(-sc, kind="stable")
+        spots = {"dominant-top-class": int(order[0]) * S + 5, "dominant-mid-class": int(order[nw // 2]) * S + 100,
+                 "dominant-low-class": int(order[-1]) * S + 190, "dominant-text": nw * S + 17}
+        for name, tok in spots.items():
+            K = base.K.copy()
+            q = base.q.copy()
+            for kvh in range(Hkv):                       # all heads of the KV head ask the same question, the token's key answers it
+                d = qdir[kvh * rep]
+                q[0, kvh * rep:(kvh + 1) * rep] = d * np.linalg.norm(base.q[0, kvh * rep:(kvh + 1) * rep], axis=-1).mean()
+            q = synth.round_bf16(q)
+            for kvh in range(Hkv):
+                qh = q[0, kvh * rep].astype(np.float64)
+                lg = (K[:, kvh].astype(np.float64) @ qh) * sm
+                lg[tok] = -np.inf
+                want = np.log(np.exp(lg - lg.max()).sum()) + lg.max() + np.log(9.0)      # the others hold a tenth of the mass
+                K[tok, kvh] = (qh / (qh @ qh) * want / sm).astype(np.float32)
+            cases[name] = (synth.round_bf16(K), base.V, q)
+        # (c) uniform softmax: a zero query; and every key the same
+        cases["zero-query"] = (base.K, base.V, np.zeros_like(base.q))
+        cases["equal-keys"] = (np.broadcast_to(base.K[:1], base.K.shape).copy(), base.V, base.q)
+        # (d) values as wide as the kernel is specified for: group scales just below 16 in every class
+        Vw = base.V.copy()
+        for c, (qmax, wins) in enumerate(((3, order[nw - quota[2]:] if quota[2] else []), (15, order[quota[0]:quota[0] + quota[1]]), (255, order[:quota[0]]))):
+            for win in wins:
+                blk = Vw[win * S:(win + 1) * S]
+                blk *= np.float32(15.5 * qmax) / (blk.reshape(S, Hkv, hd // g, g).max(-1) - blk.reshape(S, Hkv, hd // g, g).min(-1)).max()
+        cases["wide-values"] = (base.K, synth.round_bf16(Vw), base.q)
+        for name, (K, V, q) in cases.items():
+            bt = synth.Batch(w, base.t, base.E_t, base.E_v, np.ascontiguousarray(K), np.ascontiguousarray(V), np.ascontiguousarray(q))
+            g_run = H.run_gpu(bt, splits=3, with_scores=False, scores_override=sc)
+            o = H.run_oracle(bt, scores_override=sc, with_scores=False)
+            assert g_run.ctx.device_status() == 0, (mix_name, name)
+            H.assert_packed_equal(g_run, o)
+            err = H.attention_error(g_run.out.cpu().numpy(), o.out)
+            lse_err = float(np.abs(g_run.lse.cpu().numpy() - o.lse).max())
+            worst[(mix_name, name)] = err
+            assert err <= H.ATTN_TOL and lse_err <= 2e-3, (mix_name, name, err, lse_err)
+            if name.startswith("dominant"):              # the case is what it says: one token holds about nine tenths of the mass
+                tok = spots[name]
+                lg = (K[:, 0].astype(np.float64) @ q[0, 0].astype(np.float64)) * sm
+                top = 1.0 / np.exp(lg - lg[tok]).sum()
+                assert 0.8 < top < 0.97 and lg[tok] - np.median(lg) > 9.0, (name, top)
+    # a value group wider than specified is reported by the quantizer
+    Vbig = base.V.copy()
+    Vbig[3, 0, :g] *= 400.0
+    bt = synth.Batch(w, base.t, base.E_t, base.E_v, base.K, synth.round_bf16(Vbig), base.q)
+    g_run = H.run_gpu(bt, splits=3, with_scores=False, scores_override=sc, algo=W.DECODE_GENERIC)
+    o = H.run_oracle(bt, scores_override=sc, with_scores=False)
+    assert g_run.ctx.device_status() == W.DEV_V_RANGE
+    assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL

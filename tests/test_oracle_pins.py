@@ -226,6 +226,34 @@ def test_quantize_special_groups():
     assert codes[:5].tolist() == [0, 3, 0, 2, 2]
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quantize_zero_minimum_is_stored_as_plus_zero(bits):
+    """Sec. 3.3.3 stores the group minimum.  -0 and +0 compare equal, so which of them a minimum search ends with depends on
+    the order it looks at the values (a loop and a tree of pairwise minima disagree); the format therefore stores a zero
+    minimum as +0 whatever its sign and wherever it stands in the group.  Only an exact zero is meant: a negative minimum
+    that rounds to zero in binary16 keeps its sign."""
+    qmax = 2 ** bits - 1
+    rest = [float(qmax), 1.0, 2.0]
+    for zeros in ([-0.0], [0.0], [-0.0, 0.0], [0.0, -0.0], [0.0, 0.0, -0.0], [-0.0, -0.0, 0.0]):
+        for where in ("front", "back", "middle"):
+            vals = {"front": zeros + rest, "back": rest + zeros, "middle": rest[:1] + zeros + rest[1:]}[where]
+            x = np.array(vals + [1.0] * (32 - len(vals)), dtype=np.float32)
+            codes, sb, mb = O.quantize_group(x, bits)
+            assert mb == 0x0000, (zeros, where, hex(mb))
+            assert O.f16_bits_to_f64(sb) == 1.0 and codes.tolist() == [int(v) for v in np.abs(x)]
+    # nothing but zeros of either sign: constant group, m = +0, s falls back to 1
+    for x in (np.full(32, -0.0, np.float32), np.array([0.0, -0.0] * 16, np.float32)):
+        codes, sb, mb = O.quantize_group(x, bits)
+        assert (mb, sb, int(codes.max())) == (0x0000, 0x3C00, 0)
+    # a zero that is the group's largest value is not touched by the rule, and neither is a tiny negative minimum
+    x = np.array([-3.0, -0.0] + [-1.0] * 30, dtype=np.float32)
+    codes, sb, mb = O.quantize_group(x, bits)
+    assert O.f16_bits_to_f64(mb) == -3.0 and codes[1] == qmax
+    x = np.array([-1e-8, 1.0] + [0.5] * 30, dtype=np.float32)
+    _, _, mb = O.quantize_group(x, bits)
+    assert mb == 0x8000
+
+
 def _unpack_k(img, cap, hd, bits):
     """Independent reading of the K-plane layout text: tile of 16 tokens, [quarter][token][hd/4 codes]."""
     out = np.zeros((cap, hd), dtype=np.uint8)
