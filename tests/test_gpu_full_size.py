@@ -35,10 +35,23 @@ def test_long_video_7b_layer_full():
     # the window counts the mix rule gives, and end-to-end agreement of bits derived from GPU and oracle scores
     assert o.seg[0].tolist() == [128, 102, 26, 0]
     from oracle import wq_oracle as O
+    # end to end: the bits that follow from the oracle's own scores are the bits that follow from the GPU's scores.  That
+    # is a theorem when every score gap across a tier boundary exceeds twice the tolerance the scores are held to, so the
+    # seeded inputs must satisfy that, for every sequence (window 0 is pinned and leaves the ranking)
     bits2, _, _ = O.assign_bits(o.scores.astype(np.float32), bt.t.win_off, 0, quota=bt.t.quota, top_bits=8, pin_first=1)
-    s = np.sort(o.scores[:256])[::-1]
-    if min(s[25] - s[26], s[127] - s[128]) > 4e-4 * abs(s).max():       # tier boundaries well separated
-        assert np.array_equal(bits2[:256], o.bits[:256])
+    from tests import wq_harness as H
+    gaps, tols = [], []
+    for b in range(bt.w.B):
+        sb = o.scores[bt.t.win_off[b]:bt.t.win_off[b + 1]]
+        n_top, n4, _ = bt.t.quota[b]
+        rest = np.sort(sb[1:])[::-1]
+        gaps += [rest[n_top - 2] - rest[n_top - 1], rest[n_top + n4 - 2] - rest[n_top + n4 - 1]]
+        tols.append(H.SCORE_ATOL + H.SCORE_RTOL * np.abs(sb).max())
+    dev = float(np.abs(g.scores.cpu().numpy().astype(np.float64) - o.scores).max())
+    print(f"smallest score gap across a tier boundary {min(gaps):.3e}, twice the score tolerance {2 * max(tols):.3e}, "
+          f"largest GPU-oracle score difference {dev:.3e}")
+    assert min(gaps) > 2 * max(tols), (min(gaps), 2 * max(tols))
+    assert np.array_equal(bits2, o.bits)
 
     # the literal pairwise form on the matrix cores at this size (workgroups of 128 rows x 512 text columns)
     import torch
@@ -109,12 +122,15 @@ def test_7b_batch8_decode_steps_in_one_call():
 
 
 def test_ragged_batch32():
-    """32 sequences, 8..128 frames, windows of 98 or 196, Dirichlet bit mixes incl. all-2-bit and all-8-bit.
-    Embedding width reduced to 512 here to keep host generation short; width 3584 is covered above."""
-    w = dataclasses.replace(synth.workload(4), D=512)
-    bt = synth.batch(w)
+    """32 sequences, 8..128 frames, windows of 98 or 196, Dirichlet bit mixes incl. all-2-bit and all-8-bit, at the
+    configuration's own embedding width (3584)."""
+    bt = synth.batch(synth.workload(4))
+    assert bt.E_v.shape[1] == 3584
     g, o = _full(bt)
     assert o.seg[0, 0] == bt.t.win_off[1] and o.seg[1, 2] == bt.t.win_off[2] - bt.t.win_off[1]
+    from tests import wq_harness as H
+    dev = float(np.abs(g.scores.cpu().numpy().astype(np.float64) - o.scores).max())
+    print(f"ragged batch at D = 3584: largest GPU-oracle score difference {dev:.3e} over scores up to {np.abs(o.scores).max():.3e}")
 
 
 def test_paper_operating_point_16bit_top_tier():
