@@ -74,9 +74,6 @@ typedef enum { WQ_OK = 0, WQ_ERR_ARG = -1, WQ_ERR_UNSUPPORTED = -2, WQ_ERR_HIP =
 typedef enum { WQ_SCORE_AUTO = 0, WQ_SCORE_PAIRWISE_MFMA = 1, WQ_SCORE_POOLED = 2 } wq_score_algo;
 typedef enum { WQ_MODE_QUOTA = 0, WQ_MODE_THRESHOLD = 1 } wq_assign_mode;
 typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } wq_decode_algo;
-/* or-ed into algo: run only the kernel that streams the cache and leave its per-split partials in the workspace
- * (out and lse are not written).  A measurement aid: it lets that kernel be timed without the merge kernel.   */
-#define WQ_DECODE_PARTIALS_ONLY 0x100
 /* or-ed into algo: every wavefront of the matrix-core kernel gets a fixed share of the token axis, so that the
  * summation order, and with it every bit of the result, is the same on every run.  Without it the wavefronts of a
  * workgroup take the blocks of the workgroup's share one by one as they get free (faster; results agree to
@@ -98,6 +95,10 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
 #define WQ_DEV_SEG16_OVERFLOW 2u /* 16-bit rows of a sequence exceeded off16[b+1]-off16[b] or cap16        */
 #define WQ_DEV_V_RANGE 8u        /* wq_reorder_quantize stored a value (V) group whose scale exceeds 16: the matrix-core
                                   * decode kernel is not laid out for it (see wq_decode_attention)                     */
+#define WQ_DEV_TOO_MANY_WINDOWS 16u /* a sequence has more windows than the max_windows given to wq_assign_bits, wq_vote_bits or
+                                  * wq_validate_assignment; the windows beyond the bound were left out                  */
+#define WQ_DEV_BAD_ASSIGNMENT 32u /* wq_validate_assignment: perm is not a permutation of a sequence's windows, or its four
+                                  * class counts do not add up to the number of its windows                             */
 #define WQ_DEV_APPEND_TIMEOUT 4u /* wq_decode_append_attention: the workgroup that raises len16[b] gave up waiting (4 s) for
                                   * the sequence's other workgroups to start; len16[b] was raised all the same, the
                                   * workspace header may hold a stale count and must be zeroed before its next use     */
@@ -155,7 +156,7 @@ int wq_window_scores(wq_ctx* ctx, const void* vis_emb, const void* txt_emb, int 
  * top_bits : 8, or 16 to keep the top tier unquantized as the paper does.
  * scores [total_win] fp32, win_off [B+1], quota [B,3] = {n_top, n4, n2} int32 (quota mode),
  * thresholds [B,2] = {T_low, T_high} fp32 (threshold mode): device.  max_windows: host bound on windows per
- * sequence (<= 8192).   Outputs (device): bits [total_win] uint8; perm [total_win] int32, per sequence the
+ * sequence (<= 8192); a sequence with more raises WQ_DEV_TOO_MANY_WINDOWS and gets only its first max_windows windows assigned.   Outputs (device): bits [total_win] uint8; perm [total_win] int32, per sequence the
  * window indices of class 2, then 4, 8, 16, each ascending; seg_windows [B,4] counts {n2,n4,n8,n16}.        */
 int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
                    const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
@@ -177,6 +178,14 @@ int wq_layer_thresholds(const double* s, int n_layers, double alpha, float* t_lo
  * All arrays device memory.                                                                                   */
 int wq_vote_bits(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, int max_windows,
                  uint8_t* bits_out, int32_t* perm, int32_t* seg_windows);
+
+/* ---- debug aid: validate an assignment on the device -----------------------------------------------------------
+ * wq_reorder_quantize trusts perm and seg_windows (it gathers whatever rows perm names).  This call checks, per
+ * sequence, that perm[win_off[b] .. win_off[b+1]) is a permutation of 0 .. W_b-1 and that seg_windows[b][0..3] are
+ * non-negative and add up to W_b, and raises WQ_DEV_BAD_ASSIGNMENT (wq_device_status) otherwise.  One small launch; meant
+ * for tables that do not come straight from wq_assign_bits / wq_vote_bits.  max_windows as in wq_assign_bits.            */
+int wq_validate_assignment(wq_ctx* ctx, int B, const int32_t* win_off, int max_windows, const int32_t* perm,
+                           const int32_t* seg_windows);
 
 /* ---- packed mixed-precision cache of one layer (layout: see the header comment) -------------------------- */
 typedef struct {
@@ -275,27 +284,6 @@ int wq_decode_attention_static(void* hip_stream, const void* q, int q_dtype, int
                                float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
 /* message of the last wq_decode_attention_static error on the current device (host string, valid until the next call) */
 const char* wq_static_last_error(void);
-
-/* ---- timing of the dominant kernel (measurement aid) ---------------------------------------------------------
- * With timing enabled every wq_decode_attention records a HIP event right before and right after its main
- * kernel (the one that streams the cache) on the context's stream, in a ring of 64 event pairs created once by
- * wq_decode_timing(ctx, 1); the decode call itself still allocates nothing and does not synchronise.
- * wq_decode_times_us waits for the last timed call and returns the durations of the last n (<= 64) timed calls,
- * oldest first, in microseconds.  Enabling or disabling restarts the count.                                   */
-int wq_decode_timing(wq_ctx* ctx, int enable);
-int wq_decode_times_us(wq_ctx* ctx, float* us, int n);
-
-/* ---- measurement probes (not part of the method; for callers that cannot time a plain kernel themselves) ----
- * wq_probe_stream streams `bytes` (multiple of 16) of device memory with 16-byte loads from `blocks` workgroups of 256 lanes:
- * read-only when dst is NULL, a plain copy otherwise.  Gives the achievable HBM rate and the reference that
- * hardware byte counters are scaled by.                                                                       */
-int wq_probe_stream(wq_ctx* ctx, const void* src, void* dst, int64_t bytes, int blocks);
-/* Runs `workgroups` x 8 wavefronts of `iters` (a multiple of 4) x 32 independent v_mfma_f32_16x16x32_bf16 products on register
- * operands (no memory traffic): all ones when random_operands == 0, else random values that change from product to
- * product.  Gives the matrix-core rate this GPU sustains, which depends on the data (the clock drops under
- * load): the figure the pairwise scoring kernel is to be read against.  *flops (host, may be NULL) receives the
- * floating-point operations of the launch.  Needs a workspace (one word of it is the kernel's sink).               */
-int wq_probe_mfma(wq_ctx* ctx, int random_operands, int workgroups, int iters, double* flops);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ DECODE_FIXED_SHARES = 0x200
 DECODE_BY_LENGTH = 0x400
 DECODE_SEPARATE_MERGE = 0x800
 CLASS_BITS = (2, 4, 8)
-DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT, DEV_V_RANGE = 1, 2, 4, 8
+DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT, DEV_V_RANGE, DEV_TOO_MANY_WINDOWS, DEV_BAD_ASSIGNMENT = 1, 2, 4, 8, 16, 32
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libwq.so")
 _lib = None
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.wq_assign_bits.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, i32, i32, vp, vp, vp]
         L.wq_layer_thresholds.argtypes = [C.POINTER(C.c_double), i32, C.c_double, C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.wq_vote_bits.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
+        L.wq_validate_assignment.argtypes = [vp, i32, vp, i32, vp, vp]
         L.wq_reorder_quantize.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, C.POINTER(_PackedKV)]
         L.wq_append_kv.argtypes = [vp, vp, vp, i32, i32, C.POINTER(_PackedKV)]
         L.wq_dequantize.argtypes = [vp, i32, C.POINTER(_PackedKV), C.POINTER(_PackedKV)]
@@ -242,6 +243,11 @@ def wq_vote_bits(ctx: Context, bits, win_off, max_windows: int):
     seg = torch.empty(B, 4, dtype=torch.int32, device=ctx.device)
     ctx.check(lib().wq_vote_bits(ctx.handle, _ptr(bits), B, _ptr(win_off), max_windows, _ptr(out), _ptr(perm), _ptr(seg)))
     return out, perm, seg
+
+
+def wq_validate_assignment(ctx: Context, win_off, max_windows: int, perm, seg_windows):
+    B = win_off.numel() - 1
+    ctx.check(lib().wq_validate_assignment(ctx.handle, B, _ptr(win_off), max_windows, _ptr(perm), _ptr(seg_windows)))
 
 
 def wq_reorder_quantize(ctx: Context, K, V, kv_off, win_size, win_off, perm, seg_windows, total_rows: int, out: PackedKV):

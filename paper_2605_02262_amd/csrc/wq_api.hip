@@ -94,32 +94,6 @@ int wq_set_stream(wq_ctx* ctx, void* hip_stream)
     return WQ_OK;
 }
 
-int wq_decode_timing(wq_ctx* ctx, int enable)
-{
-    if (!ctx) return WQ_ERR_ARG;
-    if (enable && !ctx->ev[0])
-        for (int i = 0; i < 2 * WQ_TIMING_RING; i++) WQ_HIP_CHECK(ctx, hipEventCreate(&ctx->ev[i]));
-    ctx->timing = enable != 0;
-    ctx->ev_calls = 0;
-    return WQ_OK;
-}
-
-int wq_decode_times_us(wq_ctx* ctx, float* us, int n)
-{
-    if (!ctx || !us || n < 0 || !ctx->ev[0]) return WQ_ERR_ARG;
-    if ((uint64_t)n > ctx->ev_calls || n > WQ_TIMING_RING) return wq_fail(ctx, WQ_ERR_ARG, "only %llu timed calls, ring of %d",
-                                                                          (unsigned long long)ctx->ev_calls, WQ_TIMING_RING);
-    for (int k = 0; k < n; k++) {                    // oldest of the last n first
-        const uint64_t call = ctx->ev_calls - (uint64_t)n + (uint64_t)k;
-        const int slot = (int)(call % WQ_TIMING_RING);
-        float ms = 0.f;
-        WQ_HIP_CHECK(ctx, hipEventSynchronize(ctx->ev[2 * slot + 1]));
-        WQ_HIP_CHECK(ctx, hipEventElapsedTime(&ms, ctx->ev[2 * slot], ctx->ev[2 * slot + 1]));
-        us[k] = ms * 1000.0f;
-    }
-    return WQ_OK;
-}
-
 const char* wq_last_error(const wq_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
 int wq_device_status(wq_ctx* ctx, uint32_t* bits)
@@ -222,6 +196,7 @@ int wq_assign_bits(wq_ctx* ctx, const float* scores, int B, const int32_t* win_o
     if (max_windows > 0 && (!scores || !bits || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL scores or output");
     if (mode == WQ_MODE_QUOTA && !quota) return wq_fail(ctx, WQ_ERR_ARG, "quota mode without quota table");
     if (mode == WQ_MODE_THRESHOLD && !thresholds) return wq_fail(ctx, WQ_ERR_ARG, "threshold mode without thresholds");
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
     return wq_launch_assign(ctx, scores, B, win_off, max_windows, mode, quota, thresholds, top_bits, pin_first != 0,
                             bits, perm, seg_windows);
 }
@@ -252,7 +227,20 @@ int wq_vote_bits(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_
     if (B == 0) return WQ_OK;
     if (!win_off || !seg_windows) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
     if (max_windows > 0 && (!bits_in || !bits_out || !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL widths or output");
-    return wq_launch_vote(ctx, bits_in, B, win_off, bits_out, perm, seg_windows);
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    return wq_launch_vote(ctx, bits_in, B, win_off, max_windows, bits_out, perm, seg_windows);
+}
+
+int wq_validate_assignment(wq_ctx* ctx, int B, const int32_t* win_off, int max_windows, const int32_t* perm, const int32_t* seg_windows)
+{
+    if (!ctx) return WQ_ERR_ARG;
+    if (B < 0 || max_windows < 0) return wq_fail(ctx, WQ_ERR_ARG, "negative size");
+    if (max_windows > WQ_MAX_WINDOWS)
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "more than %d windows per sequence", WQ_MAX_WINDOWS);
+    if (B == 0) return WQ_OK;
+    if (!win_off || !seg_windows || (max_windows > 0 && !perm)) return wq_fail(ctx, WQ_ERR_ARG, "NULL table");
+    if (!ctx->ws || ctx->ws_bytes < WQ_WS_HEADER) return wq_fail(ctx, WQ_ERR_WORKSPACE, "no workspace");
+    return wq_launch_validate(ctx, B, win_off, max_windows, perm, seg_windows);
 }
 
 int wq_reorder_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,

@@ -47,16 +47,19 @@ __device__ __forceinline__ void emit_class_order(const uint8_t* s_bits, int* s_c
 // Most votes win, the wider width on a tie.
 __global__ __launch_bounds__(ASSIGN_THREADS) void k_vote(const uint8_t* __restrict__ bits_in, int B, const int32_t* __restrict__ win_off,
                                                          uint8_t* __restrict__ bits, int32_t* __restrict__ perm,
-                                                         int32_t* __restrict__ seg_windows)
+                                                         int32_t* __restrict__ seg_windows, int max_windows, uint32_t* __restrict__ status)
 {
     __shared__ __align__(16) uint8_t s_bits[WQ_MAX_WINDOWS + 4];
     __shared__ int s_cnt[4];
     const int b = blockIdx.x;
     const int w0 = win_off[b];
     int W = win_off[b + 1] - w0;
-    if (W > WQ_MAX_WINDOWS) W = WQ_MAX_WINDOWS;
-    const int W4 = (W + 3) & ~3;
     const int tid = threadIdx.x;
+    if (W > max_windows) {                        // reported; only the positions inside the caller's bound are voted on
+        if (tid == 0) atomicOr(status, WQ_DEV_TOO_MANY_WINDOWS);
+        W = max_windows;
+    }
+    const int W4 = (W + 3) & ~3;
     if (tid < 4) s_cnt[tid] = 0;
     for (int p = tid; p < W4; p += ASSIGN_THREADS) {
         int votes[4] = {0, 0, 0, 0};
@@ -78,7 +81,8 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_vote(const uint8_t* __restri
 __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
                                                            const int32_t* __restrict__ quota, const float* __restrict__ thresholds,
                                                            int top_bits, int pin_first, uint8_t* __restrict__ bits,
-                                                           int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
+                                                           int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows,
+                                                           int max_windows, uint32_t* __restrict__ status)
 {
     // keys and widths are read four at a time in the counting loops; both arrays are padded to a multiple of four
     // (keys with -inf, which no key is smaller than and which never counts as an earlier equal; widths with 0)
@@ -88,9 +92,12 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restri
     const int b = blockIdx.x;
     const int w0 = win_off[b];
     int W = win_off[b + 1] - w0;
-    if (W > WQ_MAX_WINDOWS) W = WQ_MAX_WINDOWS;   // host validated max_windows; never index past the arrays
-    const int W4 = (W + 3) & ~3;
     const int tid = threadIdx.x;
+    if (W > max_windows) {                        // more windows than the caller's bound (itself at most WQ_MAX_WINDOWS): reported,
+        if (tid == 0) atomicOr(status, WQ_DEV_TOO_MANY_WINDOWS);      // and only the windows inside the bound are assigned
+        W = max_windows;
+    }
+    const int W4 = (W + 3) & ~3;
     if (tid < 4) s_cnt[tid] = 0;
     for (int i = tid; i < W4; i += ASSIGN_THREADS) {
         float s = i < W ? scores[w0 + i] : -INFINITY;
@@ -146,12 +153,50 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restri
     emit_class_order(s_bits, s_cnt, W, w0, b, bits, perm, seg_windows);
 }
 
+// Debug aid: is perm[win_off[b] .. win_off[b+1]) a permutation of 0 .. W_b-1, and do the four class counts of the sequence
+// add up to W_b?  One workgroup per sequence, one bit per window in LDS.
+__global__ __launch_bounds__(ASSIGN_THREADS) void k_validate(const int32_t* __restrict__ win_off, const int32_t* __restrict__ perm,
+                                                             const int32_t* __restrict__ seg_windows, int max_windows,
+                                                             uint32_t* __restrict__ status)
+{
+    __shared__ unsigned s_seen[WQ_MAX_WINDOWS / 32];
+    __shared__ int s_bad;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int w0 = win_off[b], W = win_off[b + 1] - w0;
+    if (tid == 0) s_bad = 0;
+    for (int i = tid; i < WQ_MAX_WINDOWS / 32; i += ASSIGN_THREADS) s_seen[i] = 0u;
+    __syncthreads();
+    if (W < 0 || W > max_windows) {
+        if (tid == 0) atomicOr(status, W < 0 ? WQ_DEV_BAD_ASSIGNMENT : WQ_DEV_TOO_MANY_WINDOWS);
+        return;
+    }
+    for (int i = tid; i < W; i += ASSIGN_THREADS) {
+        const int v = perm[w0 + i];
+        if (v < 0 || v >= W) s_bad = 1;
+        else if (atomicOr(&s_seen[v >> 5], 1u << (v & 31)) & (1u << (v & 31))) s_bad = 1;      // seen before
+    }
+    if (tid == 0) {
+        const int32_t* c = seg_windows + 4 * b;
+        if (c[0] < 0 || c[1] < 0 || c[2] < 0 || c[3] < 0 || c[0] + c[1] + c[2] + c[3] != W) s_bad = 1;
+    }
+    __syncthreads();
+    if (tid == 0 && s_bad) atomicOr(status, WQ_DEV_BAD_ASSIGNMENT);
+}
+
 }  // namespace
 
-int wq_launch_vote(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, uint8_t* bits_out, int32_t* perm,
+int wq_launch_validate(wq_ctx* ctx, int B, const int32_t* win_off, int max_windows, const int32_t* perm, const int32_t* seg_windows)
+{
+    hipLaunchKernelGGL(k_validate, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, win_off, perm, seg_windows, max_windows, wq_status_ptr(ctx));
+    WQ_HIP_CHECK(ctx, hipGetLastError());
+    return WQ_OK;
+}
+
+int wq_launch_vote(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, int max_windows, uint8_t* bits_out, int32_t* perm,
                    int32_t* seg_windows)
 {
-    hipLaunchKernelGGL(k_vote, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, bits_in, B, win_off, bits_out, perm, seg_windows);
+    hipLaunchKernelGGL(k_vote, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, bits_in, B, win_off, bits_out, perm, seg_windows, max_windows,
+                       wq_status_ptr(ctx));
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }
@@ -160,9 +205,8 @@ int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win
                      const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
                      int32_t* perm, int32_t* seg_windows)
 {
-    (void)max_windows;
     hipLaunchKernelGGL(k_assign, dim3(B), dim3(ASSIGN_THREADS), 0, ctx->stream, scores, win_off, mode, quota, thresholds, top_bits,
-                       pin_first, bits, perm, seg_windows);
+                       pin_first, bits, perm, seg_windows, max_windows, wq_status_ptr(ctx));
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

@@ -8,6 +8,7 @@
 #include <stdio.h>
 
 #include "../../include/wq.h"
+#include "../../include/wq_measure.h"
 
 struct wq_ctx {
     hipStream_t stream;
@@ -111,8 +112,9 @@ int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, i
 int wq_launch_assign(wq_ctx* ctx, const float* scores, int B, const int32_t* win_off, int max_windows, int mode,
                      const int32_t* quota, const float* thresholds, int top_bits, int pin_first, uint8_t* bits,
                      int32_t* perm, int32_t* seg_windows);
-int wq_launch_vote(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, uint8_t* bits_out, int32_t* perm,
+int wq_launch_vote(wq_ctx* ctx, const uint8_t* bits_in, int B, const int32_t* win_off, int max_windows, uint8_t* bits_out, int32_t* perm,
                    int32_t* seg_windows);
+int wq_launch_validate(wq_ctx* ctx, int B, const int32_t* win_off, int max_windows, const int32_t* perm, const int32_t* seg_windows);
 int wq_launch_quantize(wq_ctx* ctx, const void* K, const void* V, int dtype, int B, const int32_t* kv_off,
                        const int32_t* win_size, const int32_t* win_off, const int32_t* perm,
                        const int32_t* seg_windows, int64_t total_rows, const wq_packed_kv* out);

@@ -22,12 +22,13 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    hdr = open(os.path.join(ROOT, "include", "wq.h")).read()
+    hdr = open(os.path.join(ROOT, "include", "wq.h")).read() + open(os.path.join(ROOT, "include", "wq_measure.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(wq_[a-z0-9_]+)\s*\(", hdr))
     assert {"wq_window_scores", "wq_assign_bits", "wq_reorder_quantize", "wq_decode_attention"} <= names
     for n in sorted(names):
-        assert hasattr(lib, n), f"{n} declared in wq.h but not exported"
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
+    assert {"wq_decode_attention_static", "wq_validate_assignment", "wq_probe_stream", "wq_decode_times_us"} <= names
 
 
 def test_pure_size_helpers(lib):

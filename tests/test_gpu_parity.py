@@ -917,3 +917,38 @@ def test_adversarial_softmax(hd, g):
     o = H.run_oracle(bt, scores_override=sc, with_scores=False)
     assert g_run.ctx.device_status() == W.DEV_V_RANGE
     assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL
+
+
+@pytest.mark.gpu
+def test_device_side_validation_of_an_assignment():
+    """wq_reorder_quantize gathers whatever rows perm names; wq_validate_assignment is the debug check of tables that do not
+    come straight from wq_assign_bits: a permutation per sequence, class counts that add up.  Also: more windows than the
+    bound given to wq_assign_bits are reported, not silently dropped."""
+    H = _h()
+    from paper_2605_02262_amd import binding as W
+    bt = synth.batch(synth.workload(1), with_embeddings=False)
+    nw = int(bt.t.win_off[-1])
+    sc = np.random.default_rng(2).standard_normal(nw).astype(np.float32)
+    g = H.run_gpu(bt, splits=2, with_scores=False, scores_override=sc)
+    win_off = H.i32(bt.t.win_off)
+    W.wq_validate_assignment(g.ctx, win_off, nw, g.perm, g.seg)
+    assert g.ctx.device_status() == 0
+    bad = g.perm.clone()
+    bad[3] = bad[5]                                   # a window named twice, another one never
+    W.wq_validate_assignment(g.ctx, win_off, nw, bad, g.seg)
+    assert g.ctx.device_status() == W.DEV_BAD_ASSIGNMENT
+    bad = g.perm.clone()
+    bad[0] = nw                                       # out of range
+    W.wq_validate_assignment(g.ctx, win_off, nw, bad, g.seg)
+    assert g.ctx.device_status() == W.DEV_BAD_ASSIGNMENT
+    seg = g.seg.clone()
+    seg[0, 1] += 1                                    # counts that do not add up
+    W.wq_validate_assignment(g.ctx, win_off, nw, g.perm, seg)
+    assert g.ctx.device_status() == W.DEV_BAD_ASSIGNMENT
+    W.wq_validate_assignment(g.ctx, win_off, nw - 1, g.perm, g.seg)
+    assert g.ctx.device_status() == W.DEV_TOO_MANY_WINDOWS
+    # wq_assign_bits with a bound below the real count: reported, the windows inside the bound assigned as if they were all
+    bits, perm, seg = W.wq_assign_bits(g.ctx, torch.from_numpy(sc).cuda(), win_off, nw - 4, W.MODE_QUOTA, H.i32(bt.t.quota), None, 8, 1)
+    assert g.ctx.device_status() == W.DEV_TOO_MANY_WINDOWS
+    assert int(seg.sum().item()) == nw - 4
+    assert g.ctx.device_status() == 0
