@@ -12,9 +12,14 @@ caches and decodes from the one written longest ago; with 8 copies about 3 GB of
 write of a cache from its read.
 
 Prints ONE JSON line.  `value` is the decode-attention rate: algorithmic bytes of the packed cache divided
-by the mean duration of a decode call over back-to-back calls on rotated caches (HIP events on the launch
-stream).  The call is one kernel (it streams the cache and its last workgroups merge the splits), so the
+by the duration of a decode call: 10 warm-up calls, then 128 calls on rotated caches timed as 16 batches of 8
+back-to-back calls (HIP events on the launch stream around each batch); the median of the batch means, with
+p10/p90 next to it.  The call is one kernel (it streams the cache and its last workgroups merge the splits), so the
 roofline entry of that kernel is the same measurement; `streaming_only_us` is the kernel without the merge.
+The line also carries the 7B-shaped 28-layer decode loop (`decode_loop_cfg2`, one HIP graph replay per step).
+
+`--decode-only [--mix P8,P4]` times only the decode call (optionally with every sequence at the given bit mix): the
+command that the rocprofv3 counter summaries under profiles/ are made with.
 """
 from __future__ import annotations
 
@@ -31,6 +36,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 N_COPIES = 8
+DECODE_BATCHES, DECODE_PER_BATCH = 16, 8      # 128 timed decode calls
 
 
 def log(*a):
@@ -162,7 +168,7 @@ def decode_loop(args):
            "bytes_per_step": int(bytes_step), "pct_hbm_peak": round(100 * bytes_step / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 1),
            "launches_per_layer": 2 if args.separate_append else 1,
            "rows_appended_per_sequence": int(len16[0] - w.seqs[0].n_text), "device_status": status, "outputs_finite": finite}
-    print(json.dumps(res), flush=True)
+    return res
 
 
 def main():
@@ -176,7 +182,11 @@ def main():
     ap.add_argument("--separate-append", action="store_true",
                     help="with --decode-loop: wq_append_kv + wq_decode_attention per layer instead of the one-call step")
     ap.add_argument("--decode-loop", action="store_true",
-                    help="time the 28-layer decode loop of the 7B-shaped batch-8 workload (one step = one HIP graph replay)")
+                    help="only time the 28-layer decode loop of the 7B-shaped batch-8 workload (one step = one HIP graph replay)")
+    ap.add_argument("--no-decode-loop", action="store_true", help="leave the 28-layer decode loop out of the default run")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="only the decode call on rotated caches (prints its timing line); with --mix P8,P4 all sequences get that bit mix")
+    ap.add_argument("--mix", type=str, default="", help="with --decode-only: percentages of 8- and 4-bit windows, e.g. 0,0 = all 2-bit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -192,33 +202,42 @@ def main():
     if args.decode_loop:
         if args.steps == 40:
             args.steps = 128
-        return decode_loop(args)
+        print(json.dumps(decode_loop(args)), flush=True)
+        return
     torch.cuda.set_device(0)
     TD = {synth.F32: torch.float32, synth.BF16: torch.bfloat16, synth.F16: torch.float16}
 
     w = synth.workload(args.config)
+    if args.mix:
+        p8, p4 = [int(x) for x in args.mix.split(",")]
+        for sq in w.seqs:
+            sq.quota = synth.mix_to_quota(sq.n_win, p8, p4)
+        w.pin_first = 0
     t = synth.tables(w)
     B = w.B
     t0 = time.time()
     # ---- seeded synthetic inputs, resident in HBM before anything is timed ----------------------------------
     ev_parts, et_parts, k_parts, v_parts, q_parts = [], [], [], [], []
     for b in range(B):
-        et, ev = synth.embeddings(w, b)
+        if not args.decode_only:
+            et, ev = synth.embeddings(w, b)
+            ev_parts.append(torch.from_numpy(ev).to(TD[w.dtype]).cuda())
+            et_parts.append(torch.from_numpy(et).to(TD[w.dtype]).cuda())
+            del ev, et
         k, v = synth.keys_values(w, b)
         q_parts.append(synth.query(w, b, k))
-        ev_parts.append(torch.from_numpy(ev).to(TD[w.dtype]).cuda())
-        et_parts.append(torch.from_numpy(et).to(TD[w.dtype]).cuda())
         k_parts.append(torch.from_numpy(k).to(TD[w.dtype]).cuda())
         v_parts.append(torch.from_numpy(v).to(TD[w.dtype]).cuda())
         if b == 0:
             k0_host, v0_host = k, v
-        del ev, et, k, v
-    E_v, E_t = torch.cat(ev_parts), torch.cat(et_parts)
+        del k, v
+    if not args.decode_only:
+        E_v, E_t = torch.cat(ev_parts), torch.cat(et_parts)
     K, V = torch.cat(k_parts), torch.cat(v_parts)
     q_host = np.stack(q_parts)
     q = torch.from_numpy(q_host).to(TD[w.dtype]).cuda()
     del ev_parts, et_parts, k_parts, v_parts
-    log(f"[bench] inputs ready in {time.time() - t0:.1f}s: E_v {tuple(E_v.shape)}, K {tuple(K.shape)}")
+    log(f"[bench] inputs ready in {time.time() - t0:.1f}s: K {tuple(K.shape)}")
 
     i32 = lambda x: torch.as_tensor(np.ascontiguousarray(x, dtype=np.int32)).cuda()
     vis_off, txt_off, kv_off = i32(t.vis_off), i32(t.txt_off), i32(t.kv_off)
@@ -249,7 +268,10 @@ def main():
     scores = torch.empty(total_win, dtype=torch.float32, device="cuda")
 
     def prefill(pk):
-        W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
+        if args.decode_only:
+            scores.copy_(torch.rand(total_win, generator=torch.Generator(device="cuda").manual_seed(w.seed), device="cuda"))
+        else:
+            W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt, total_win, scores=scores)
         bits, perm, seg = W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first)
         W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, pk)
         return bits, perm, seg
@@ -279,6 +301,36 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / n
 
+    # ---- the decode call on rotated caches: 10 warm-up calls, then DECODE_BATCHES batches of DECODE_PER_BATCH back-to-back
+    #      calls, one pair of HIP events around each batch (a pair around every call would put several microseconds of
+    #      marker overhead into a kernel of under 30 us); median and spread over the batch means -----------------------
+    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo | by_length, out=out, lse=lse))
+
+    def decode_stats(algo):
+        for i in range(10):
+            dec(algo)(i)
+        means = np.array([timed(dec(algo), DECODE_PER_BATCH) for _ in range(DECODE_BATCHES)])
+        return {"median": float(np.median(means)), "p10": float(np.percentile(means, 10)), "p90": float(np.percentile(means, 90)),
+                "mean": float(means.mean()), "calls": DECODE_BATCHES * DECODE_PER_BATCH, "calls_per_event_pair": DECODE_PER_BATCH}
+
+    dstat = decode_stats(W.DECODE_AUTO)                                       # the whole call: one kernel
+    kstat = decode_stats(W.DECODE_AUTO | W.DECODE_PARTIALS_ONLY)             # ... without the merge of the splits
+    # the library's own ring of event pairs around the kernel of every call (includes the markers' overhead)
+    ctx.decode_timing(True)
+    for i in range(64):
+        dec(W.DECODE_AUTO)(i)
+    ring = np.array(ctx.decode_times_us(64))
+    ctx.decode_timing(False)
+    dec_us, kern_mean_us = dstat["median"], kstat["median"]
+    if args.decode_only:
+        alg_bytes = copies[0].bytes_algorithmic()
+        print(json.dumps({"workload": w.name, "mix_8_4": args.mix or "config", "splits": nsplit, "bytes": alg_bytes,
+                          "decode_us": {k: round(v, 2) for k, v in dstat.items()}, "kernel_without_merge_us": {k: round(v, 2) for k, v in kstat.items()},
+                          "GBs": round(alg_bytes / dec_us / 1e3, 1), "pct_hbm_peak": round(100 * alg_bytes / dec_us / 1e3 / HBM_PEAK_GBS, 1),
+                          "per_call_event_pairs_us": {"median": round(float(np.median(ring)), 2), "p10": round(float(np.percentile(ring, 10)), 2),
+                                                      "p90": round(float(np.percentile(ring, 90)), 2)}}), flush=True)
+        return
+
     # ---- the timed region: K passes of the whole hot path --------------------------------------------------
     for i in range(args.warmup):
         step(i)
@@ -287,14 +339,8 @@ def main():
     step_us = timed(lambda i: step(args.warmup + i), args.steps)
     wall = time.perf_counter() - t_start
 
-    # ---- its stages, each over the same number of back-to-back calls (a pair of events per call would add
-    #      several microseconds of marker overhead to a 30 us kernel) ---------------------------------------
+    # ---- the other stages, each over back-to-back calls -----------------------------------------------------
     n = max(args.steps, 2 * N_COPIES)
-    dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo | by_length, out=out, lse=lse))
-    for i in range(N_COPIES):
-        dec(W.DECODE_AUTO)(i)
-    dec_us = timed(dec(W.DECODE_AUTO), n)                                     # the whole call: one kernel
-    kern_mean_us = timed(dec(W.DECODE_AUTO | W.DECODE_PARTIALS_ONLY), n)     # ... without the merge of the splits
     sc_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
                                                total_win, scores=scores), n)
     scm_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
@@ -352,6 +398,10 @@ def main():
                    "window": w.seqs[0].win_size, "bit_mix_windows_8_4_2": list(map(int, w.seqs[0].quota)),
                    "splits": nsplit, "splits_by_length": bool(by_length), "kv_copies_rotated": N_COPIES, "calls_per_stage_timing": n},
         "decode_us_per_step": round(dec_us, 2),
+        "decode_us": {k: (round(v, 2) if isinstance(v, float) else v) for k, v in dstat.items()},
+        "decode_us_per_call_event_pairs": {"median": round(float(np.median(ring)), 2), "p10": round(float(np.percentile(ring, 10)), 2),
+                                           "p90": round(float(np.percentile(ring, 90)), 2), "calls": int(ring.size),
+                                           "note": "one HIP event pair per call around the kernel (wq_decode_times_us): includes the markers' overhead"},
         "pct_hbm_peak": round(100 * gbs / HBM_PEAK_GBS, 1),
         "stage_us": {"window_scores": round(float(st_mean[0]), 1), "assign_bits": round(float(st_mean[1]), 1),
                      "reorder_quantize": round(float(st_mean[2]), 1), "decode_attention": round(dec_us, 2)},
@@ -362,8 +412,12 @@ def main():
                                      "note": "unfused = wq_dequantize (packed -> 16-bit rows in HBM) + wq_decode_attention over those rows, per step"},
         "roofline": {"kernel": "k_decode_mfma<128>", "bound": "hbm", "achieved": round(kern_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kern_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic() if args.config == 3 else None, "algorithmic_bytes_per_launch": alg_bytes,
-                     "kernel_us": round(dec_us, 2), "streaming_only_us": round(kern_mean_us, 2)},
+                     "traffic": measured_traffic() if args.config == 3 else None,
+                     "traffic_source": "profiles/decode_attention_cfg3_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, committed; not re-measured in this run)",
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel_us": round(dec_us, 2), "kernel_us_p10_p90": [round(dstat["p10"], 2), round(dstat["p90"], 2)],
+                     "streaming_only_us": round(kern_mean_us, 2),
+                     "frac_of_stream_ceiling": round(kern_gbs / read_gbs, 4), "frac_of_plain_read": round(same_us / dec_us, 4)},
         "roofline_other": {
             "reorder_quantize": {"bound": "hbm", "unit": "GB/s",
                                  "achieved": round((total_rows * w.Hkv * w.hd * 2 * 2 + alg_bytes) / (st_mean[2] * 1e-6) / 1e9, 1)
@@ -419,6 +473,17 @@ def main():
                                "one_thread": {"value": round(bytes0 / dt1 / 1e9, 4), "seconds_per_pass": round(dt1, 3)},
                                "sample": f"decode attention of sequence 0 of {B} (all {w.Hq} heads, {rows0} tokens), fp64"}
         res["parity_max_rel_err_seq0"] = err
+    if not args.no_decode_loop:
+        # the 7B-shaped decoder loop (28 layers, batch 8, 128 steps in a HIP graph) as one more key of the line
+        del E_v, E_t, K, V, copies, out
+        torch.cuda.empty_cache()
+        la = argparse.Namespace(**vars(args))
+        la.steps, la.warmup, la.splits, la.separate_append = 128, 8, 0, False
+        lp = decode_loop(la)
+        res["decode_loop_cfg2"] = {k: lp[k] for k in ("us_per_step_graph", "us_per_layer", "us_per_step_eager", "bytes_per_step", "pct_hbm_peak",
+                                                      "launches_per_layer", "rows_appended_per_sequence", "device_status", "outputs_finite")}
+        res["decode_loop_cfg2"].update({"GBs": lp["value"], "workload": lp["config"]["workload"], "steps": lp["steps"], "splits": lp["config"]["splits"]})
+
     print(json.dumps(res), flush=True)
 
 
