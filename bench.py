@@ -187,6 +187,8 @@ def main():
     ap.add_argument("--decode-only", action="store_true",
                     help="only the decode call on rotated caches (prints its timing line); with --mix P8,P4 all sequences get that bit mix")
     ap.add_argument("--mix", type=str, default="", help="with --decode-only: percentages of 8- and 4-bit windows, e.g. 0,0 = all 2-bit")
+    ap.add_argument("--frames", type=int, default=0,
+                    help="with --decode-only: every sequence gets this many video frames (the bit mix keeps its percentages): decode time against cache size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -208,11 +210,18 @@ def main():
     TD = {synth.F32: torch.float32, synth.BF16: torch.bfloat16, synth.F16: torch.float16}
 
     w = synth.workload(args.config)
-    if args.mix:
-        p8, p4 = [int(x) for x in args.mix.split(",")]
+    if args.frames and not args.decode_only:
+        raise SystemExit("bench.py: --frames goes with --decode-only")
+    if args.mix or args.frames:
         for sq in w.seqs:
+            if args.mix:
+                p8, p4 = [int(x) for x in args.mix.split(",")]
+            else:
+                p8, p4 = round(100 * sq.quota[0] / sq.n_win), round(100 * sq.quota[1] / sq.n_win)
+            if args.frames:
+                sq.frames = args.frames
             sq.quota = synth.mix_to_quota(sq.n_win, p8, p4)
-        w.pin_first = 0
+        w.pin_first = 0                     # (a pinned first window would not fit a mix without 8-bit windows)
     t = synth.tables(w)
     B = w.B
     t0 = time.time()
@@ -324,7 +333,8 @@ def main():
     dec_us, kern_mean_us = dstat["median"], kstat["median"]
     if args.decode_only:
         alg_bytes = copies[0].bytes_algorithmic()
-        print(json.dumps({"workload": w.name, "mix_8_4": args.mix or "config", "splits": nsplit, "bytes": alg_bytes,
+        print(json.dumps({"workload": w.name, "mix_8_4": args.mix or "config", "frames_per_sequence": w.seqs[0].frames,
+                          "tokens_per_sequence": max_tok, "splits": nsplit, "bytes": alg_bytes,
                           "decode_us": {k: round(v, 2) for k, v in dstat.items()}, "kernel_without_merge_us": {k: round(v, 2) for k, v in kstat.items()},
                           "GBs": round(alg_bytes / dec_us / 1e3, 1), "pct_hbm_peak": round(100 * alg_bytes / dec_us / 1e3 / HBM_PEAK_GBS, 1),
                           "per_call_event_pairs_us": {"median": round(float(np.median(ring)), 2), "p10": round(float(np.percentile(ring, 10)), 2),

@@ -308,7 +308,8 @@ static int check_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, 
     if (*num_splits == 0) {
         *num_splits = wq_auto_splits(B, kv->Hkv, max_seq_tokens);
         if (by_length) {    // more splits (the caches' capacities stand in for the tokens), if the workspace has room for them
-            const int more = wq_auto_splits_ragged(B, kv->Hkv, max_seq_tokens, kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16);
+            int more = wq_auto_splits_ragged(B, kv->Hkv, max_seq_tokens, kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16);
+            if (more > WQ_MAX_FUSED_SPLITS) more = WQ_MAX_FUSED_SPLITS;    // (splits by length need the merge inside the kernel)
             if (more > *num_splits && ctx->ws_bytes >= WQ_WS_HEADER + wq_decode_ws_bytes(B, Hq, kv->hd, more)) *num_splits = more;
         }
     }

@@ -28,7 +28,6 @@ struct DecodeArgs {
     int fused;              // the matrix-core kernel merges the splits itself (last workgroup per (b, KV head))
     unsigned* arrive;       // [B*Hkv] arrival counters, WQ_ARRIVE_STRIDE words apart, zero between launches
     int fixed_shares;       // every wavefront of the matrix-core kernel gets a fixed share of its workgroup's range
-    float wgt[4], inv_wgt[4];   // cost of one 32-token block of the 2-, 4-, 8- and 16-bit class, relative to each other
     wq_packed_kv kv;
     float* part;            // [B][Hkv][nparts][rep][hd + 2]
     float* out;
@@ -43,17 +42,54 @@ struct DecodeArgs {
 #endif
 };
 
-// One wavefront turns the m_s of n splits (in w) into the weights e^{m_s - M} in place and returns M and the sum of l_s
-// times the weights.  The sums are taken in one fixed order (lane i takes the splits i, i + 64, ..., then a butterfly
-// over the lanes).  Both merges (the one inside the matrix-core kernel and k_combine) go through this function and sum
-// the numerators in split order, which is why their results agree bit for bit.
+// ---- the weights of the splits -----------------------------------------------------------------------------
+// Reductions over the 64 lanes of a wavefront in a fixed order: four rotations inside the rows of 16 lanes (one
+// data-parallel-primitive instruction each, no LDS), then the four rows' results as scalars.
+template <int CTRL>
+__device__ __forceinline__ float lanes_moved(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_value(float x, int l)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = fmaxf(x, lanes_moved<0x128>(x));           // row_ror:8, 4, 2, 1
+    x = fmaxf(x, lanes_moved<0x124>(x));
+    x = fmaxf(x, lanes_moved<0x122>(x));
+    x = fmaxf(x, lanes_moved<0x121>(x));
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
+}
+__device__ __forceinline__ float wave_sum(float x)
+{
+    x += lanes_moved<0x128>(x);
+    x += lanes_moved<0x124>(x);
+    x += lanes_moved<0x122>(x);
+    x += lanes_moved<0x121>(x);
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
+}
+
+// Up to 64 splits, one per lane: lane s holds m_s (-inf beyond the last split) and l_s; it gets its weight
+// w_s = e^{m_s - M}, and every lane M = max m_s and L = sum l_s w_s.  Both merges (the one inside the matrix-core
+// kernel and k_combine) go through this function when there are at most 64 splits and then sum the numerators in
+// split order, which is why their results agree bit for bit.
+__device__ __forceinline__ void merge_weights_lanes(float m, float l, float& w, float& M, float& L)
+{
+    M = wave_max(m);
+    w = (m == -INFINITY) ? 0.f : __expf(m - M);
+    L = wave_sum(l * w);
+}
+
+// More than 64 splits (k_combine only): one wavefront turns the m_s of n splits (in w) into the weights in place and
+// returns M and L.  Lane i takes the splits i, i + 64, ..., then the lanes are reduced as above.
 __device__ __forceinline__ void merge_weights(float* w, const float* l, int n, float& M, float& L)
 {
     const int lane = threadIdx.x & 63;
     float mx = -INFINITY;
     for (int s = lane; s < n; s += 64) mx = fmaxf(mx, w[s]);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    mx = wave_max(mx);
     float sum = 0.f;
     for (int s = lane; s < n; s += 64) {
         const float ms = w[s];
@@ -61,10 +97,8 @@ __device__ __forceinline__ void merge_weights(float* w, const float* l, int n, f
         w[s] = e;
         sum = fmaf(l[s], e, sum);
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
     M = mx;
-    L = sum;
+    L = wave_sum(sum);
 }
 
 __device__ __forceinline__ float load_q(const void* q, int dtype, int64_t i)
@@ -352,7 +386,13 @@ __global__ __launch_bounds__(128) void k_combine(const float* __restrict__ part,
     __syncthreads();
     if (tid < 64) {
         float M, L;
-        merge_weights(s_w, s_l, nparts, M, L);
+        if (nparts <= 64) {
+            float w;
+            merge_weights_lanes(tid < nparts ? s_w[tid] : -INFINITY, tid < nparts ? s_l[tid] : 0.f, w, M, L);
+            if (tid < nparts) s_w[tid] = w;
+        } else {
+            merge_weights(s_w, s_l, nparts, M, L);
+        }
         if (tid == 0) {
             s_red[0] = M;
             s_red[1] = L;
@@ -403,8 +443,8 @@ bool wq_decode_can_append(int q_dtype, int B, int Hq, const wq_packed_kv* kv, in
     const bool use_mfma = (balgo == WQ_DECODE_MFMA) || (balgo == WQ_DECODE_AUTO && kv->hd / kv->group == 2);
     const bool mfma16 = use_mfma && !(kv->dtype16 == WQ_BF16 && q_dtype != WQ_BF16);
     const int rep = Hq / kv->Hkv;
-    return mfma16 && new_dtype == kv->dtype16 && (int64_t)B * kv->Hkv + B <= WQ_MAX_ARRIVE &&
-           2 * num_splits * rep <= WQ_WAVES * WQ_MAX_REP * kv->hd;
+    return mfma16 && new_dtype == kv->dtype16 && (int64_t)B * kv->Hkv + B <= WQ_MAX_ARRIVE && num_splits <= WQ_MAX_FUSED_SPLITS &&
+           rep <= WQ_MAX_REP;
 }
 
 int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv, float sm_scale,
@@ -433,13 +473,12 @@ int wq_launch_decode(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, con
     a.fixed_shares = fixed_shares;
     a.arrive = reinterpret_cast<unsigned*>(ctx->ws + 256);
     // one launch does it all when the matrix-core kernel walks every segment, the counters fit the workspace
-    // header and the splits' weights fit the merge buffer in LDS
+    // header and a wavefront's lanes hold the splits' weights
     a.fused = a.use_mfma && a.mfma16 && !partials_only && !separate_merge && (int64_t)B * kv->Hkv <= WQ_MAX_ARRIVE &&
-              2 * a.nparts * a.rep <= WQ_WAVES * WQ_MAX_REP * kv->hd;
-    for (int c = 0; c < 4; c++) {
-        a.wgt[c] = (float)WQ_BLOCK_COST[c];
-        a.inv_wgt[c] = 1.0f / a.wgt[c];
-    }
+              a.nparts <= WQ_MAX_FUSED_SPLITS;
+    // the shares of the token axis are cut on a 32-bit cost axis (at most 500 per 32-token block)
+    if (a.use_mfma && (int64_t)kv->cap[0] + kv->cap[1] + kv->cap[2] + kv->cap16 > ((int64_t)1 << 27))
+        return wq_fail(ctx, WQ_ERR_UNSUPPORTED, "the matrix-core decode kernel takes caches of up to 2^27 token slots");
     a.part = reinterpret_cast<float*>(ctx->ws + WQ_WS_HEADER);
     a.out = out;
     a.k_new = static_cast<const uint16_t*>(k_new);

@@ -760,14 +760,75 @@ __device__ __forceinline__ void finish_append(const DecodeArgs& a, int b, int kv
     if (new_row >= 0) a.kv.len16[b] = new_row + 1;
 }
 
-// Shares are laid out on a cost axis in float arithmetic: every wavefront evaluates the same expressions for the
-// same boundary, so neighbouring shares meet exactly whatever the rounding, and a division-free float mapping is
-// monotone, which is all that the partition needs.
-// first block of a class (n blocks of cost w each, starting at cost `base`) at or after cost x
-__device__ __forceinline__ int range_edge(float x, float base, float inv_w, int n)
+// Shares are laid out on a cost axis in integers (a 32-token block of a class costs WQ_BLOCK_COST of it): everything
+// here depends only on the sequence's tables and the workgroup's and wavefront's numbers, which are the same for all
+// lanes, so the compiler keeps it in scalar registers and on the scalar unit, where it does not compete with the vector
+// work of the wavefront that shares the SIMD (as float arithmetic on the vector unit it held every wavefront's first
+// loads back by most of a microsecond).  Every wavefront evaluates the same expressions for the same boundary, so
+// neighbouring shares meet exactly, and the mapping is monotone, which is all that the partition needs.
+// first block of a class (n blocks of cost W each, starting at cost `base`) at or after cost x
+template <unsigned W>
+__device__ __forceinline__ int range_edge(unsigned x, unsigned base, int n)
 {
-    return (int)fminf(fmaxf(ceilf((x - base) * inv_w), 0.f), (float)n);      // no branches: every wavefront runs this before its first load
+    const unsigned e = x > base ? (x - base + (W - 1u)) / W : 0u;             // (division by a constant: a multiplication)
+    return (int)min(e, (unsigned)n);
 }
+
+__device__ __forceinline__ int range_edge_of(int c, unsigned x, unsigned base, int n)
+{
+    return c == 0 ? range_edge<(unsigned)WQ_BLOCK_COST[0]>(x, base, n)
+         : c == 1 ? range_edge<(unsigned)WQ_BLOCK_COST[1]>(x, base, n)
+         : c == 2 ? range_edge<(unsigned)WQ_BLOCK_COST[2]>(x, base, n)
+                  : range_edge<(unsigned)WQ_BLOCK_COST[3]>(x, base, n);
+}
+
+// ---- helpers of the two merges --------------------------------------------------------------------------------
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+template <int N> struct FloatN;
+template <> struct FloatN<1> { typedef float type; };
+template <> struct FloatN<2> { typedef floatx2 type; };
+template <int N> __device__ __forceinline__ float part_elem(typename FloatN<N>::type v, int c);
+template <> __device__ __forceinline__ float part_elem<1>(float v, int) { return v; }
+template <> __device__ __forceinline__ float part_elem<2>(floatx2 v, int c) { return v[c]; }
+
+// N floats (N * 4 bytes, aligned to that) to memory with a device-scope store (one instruction)
+template <int N>
+__device__ __forceinline__ void store_through(float* p, const float* v)
+{
+    if constexpr (N == 1) {
+        __hip_atomic_store(p, v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        static_assert(N == 2, "one or two floats");
+        const unsigned long long u = (unsigned long long)__float_as_uint(v[0]) | ((unsigned long long)__float_as_uint(v[1]) << 32);
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void store_plain(float* p, const float* v)
+{
+    if constexpr (N == 1) {
+        p[0] = v[0];
+    } else {
+        static_assert(N == 2, "one or two floats");
+        *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+    }
+}
+
+// N floats of a partial through a buffer descriptor, with a device-scope load (does not stop at a cache); zero
+// when the offset is beyond the descriptor's range
+template <int N>
+__device__ __forceinline__ typename FloatN<N>::type ld_part(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off)
+{
+    constexpr int DEVICE_SCOPE = 16;               // the sc1 bit of the instruction
+    if constexpr (N == 1) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)byte_off, 0, DEVICE_SCOPE));
+    } else {
+        static_assert(N == 2, "one or two floats");
+        return __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)byte_off, 0, DEVICE_SCOPE));
+    }
+}
+
 
 template <int HD>
 __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
@@ -847,26 +908,28 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #pragma unroll
         for (int c = 0; c < 3; c++) nb[c] = (cls_len[c] + 31) >> 5;
         nb[3] = a.mfma16 ? (cls_len[3] + 31) >> 5 : 0;
-        float total = 0.f;
+        unsigned total = 0u;
 #pragma unroll
-        for (int c = 0; c < 4; c++) total += (float)nb[c] * a.wgt[c];
-        const float rS = 1.0f / (float)S;
-        // the workgroup's range [G0, G1): the first one starts at cost 0 (every class's edge is then block 0), the last one
-        // ends behind everything, whatever the rounding
-        const float G0 = total * ((float)split * rS), G1 = split == S - 1 ? 3.0e38f : total * ((float)(split + 1) * rS);
-        float base = 0.f;
+        for (int c = 0; c < 4; c++) total += (unsigned)nb[c] * (unsigned)WQ_BLOCK_COST[c];
+        // cost at which split x starts: floor(total * x / S) up to rounding (one reciprocal, the same bits in every
+        // wavefront of the launch); split 0 starts at cost 0, the last one ends behind everything
+        const float rS = __builtin_amdgcn_rcpf((float)S);
+        const unsigned G0 = split == 0 ? 0u
+                                       : min(total, (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((float)total * ((float)split * rS))));
+        const unsigned G1 = split == S - 1 ? total
+                                           : min(total, (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((float)total * ((float)(split + 1) * rS))));
+        unsigned base = 0u;
         unsigned t = 0;
 #pragma unroll
         for (int c = 3; c >= 0; c--) {
-            const float iw = a.inv_wgt[c];
-            const int e0 = range_edge(G0, base, iw, nb[c]);
-            const int e1 = range_edge(G1, base, iw, nb[c]);
+            const int e0 = range_edge_of(c, G0, base, nb[c]);
+            const int e1 = range_edge_of(c, G1, base, nb[c]);
             if (a.fixed_shares) {                  // the range is divided among the wavefronts by cost; no pool
-                const float rnw = 1.0f / (float)WQ_WAVES;
-                const float Ge = split == S - 1 ? total : G1;
-                const float x0 = G0 + (Ge - G0) * ((float)wave * rnw), x1 = G0 + (Ge - G0) * ((float)(wave + 1) * rnw);
-                src[c].cur = wave == 0 ? e0 : range_edge(x0, base, iw, nb[c]);
-                src[c].end = wave == WQ_WAVES - 1 ? e1 : range_edge(x1, base, iw, nb[c]);
+                const unsigned long long span = G1 - G0;
+                const unsigned x0 = G0 + (unsigned)((span * (unsigned)wave) >> 3), x1 = G0 + (unsigned)((span * (unsigned)(wave + 1)) >> 3);
+                static_assert(WQ_WAVES == 8, "the shift above");
+                src[c].cur = wave == 0 ? e0 : range_edge_of(c, x0, base, nb[c]);
+                src[c].end = wave == WQ_WAVES - 1 ? e1 : range_edge_of(c, x1, base, nb[c]);
                 src[c].pool_first = e1;
                 src[c].tk_lo = src[c].tk_hi = t;
             } else {                               // the whole range is the pool
@@ -876,7 +939,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
                 t += (unsigned)(e1 - e0);
                 src[c].tk_hi = t;
             }
-            base += (float)nb[c] * a.wgt[c];
+            base += (unsigned)nb[c] * (unsigned)WQ_BLOCK_COST[c];
         }
     }
 
@@ -936,29 +999,36 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     pass_setup_barrier(tk);
     __syncthreads();
-    // ---- merge the wavefronts, write the partial (m in natural-log units) ----
+    // ---- merge the wavefronts, write the partial (m in natural-log units): wavefront r takes head r, a lane CPL
+    //      neighbouring channels, so the eight scales of a head are computed once per lane ----
+    constexpr int CPL = HD / 64;                   // channels per lane
+    static_assert(WQ_WAVES >= WQ_MAX_REP, "one wavefront per head");
     const int64_t pstride = (int64_t)a.rep * (HD + 2);
     float* pbase = a.part + ((int64_t)unit * a.nparts) * pstride;
-    float* out = pbase + split * pstride;
-    for (int idx = tid; idx < a.rep * HD; idx += 64 * WQ_WAVES) {
-        const int r = idx / HD, ch = idx - r * HD;
-        float M = sm.ml[0][r][0];
+    if (wave < a.rep) {
+        float* out = pbase + split * pstride + wave * (HD + 2);
+        float mw[WQ_WAVES];
 #pragma unroll
-        for (int w = 1; w < WQ_WAVES; w++) M = fmaxf(M, sm.ml[w][r][0]);
-        float num = 0.f, L = 0.f;
+        for (int w = 0; w < WQ_WAVES; w++) mw[w] = sm.ml[w][wave][0];
+        float M = mw[0];
+#pragma unroll
+        for (int w = 1; w < WQ_WAVES; w++) M = fmaxf(M, mw[w]);
+        float num[CPL], L = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL; c++) num[c] = 0.f;
 #pragma unroll
         for (int w = 0; w < WQ_WAVES; w++) {
-            const float mw = sm.ml[w][r][0];
-            const float s = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-            num = fmaf(sm.O[w][r][ch], s, num);
-            L = fmaf(sm.ml[w][r][1], s, L);
+            const float sc = (mw[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw[w] - M);
+#pragma unroll
+            for (int c = 0; c < CPL; c++) num[c] = fmaf(sm.O[w][wave][CPL * lane + c], sc, num[c]);
+            L = fmaf(sm.ml[w][wave][1], sc, L);
         }
         // device-scope stores go through to memory (every XCD has an L2 of its own), so that no cache write-back
         // is needed to hand the partial to the workgroup that merges the splits
-        __hip_atomic_store(out + r * (HD + 2) + ch, num, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (ch == 0) {
-            __hip_atomic_store(out + r * (HD + 2) + HD, M * 0.6931471805599453f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(out + r * (HD + 2) + HD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_through<CPL>(out + CPL * lane, num);
+        if (lane == 0) {
+            const float ml2[2] = {M * 0.6931471805599453f, L};
+            store_through<2>(out + HD, ml2);
         }
     }
     WQ_STAMP(5);
@@ -973,64 +1043,57 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
+    WQ_STAMP(56);
     if (tid == 0) {
         const unsigned old = __hip_atomic_fetch_add(a.arrive + unit * WQ_ARRIVE_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sm.last = old == (unsigned)S - 1u;
     }
     __syncthreads();
+    WQ_STAMP(57);
     if (!sm.last) {
         finish_append(a, b, kvh, split, new_row);
         return;
     }
     if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-    const int np = S;                              // (the splits are all the partials there are in a launch that merges them itself)
-    float* wts = &sm.O[0][0][0];                   // [rep][np]: m_s, then the weights e^{m_s - M}
-    float* lsum = wts + a.rep * np;                // [rep][np]: l_s
-    // all loads first (one round trip): this thread's channels of the first PRE splits, then the (m, l) pairs
-    constexpr int PRE = 16, PER = (WQ_MAX_REP * HD + 64 * WQ_WAVES - 1) / (64 * WQ_WAVES);
-    float pre[PER][PRE];
+    // What follows runs once per (b, kvh) while the rest of the chip waits, and a wavefront's vector instruction takes
+    // four cycles: every instruction counts.  Wavefront r merges head r on its own: lane s holds (m, l) of split s (the
+    // launch takes this path with at most 64 splits), the weights come from reductions inside the wavefront, lane s's
+    // weight is read back as a scalar for the sum over the splits; no LDS, no barrier.  The partials are read through
+    // a buffer descriptor, whose range check returns zero beyond the last split.
+    if (wave < a.rep) {
+        const int np = S;                          // (the splits are all the partials there are in a launch that merges them itself)
+        const unsigned pbytes = (unsigned)pstride * 4u;
+        const __amdgpu_buffer_rsrc_t parts = __builtin_amdgcn_make_buffer_rsrc(pbase, 0, np * (int)pbytes, 0x00020000);
+        const unsigned row = (unsigned)(wave * (HD + 2)) * 4u;
+        const floatx2 ml = ld_part<2>(parts, (unsigned)lane * pbytes + row + HD * 4u);
+        const float m_s = lane < np ? ml[0] : -INFINITY, l_s = ml[1];
+        float w_s = 0.f, M = -INFINITY, L = 0.f;
+        float acc[CPL];
 #pragma unroll
-    for (int u = 0; u < PER; u++) {
-        const int idx = tid + u * 64 * WQ_WAVES;
-        const int r = idx / HD, ch = idx - r * HD;
+        for (int c = 0; c < CPL; c++) acc[c] = 0.f;
+        const unsigned chan = row + (unsigned)lane * (CPL * 4u);
+#pragma unroll 1
+        for (int k0 = 0; k0 < np; k0 += 16) {      // 16 splits at a time: their loads are in flight together
+            typename FloatN<CPL>::type pre[16];
 #pragma unroll
-        for (int k = 0; k < PRE; k++)
-            pre[u][k] = (idx < a.rep * HD && k < np)
-                            ? __hip_atomic_load(pbase + (int64_t)k * pstride + r * (HD + 2) + ch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                            : 0.f;
-    }
-    for (int idx = tid; idx < a.rep * np; idx += 64 * WQ_WAVES) {
-        const int r = idx / np, s = idx - r * np;
-        const float* src = pbase + s * pstride + r * (HD + 2) + HD;
-        wts[idx] = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        lsum[idx] = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (wave < a.rep) {                            // head `wave`: largest m, weights and denominator, the same way as the merge kernel
-        static_assert(WQ_WAVES >= WQ_MAX_REP, "one wavefront per head");
-        float M, L;
-        merge_weights(wts + wave * np, lsum + wave * np, np, M, L);
-        if (lane == 0) {
-            sm.ml[0][wave][0] = M;
-            sm.ml[0][wave][1] = L;
+            for (int k = 0; k < 16; k++) pre[k] = ld_part<CPL>(parts, chan + (unsigned)(k0 + k) * pbytes);
+            if (k0 == 0) merge_weights_lanes(m_s, l_s, w_s, M, L);
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_s), k0 + k));   // 0 beyond the last split
+#pragma unroll
+                for (int c = 0; c < CPL; c++) acc[c] = fmaf(part_elem<CPL>(pre[k], c), wk, acc[c]);
+            }
         }
-    }
-    __syncthreads();
+        WQ_STAMP(58);
+        const int hq = kvh * a.rep + wave;
+        float o[CPL];
 #pragma unroll
-    for (int u = 0; u < PER; u++) {
-        const int idx = tid + u * 64 * WQ_WAVES;
-        if (idx >= a.rep * HD) break;
-        const int r = idx / HD, ch = idx - r * HD;
-        const float* src = pbase + r * (HD + 2) + ch;
-        float acc = 0.f;
-#pragma unroll
-        for (int k = 0; k < PRE; k++) acc = fmaf(pre[u][k], k < np ? wts[r * np + k] : 0.f, acc);
-        for (int s = PRE; s < np; s++) acc = fmaf(__hip_atomic_load(src + (int64_t)s * pstride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wts[r * np + s], acc);
-        const float L = sm.ml[0][r][1];
-        const int hq = kvh * a.rep + r;
-        a.out[((int64_t)b * a.Hq + hq) * HD + ch] = L > 0.f ? acc / L : 0.f;
-        if (a.lse && ch == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? sm.ml[0][r][0] + logf(L) : -INFINITY;
+        for (int c = 0; c < CPL; c++) o[c] = L > 0.f ? acc[c] / L : 0.f;
+        store_plain<CPL>(a.out + ((int64_t)b * a.Hq + hq) * HD + CPL * lane, o);
+        if (a.lse && lane == 0) a.lse[(int64_t)b * a.Hq + hq] = L > 0.f ? M + logf(L) : -INFINITY;
     }
+    WQ_STAMP(59);
     finish_append(a, b, kvh, split, new_row);
 }
 

@@ -27,6 +27,7 @@ constexpr int WQ_MAX_ARRIVE = (16384 - 256) / (4 * WQ_ARRIVE_STRIDE);
 constexpr int WQ_DECODE_FLAGS = WQ_DECODE_PARTIALS_ONLY | WQ_DECODE_FIXED_SHARES | WQ_DECODE_BY_LENGTH | WQ_DECODE_SEPARATE_MERGE;
 constexpr int WQ_TIMING_RING = 64;
 constexpr int WQ_MAX_REP = 8;          // query heads per KV head
+constexpr int WQ_MAX_FUSED_SPLITS = 64; // splits that the decode kernel merges itself (one per lane of a wavefront)
 // wall time of one 32-token block of the 2-, 4-, 8- and 16-bit class in the decode kernel, relative to each other
 // (measured on MI355X with the whole chip streaming): the fixed shares of the token axis are balanced by it
 constexpr int WQ_BLOCK_COST[4] = {100, 130, 230, 500};
