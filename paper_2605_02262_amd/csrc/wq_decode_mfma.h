@@ -201,6 +201,35 @@ struct MfmaSmem {
 };
 
 
+// ---- a lane's value next to that of lane ^ 16 and of lane ^ 32 -------------------------------------------------
+// The row-swap instructions exchange rows of 16 lanes between two registers: given the same value x twice, the first
+// register comes back holding the even row of every pair of rows in both of them (the lower half of the wavefront in
+// both halves, for the 32-lane form), the second one the odd row (the upper half).  No LDS, no waiting.
+struct RowPair { float even, odd; };
+__device__ __forceinline__ RowPair rows_16(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return RowPair{__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ RowPair halves_32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return RowPair{__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+// sum / maximum over the four lanes {l, l ^ 16, l ^ 32, l ^ 48}, in every one of them
+__device__ __forceinline__ float sum_over_rows(float x)
+{
+    const RowPair a = rows_16(x);
+    const RowPair b = halves_32(a.even + a.odd);
+    return b.even + b.odd;
+}
+__device__ __forceinline__ float max_over_rows(float x)
+{
+    const RowPair a = rows_16(x);
+    const RowPair b = halves_32(fmaxf(a.even, a.odd));
+    return fmaxf(b.even, b.odd);
+}
+
 // ---- the query operands of one class, built by the wavefront itself -------------------------------------------
 // Lane (j, (g,h)) loads its quarter j of head h's query straight from global memory (hd/4 values), the head's
 // largest magnitude is found with two cross-lane exchanges, the query is scaled by a power of two into [-1, 1)
@@ -236,8 +265,7 @@ __device__ __forceinline__ void build_q_operands(const DecodeArgs& a, int b, int
         if (!live) v[k] = 0.f;
         mx = fmaxf(mx, fabsf(v[k]));
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = max_over_rows(mx);
     const int eb = (int)((__float_as_uint(mx) >> 23) & 0xFFu);              // biased exponent of the largest |q|
     const bool ok = eb > 0 && eb < 253;                                       // zero, denormal or non-finite: leave as is
     const float dn = ok ? __uint_as_float((uint32_t)(253 - eb) << 23) : 1.0f;     // 2^-(eb-126): max |q| lands in [0.5, 1)
@@ -245,8 +273,10 @@ __device__ __forceinline__ void build_q_operands(const DecodeArgs& a, int b, int
     float s = 0.f;
 #pragma unroll
     for (int k = 0; k < QC; k++) s += (float)(_Float16)(v[k] * dn);
-    const float pair = s + __shfl_xor(s, 16, 64);                            // both quarters of group j/2
-    const float other = __shfl_xor(pair, 32, 64);
+    const RowPair quarters = rows_16(s);
+    const float pair = quarters.even + quarters.odd;                         // both quarters of group j/2
+    const RowPair groups = halves_32(pair);
+    const float other = (lane & 32) ? groups.even : groups.odd;
     const bool mine = (j >> 1) == g;
     qsum = mine ? pair : other;
     qexp = raw_bf16 ? 1.0f : up;
@@ -508,8 +538,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
         float lm = max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
         lm *= cexp;                                // cexp > 0
         if (__builtin_amdgcn_ballot_w64(lm > st.m + WQ_MAX_SLACK) != 0) {
-            lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
-            lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
+            lm = max_over_rows(lm);
             const float mn = fmaxf(st.m, lm);
             const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);   // 0 on the first block
             st.m = mn;
@@ -650,8 +679,7 @@ __device__ __forceinline__ void walk_seg16_mfma(const DecodeArgs& a, MfmaSmem<HD
         float lm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         lm *= cexp;
         if (__builtin_amdgcn_ballot_w64(lm > st.m + WQ_MAX_SLACK) != 0) {
-            lm = fmaxf(lm, __shfl_xor(lm, 16, 64));
-            lm = fmaxf(lm, __shfl_xor(lm, 32, 64));
+            lm = max_over_rows(lm);
             const float mn = fmaxf(st.m, lm);
             const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - mn);
             st.m = mn;
@@ -982,10 +1010,8 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
 #endif
     // ---- reduce the lane groups' shares, hand the wave's numerators to LDS ----
     float l = st.l, am = st.accM;
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    am += __shfl_xor(am, 16, 64);
-    am += __shfl_xor(am, 32, 64);
+    l = sum_over_rows(l);
+    am = sum_over_rows(am);
 #pragma unroll
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct

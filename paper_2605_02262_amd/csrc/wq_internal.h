@@ -30,7 +30,10 @@ constexpr int WQ_MAX_REP = 8;          // query heads per KV head
 constexpr int WQ_MAX_FUSED_SPLITS = 64; // splits that the decode kernel merges itself (one per lane of a wavefront)
 // wall time of one 32-token block of the 2-, 4-, 8- and 16-bit class in the decode kernel, relative to each other
 // (measured on MI355X with the whole chip streaming): the fixed shares of the token axis are balanced by it
-constexpr int WQ_BLOCK_COST[4] = {100, 130, 230, 500};
+#ifndef WQ_COSTS
+#define WQ_COSTS 100, 130, 230, 500
+#endif
+constexpr int WQ_BLOCK_COST[4] = {WQ_COSTS};
 constexpr float WQ_MAX_V_SCALE = 16.0f; // largest scale of a value group that the decode kernel's fp16 weights are laid out for
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 
