@@ -86,7 +86,8 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
  * itself (the launches that can also append); elsewhere every sequence uses all splits.                              */
 #define WQ_DECODE_BY_LENGTH 0x400
 /* or-ed into algo: the splits are merged by a second kernel instead of by the decode kernel's last workgroup per
- * (sequence, KV head) (what the library does by itself when a launch's split count is too large for the in-kernel merge).
+ * (sequence, KV head) (what the library does by itself when a launch has more than 64 splits: the in-kernel merge holds
+ * one split per lane of a wavefront).
  * Both merges do the same arithmetic in the same order: with WQ_DECODE_FIXED_SHARES their results agree bit for bit.   */
 #define WQ_DECODE_SEPARATE_MERGE 0x800
 
@@ -226,8 +227,8 @@ int wq_append_kv(wq_ctx* ctx, const void* k_new, const void* v_new, int dtype, i
 /* ---- a decode step in one call (Sec. 2.2): append the generated token's keys and values, then attend over the
  * cache that now includes them.  Same arguments and results as wq_append_kv(k_new, v_new, new_dtype) followed by
  * wq_decode_attention(...).  When the matrix-core kernel handles the whole launch (what WQ_DECODE_AUTO picks for
- * hd/group == 2 with a query of the cache's 16-bit type family) and k_new, v_new have the cache's own 16-bit type, it is
- * ONE kernel launch: the new row is read from k_new / v_new by the workgroup that walks its block, copied into the cache
+ * hd/group == 2 with a query of the cache's 16-bit type family), k_new, v_new have the cache's own 16-bit type and there
+ * are at most 64 splits, it is ONE kernel launch: the new row is read from k_new / v_new by the workgroup that walks its block, copied into the cache
  * by another, and len16[b] is raised by the sequence's last workgroup to finish; otherwise the two launches are made.
  * A sequence whose 16-bit segment is full is attended without the new token and raises WQ_DEV_SEG16_OVERFLOW.
  * WQ_DECODE_PARTIALS_ONLY is not accepted here.                                                                  */
@@ -257,8 +258,9 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
  * bound on tokens of any one sequence (used by the automatic split and by WQ_DECODE_BY_LENGTH; a wrong value costs speed,
  * not correctness).  algo: WQ_DECODE_AUTO picks the
  * matrix-core kernel when hd/group == 2, else the generic one.  Limits (WQ_ERR_UNSUPPORTED beyond them): Hq a
- * multiple of Hkv with at most 8 query heads per KV head, hd 64 or 128, group 32, 64 or 128, B at most 65535;
- * num_splits above 1024 is WQ_ERR_ARG.
+ * multiple of Hkv with at most 8 query heads per KV head, hd 64 or 128, group 32, 64 or 128, B at most 65535, and for
+ * the matrix-core kernel at most 2^27 token slots in the cache (cap[0] + cap[1] + cap[2] + cap16: it cuts the workgroups'
+ * shares on a 32-bit cost axis); num_splits above 1024 is WQ_ERR_ARG.
  * Value range: the matrix-core kernel multiplies the softmax weights (at most 32 relative to its running reference) with
  * the scales of the value groups in fp16; that product cannot overflow for scales up to 16, i.e. value groups spanning at
  * most 16 * (2^b - 1) (48 / 240 / 4080 at 2 / 4 / 8 bits), and a weight is lost only when it is below 2^-31 of the largest

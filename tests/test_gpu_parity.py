@@ -550,8 +550,8 @@ def test_random_ragged_workloads(seed):
 
 @pytest.mark.parametrize("hd,g", [(128, 64), (64, 32)])
 def test_extreme_split_counts(hd, g):
-    """Split counts from 1 to the largest allowed (1024: most workgroups get no block at all; beyond 585 partials per
-    sequence the separate merge kernel takes over from the in-kernel merge), with and without fixed shares."""
+    """Split counts from 1 to the largest allowed (1024: most workgroups get no block at all; beyond 64 splits the
+    separate merge kernel takes over from the in-kernel merge), with and without fixed shares."""
     H = _h()
     from paper_2605_02262_amd import binding as W
     specs = [synth.SeqSpec(40, 50, 50, 70, (6, 14, 20)), synth.SeqSpec(3, 64, 64, 5, (1, 1, 1))]
@@ -561,7 +561,7 @@ def test_extreme_split_counts(hd, g):
     q = H.to_dev(bt.q, w.dtype)
     sm = 1.0 / float(np.sqrt(w.hd))
     big = W.Context(W.workspace_bytes(w.B, w.Hq, w.hd, 1024))
-    for splits in (2, 37, 300, 585, 586, 1024):
+    for splits in (2, 37, 64, 65, 300, 585, 586, 1024):     # (up to 64 the kernel merges its splits itself)
         for algo in (W.DECODE_AUTO, W.DECODE_AUTO | W.DECODE_FIXED_SHARES):
             lse = torch.empty(w.B, w.Hq, dtype=torch.float32, device="cuda")
             out = W.wq_decode_attention(big, q, g_run.pk, sm, splits, 2100, algo, lse=lse)
@@ -696,7 +696,7 @@ def test_random_medium_caches_through_the_matrix_core_decode_kernel():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("cfg,splits", [(1, 7), (1, 16), (3, 16)])
+@pytest.mark.parametrize("cfg,splits", [(1, 7), (1, 16), (1, 40), (1, 64), (3, 16)])
 def test_both_merges_of_the_splits_agree_bit_for_bit(cfg, splits):
     """Alg. 2 takes one softmax over all segments; the split over tokens is merged either by the decode kernel's last
     workgroup per (sequence, KV head) or by the merge kernel.  With fixed shares the partials are the same on every run, and
