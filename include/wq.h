@@ -94,8 +94,6 @@ typedef enum { WQ_DECODE_AUTO = 0, WQ_DECODE_GENERIC = 1, WQ_DECODE_MFMA = 2 } w
 /* device status bits (wq_device_status) */
 #define WQ_DEV_CLASS_OVERFLOW 1u /* a class segment did not fit its cap[c]; the excess was not written    */
 #define WQ_DEV_SEG16_OVERFLOW 2u /* 16-bit rows of a sequence exceeded off16[b+1]-off16[b] or cap16        */
-#define WQ_DEV_V_RANGE 8u        /* wq_reorder_quantize stored a value (V) group whose scale exceeds 16: the matrix-core
-                                  * decode kernel is not laid out for it (see wq_decode_attention)                     */
 #define WQ_DEV_TOO_MANY_WINDOWS 16u /* a sequence has more windows than the max_windows given to wq_assign_bits, wq_vote_bits or
                                   * wq_validate_assignment; the windows beyond the bound were left out                  */
 #define WQ_DEV_BAD_ASSIGNMENT 32u /* wq_validate_assignment: perm is not a permutation of a sequence's windows, or its four
@@ -203,7 +201,15 @@ typedef struct {
     int64_t cap16;         /* host                                                                          */
     int32_t* off16;        /* device [B+1], set by the caller: first row of each sequence, [B] = end        */
     int32_t* len16;        /* device [B], written by wq_reorder_quantize, bumped by the caller on append    */
+    float* v_scale_max;    /* device [wq_v_scale_floats(B, Hkv, cap)]: entry b, written by wq_reorder_quantize (and
+                            * set to 0 by wq_dequantize in its destination, where B entries are enough), is the largest
+                            * scale of a value (V) group among sequence b's quantized tokens, 0 if it has none: the
+                            * matrix-core decode kernel places its fp16 weights by it.  The entries behind the first
+                            * B (one per 32-token block and KV head) are wq_reorder_quantize's scratch for finding it */
 } wq_packed_kv;
+
+/* Host-only, pure: number of floats of a cache's v_scale_max table (cap: the three class capacities in tokens). */
+size_t wq_v_scale_floats(int B, int Hkv, const int64_t cap[3]);
 
 /* ---- a3: reorder + quantize + pack (Alg. 2, prefill half) ------------------------------------------------
  * K, V [total_rows, Hkv, hd] device, element type `dtype`; sequence b owns rows kv_off[b]..kv_off[b+1]-1:
@@ -262,10 +268,13 @@ int wq_dequantize(wq_ctx* ctx, int B, const wq_packed_kv* src, const wq_packed_k
  * the matrix-core kernel at most 2^27 token slots in the cache (cap[0] + cap[1] + cap[2] + cap16: it cuts the workgroups'
  * shares on a 32-bit cost axis); num_splits above 1024 is WQ_ERR_ARG.
  * Value range: the matrix-core kernel multiplies the softmax weights (at most 32 relative to its running reference) with
- * the scales of the value groups in fp16; that product cannot overflow for scales up to 16, i.e. value groups spanning at
- * most 16 * (2^b - 1) (48 / 240 / 4080 at 2 / 4 / 8 bits), and a weight is lost only when it is below 2^-31 of the largest
- * one per unit of scale.  wq_reorder_quantize raises WQ_DEV_V_RANGE when it stores a wider group; such a cache decodes
- * correctly with WQ_DECODE_GENERIC, while the matrix-core kernel may then return infinities.  Keys have no such limit.  */
+ * the scales of the value groups in fp16.  It places that product by the sequence's largest value scale (v_scale_max[b] of
+ * the cache, which wq_reorder_quantize writes): the largest product is 2^14..2^15 whatever the values' magnitude, so nothing
+ * overflows for any scale that fp16 holds, and a token's weight is lost to fp16's subnormal range only when it is below
+ * 2^-29 of the largest one (times the ratio of the sequence's largest value scale to the token's own: a group of small
+ * values next to groups of large ones loses more, of a contribution that is small by the same ratio).  A cache filled by
+ * other means than wq_reorder_quantize must set v_scale_max[b] itself (an upper bound will do; too large a bound costs
+ * range at the bottom).  Keys have no such limit.  */
 int wq_decode_attention(wq_ctx* ctx, const void* q, int q_dtype, int B, int Hq, const wq_packed_kv* kv,
                         float sm_scale, int num_splits, int64_t max_seq_tokens, int algo, float* out, float* lse);
 

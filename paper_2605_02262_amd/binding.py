@@ -21,7 +21,7 @@ DECODE_FIXED_SHARES = 0x200
 DECODE_BY_LENGTH = 0x400
 DECODE_SEPARATE_MERGE = 0x800
 CLASS_BITS = (2, 4, 8)
-DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT, DEV_V_RANGE, DEV_TOO_MANY_WINDOWS, DEV_BAD_ASSIGNMENT = 1, 2, 4, 8, 16, 32
+DEV_CLASS_OVERFLOW, DEV_SEG16_OVERFLOW, DEV_APPEND_TIMEOUT, DEV_TOO_MANY_WINDOWS, DEV_BAD_ASSIGNMENT = 1, 2, 4, 16, 32
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libwq.so")
 _lib = None
@@ -39,7 +39,7 @@ class _PackedKV(C.Structure):
                 ("codes", C.c_void_p * 3), ("meta", C.c_void_p * 3), ("cap", C.c_int64 * 3),
                 ("cls_off", C.c_void_p * 3), ("cls_len", C.c_void_p * 3),
                 ("k16", C.c_void_p), ("v16", C.c_void_p), ("cap16", C.c_int64),
-                ("off16", C.c_void_p), ("len16", C.c_void_p)]
+                ("off16", C.c_void_p), ("len16", C.c_void_p), ("v_scale_max", C.c_void_p)]
 
 
 def lib() -> C.CDLL:
@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         L.wq_last_error.argtypes = [vp]
         L.wq_last_error.restype = C.c_char_p
         L.wq_device_status.argtypes = [vp, C.POINTER(C.c_uint32)]
+        L.wq_v_scale_floats.argtypes = [i32, i32, C.POINTER(C.c_int64)]
+        L.wq_v_scale_floats.restype = C.c_size_t
         L.wq_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64, i32]
         L.wq_workspace_bytes.restype = C.c_size_t
         L.wq_packed_bytes.argtypes = [i32, i64, i32, i32, i32, C.POINTER(C.c_size_t)]
@@ -173,6 +175,8 @@ class PackedKV:
         self.k16 = torch.zeros(self.cap16, Hkv, hd, dtype=dtype16, device=dev)
         self.v16 = torch.zeros(self.cap16, Hkv, hd, dtype=dtype16, device=dev)
         self.len16 = torch.zeros(B, dtype=torch.int32, device=dev)
+        n_vs = lib().wq_v_scale_floats(B, Hkv, (C.c_int64 * 3)(*[int(c) for c in self.cap]))
+        self.v_scale_max = torch.zeros(n_vs, dtype=torch.float32, device=dev)
         d = _PackedKV()
         d.B, d.Hkv, d.hd, d.group = B, Hkv, hd, group
         d.dtype16 = _dtype_id(self.k16)
@@ -184,6 +188,7 @@ class PackedKV:
             d.cls_len[c] = _ptr(self.cls_len[c])
         d.k16, d.v16, d.cap16 = _ptr(self.k16), _ptr(self.v16), self.cap16
         d.off16, d.len16 = self.off16.data_ptr(), _ptr(self.len16)
+        d.v_scale_max = _ptr(self.v_scale_max)
         self.desc = d
 
     def bytes_algorithmic(self) -> int:

@@ -36,6 +36,7 @@ int check_packed(wq_ctx* ctx, const wq_packed_kv* kv, int B, bool need_tables)
     if (kv->cap16 < 0 || kv->cap16 > (int64_t)1 << 26) return wq_fail(ctx, WQ_ERR_ARG, "bad cap16");
     if (kv->cap16 > 0 && (!kv->k16 || !kv->v16)) return wq_fail(ctx, WQ_ERR_ARG, "16-bit segment has capacity but NULL k16/v16");
     if (!kv->off16 || !kv->len16) return wq_fail(ctx, WQ_ERR_ARG, "off16/len16 tables are NULL");
+    if (!kv->v_scale_max) return wq_fail(ctx, WQ_ERR_ARG, "v_scale_max table is NULL");
     return WQ_OK;
 }
 
@@ -114,6 +115,14 @@ size_t wq_workspace_bytes(int B, int Hq, int hd, int max_splits, int64_t total_v
     size_t m = a > b ? a : b;
     if (c > m) m = c;
     return WQ_WS_HEADER + m;
+}
+
+size_t wq_v_scale_floats(int B, int Hkv, const int64_t cap[3])
+{
+    if (B < 0 || Hkv <= 0 || !cap) return 0;
+    size_t blocks = 0;
+    for (int c = 0; c < 3; c++) blocks += (size_t)((cap[c] > 0 ? cap[c] : 0) / 32);
+    return (size_t)B + blocks * (size_t)Hkv;
 }
 
 size_t wq_packed_bytes(int bits, int64_t cap_tokens, int Hkv, int hd, int group, size_t* meta_bytes)

@@ -170,6 +170,7 @@ struct WaveState {
     float m;              // reference exponent of this column (a recent largest logit), log2 domain, shared by the four lane groups
     float l;              // this lane's share of sum p
     float accM;           // this lane's share of sum p * m_v
+    float up;             // log2 of the factor that the weights of the quantized classes are formed with (the same in all lanes)
 };
 
 // 32-token blocks in flight per wavefront and class: enough bytes to keep the memory system busy while a block
@@ -178,11 +179,22 @@ constexpr int WQ_D2 = 4, WQ_D4 = 3, WQ_D8 = 2;
 constexpr int WQ_FIRST_TICKETS = 4;    // blocks every wavefront starts with (the deepest pipeline's fill)
 constexpr int WQ_WAVES = 8;            // wavefronts per workgroup: one workgroup per compute unit, two wavefronts per SIMD
 constexpr float WQ_MAX_SLACK = 5.0f;   // log2 of the largest softmax weight tolerated before the reference exponent moves
-// The weights meet the value scales in fp16 (P' = p * s_v).  They are formed 2^WQ_P_UP too large (for free, in the exponent
-// of the exp2), which the sums undo exactly at the end: with p <= 2^WQ_MAX_SLACK and s_v <= WQ_MAX_V_SCALE = 2^4 the product
-// stays below 2^15, and a weight has to be 2^-(24 + WQ_P_UP) of the largest one, per unit of s_v, before it is lost.
-constexpr float WQ_P_UP = 6.0f;
-constexpr float WQ_O_UNIT = 262144.0f; // 2^(24 - WQ_P_UP): what an accumulator of the value product counts in units of
+// The weights meet the value scales in fp16 (P' = p * s_v).  They are formed 2^up too large (for free, in the exponent of
+// the exp2), which the sums undo exactly at the end; up is chosen per sequence from its largest value scale s_max (a table
+// of the cache that the quantizer fills) so that the largest product, 2^(WQ_MAX_SLACK + up) * s_max, lies in
+// [2^(WQ_P_TOP - 1), 2^WQ_P_TOP]: nothing overflows whatever the values' magnitude, and a weight has to be
+// 2^-(24 + WQ_P_TOP - WQ_MAX_SLACK - 6) = 2^-29 of the largest one, in a group whose scale is the sequence's largest and
+// in the slot that is shifted most, before it is lost.
+constexpr int WQ_P_TOP = 15;
+// up for a sequence whose largest value scale is s_max (0: no quantized token; any up will do)
+__device__ __forceinline__ float weight_upscale(float s_max)
+{
+    const uint32_t u = __float_as_uint(s_max);
+    const int ceil_log2 = (int)((u >> 23) & 0xFFu) - 127 + ((u & 0x7FFFFFu) != 0u ? 1 : 0);
+    const int up = (WQ_P_TOP - (int)WQ_MAX_SLACK) - ceil_log2;
+    return s_max > 0.f ? (float)min(max(up, -16), 40) : 6.0f;
+}
+__device__ __forceinline__ float pow2_of(float e) { return __uint_as_float((uint32_t)(127 + (int)e) << 23); }   // e an integer in [-126, 127]
 constexpr int VT_PAD = 4;   // row pitch of the transposition buffer: (HD/2+4)*2 bytes, i.e. 4 rows apart = 8 banks (mod 32)
 
 template <int HD>
@@ -492,7 +504,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
     // partial sums per slot register v: its weights carry 2^-shift(v) (folded into the exponent), undone after the loop
     float lv[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f}, ms[4];
 #pragma unroll
-    for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v) - WQ_P_UP;
+    for (int v = 0; v < 4; v++) ms[v] = st.m + v_slot_shift<BITS>(v) - st.up;
 
     auto compute = [&](int blk, const F& f) {
         const bool redraw = tk.spent;
@@ -549,7 +561,7 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
             for (int v = 0; v < 4; v++) {
                 lv[v] *= alpha;
                 av[v] *= alpha;
-                ms[v] = mn + v_slot_shift<BITS>(v) - WQ_P_UP;
+                ms[v] = mn + v_slot_shift<BITS>(v) - st.up;
             }
 #pragma unroll
             for (int ct = 0; ct < CT; ct++) st.O[ct] *= alpha;
@@ -588,10 +600,11 @@ __device__ __forceinline__ void walk_class_mfma(const DecodeArgs& a, MfmaSmem<HD
             }
         }
     }
+    const float down = pow2_of(-st.up);            // undoes the factor that the weights were formed with
 #pragma unroll
     for (int v = 0; v < 4; v++) {
-        st.l = fmaf(lv[v], 0.015625f / v_slot_scale<BITS>(v), st.l);        // (2^-WQ_P_UP)
-        st.accM = fmaf(av[v], 0.015625f / v_slot_scale<BITS>(v), st.accM);
+        st.l = fmaf(lv[v], down * (1.0f / v_slot_scale<BITS>(v)), st.l);
+        st.accM = fmaf(av[v], down * (1.0f / v_slot_scale<BITS>(v)), st.accM);
     }
 }
 
@@ -883,6 +896,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     }
     cls_len[3] = a.kv.len16[b];
     cls_off[3] = a.kv.off16[b];
+    const float v_scale_max = a.kv.v_scale_max[b];
     note_tables_read(a, b, cls_len[3]);
     // a token appended by this launch becomes the last row of the 16-bit segment: read from k_new / v_new by whoever
     // walks its block, copied into the cache by the first split's workgroup, counted in len16 once every workgroup of
@@ -991,6 +1005,8 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     st.m = -INFINITY;
     st.l = 0.f;
     st.accM = 0.f;
+    st.up = weight_upscale(v_scale_max);
+    const float o_unit = pow2_of(24.0f - st.up);   // what an accumulator of the value product counts in units of
     const float c_log2 = a.sm_scale * 1.4426950408889634f;
     WQ_WSTAMP(0, wall_clock64());
     if (has_blocks(src[3], tk, 1u)) {              // (most wavefronts have no block of the 16-bit segment and go straight on)
@@ -998,9 +1014,10 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
             walk_seg16_mfma<HD, true>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
         else
             walk_seg16_mfma<HD, false>(a, sm, b, kvh, cls_len[3], cls_off[3], src[3], tk, c_log2, st, new_row, knew, vnew);
-        // the quantized classes accumulate 2^(WQ_P_UP-24) * (p s_v code); bring the 16-bit part to the same unit (exact)
+        // the quantized classes accumulate 2^(up-24) * (p s_v code); bring the 16-bit part to the same unit (exact)
+        const float to_unit = pow2_of(st.up - 24.0f);
 #pragma unroll
-        for (int ct = 0; ct < CT; ct++) st.O[ct] *= (1.0f / WQ_O_UNIT);
+        for (int ct = 0; ct < CT; ct++) st.O[ct] *= to_unit;
     }
     WQ_WSTAMP(1, wall_clock64());
     walk_class_mfma<HD, 8, WQ_D8>(a, sm, b, kvh, cls_len[2], cls_off[2], src[2], tk, c_log2, st);
@@ -1022,7 +1039,7 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     for (int ct = 0; ct < CT; ct++) {
         if ((ct >= CT / 2) == (g == 1)) {          // this column's group owns channel tile ct
 #pragma unroll
-            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], WQ_O_UNIT, am);
+            for (int i = 0; i < 4; i++) sm.O[wave][h][16 * ct + 4 * j + i] = fmaf(st.O[ct][i], o_unit, am);
         }
     }
     if (j == 0 && g == 0) {

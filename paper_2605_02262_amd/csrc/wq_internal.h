@@ -34,7 +34,6 @@ constexpr int WQ_MAX_FUSED_SPLITS = 64; // splits that the decode kernel merges 
 #define WQ_COSTS 100, 130, 230, 500
 #endif
 constexpr int WQ_BLOCK_COST[4] = {WQ_COSTS};
-constexpr float WQ_MAX_V_SCALE = 16.0f; // largest scale of a value group that the decode kernel's fp16 weights are laid out for
 constexpr int WQ_MAX_WINDOWS = 8192;   // windows per sequence handled by the ranking kernel
 
 inline int wq_fail(wq_ctx* ctx, int code, const char* fmt, ...)

@@ -63,7 +63,66 @@ __global__ __launch_bounds__(256) void k_plan(int B, const int32_t* __restrict__
             pre16[b + 1] = (int32_t)run;
         }
         if (over) atomicOr(status, WQ_DEV_SEG16_OVERFLOW);
+    } else if (tid >= 64) {
+        for (int b = tid - 64; b < B; b += 192) pk.v_scale_max[b] = 0.f;      // k_v_scale_max raises it
     }
+}
+
+// maximum of a small unsigned value over the 64 lanes of a wavefront: four rotations inside the rows of 16 lanes (one
+// data-parallel-primitive instruction each, no LDS), then the four rows' results as scalars
+template <int CTRL>
+__device__ __forceinline__ uint32_t lanes_moved(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ uint32_t lanes_max_u16(uint32_t x)
+{
+    x = max(x, lanes_moved<0x128>(x));             // row_ror:8, 4, 2, 1
+    x = max(x, lanes_moved<0x124>(x));
+    x = max(x, lanes_moved<0x122>(x));
+    x = max(x, lanes_moved<0x121>(x));
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    return max(max(a, b), max(c, d));
+}
+
+// v_scale_max holds [B] results, then one float per (32-token block, KV head) of the three classes (class c's blocks
+// behind those of the classes before it, by capacity)
+__device__ __forceinline__ int64_t v_scale_slot(const wq_packed_kv& pk, int B, int c, int64_t blk, int kvh)
+{
+    int64_t base = 0;
+    for (int k = 0; k < c; k++) base += pk.cap[k] / 32;
+    return (int64_t)B + (base + blk) * pk.Hkv + kvh;
+}
+
+// per sequence: the largest of its blocks' largest value scales (0 if it has no quantized token).  WQ_VS_PARTS workgroups
+// per sequence take a slice of the blocks each and raise the sequence's entry, which k_plan has set to zero (positive
+// floats order like their bit patterns)
+constexpr int WQ_VS_PARTS = 16;
+__global__ __launch_bounds__(256) void k_v_scale_max(int B, wq_packed_kv pk)
+{
+    __shared__ float red[256];
+    const int b = blockIdx.x / WQ_VS_PARTS, part = blockIdx.x % WQ_VS_PARTS, tid = threadIdx.x;
+    float mx = 0.f;
+    for (int c = 0; c < 3; c++) {
+        const int64_t t0 = pk.cls_off[c][b] / 32, t1 = pk.cls_off[c][b + 1] / 32;
+        const int64_t first = v_scale_slot(pk, B, c, t0, 0), n = (t1 - t0) * pk.Hkv;
+        const int64_t per = (n + WQ_VS_PARTS - 1) / WQ_VS_PARTS, lo = part * per, hi = min(n, lo + per);
+        const float* src = pk.v_scale_max + first;
+        int64_t i = lo + tid;
+        for (; i + 768 < hi; i += 1024) {          // four loads in flight
+            const float a0 = src[i], a1 = src[i + 256], a2 = src[i + 512], a3 = src[i + 768];
+            mx = fmaxf(fmaxf(mx, a0), fmaxf(fmaxf(a1, a2), a3));
+        }
+        for (; i < hi; i += 256) mx = fmaxf(mx, src[i]);
+    }
+    red[tid] = mx;
+    __syncthreads();
+    for (int o = 128; o >= 1; o >>= 1) {
+        if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
+        __syncthreads();
+    }
+    if (tid == 0 && red[0] > 0.f) atomicMax(reinterpret_cast<unsigned*>(pk.v_scale_max + b), __float_as_uint(red[0]));
 }
 
 // bits -> class index
@@ -147,9 +206,6 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
             s = 1.0f;
             sh = __float2half_rn(1.0f);
         }
-        // the decode kernel forms (softmax weight) x (value scale) in fp16 and keeps both factors' product below 2^15 for
-        // scales up to WQ_MAX_V_SCALE; a value group with a larger scale is stored like any other and reported
-        if (plane == 1 && s > WQ_MAX_V_SCALE) atomicOr(status, WQ_DEV_V_RANGE);
         const float inv = 1.0f / s;
         // This thread's codes: the K plane takes them as consecutive BITS-wide fields of its token's row quarter
         // (pw, stored below); the V plane as bytes, 4 per word (cw), for the transposition through LDS.
@@ -195,6 +251,16 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
         }
     }
     __syncthreads();
+
+    // ---- the block's largest value scale (the decode kernel places its fp16 weights by the sequence's largest one): the
+    //      scales are the low halves of the V metadata words, zero for tokens past the end; positive f16 values order like
+    //      their bit patterns.  One plain store per workgroup into the table's scratch part; k_v_scale_max collects them ----
+    if (tid < 64) {
+        uint32_t top = 0;
+        for (int i = tid; i < 32 * G; i += 64) top = max(top, s_meta[1][i >> 5][i & 31] & 0xFFFFu);
+        top = lanes_max_u16(top);
+        if (tid == 0) pk.v_scale_max[v_scale_slot(pk, B, C, blk, kvh)] = wq_f16_bits_to_float(top);
+    }
 
     // ---- V plane: block of 32 tokens, field n = ((jj*16 + mm)*(HD/16) + ct)*8 + tau ----------------------
     {
@@ -339,6 +405,7 @@ __global__ __launch_bounds__(256) void k_dense_plan(int B, wq_packed_kv src, wq_
         if (!ok) atomicOr(status, WQ_DEV_SEG16_OVERFLOW);
 #pragma unroll
         for (int c = 0; c < 3; c++) dst.cls_len[c][b] = 0;
+        dst.v_scale_max[b] = 0.f;
     }
     for (int b = threadIdx.x; b <= B; b += 256)
 #pragma unroll
@@ -479,6 +546,7 @@ int run(wq_ctx* ctx, const void* K_, const void* V_, int B, const int32_t* kv_of
     if (n2 + rows16 > 0)
         hipLaunchKernelGGL((k_quantize_all<T, HD>), dim3((unsigned)(n2 + rows16)), dim3(256), 0, st, K, V, B, pk->group, kv_off, win_size,
                            win_off, perm, seg_windows, pre16, *pk, (unsigned)n0, (unsigned)n1, (unsigned)n2, wq_status_ptr(ctx));
+    if (B > 0) hipLaunchKernelGGL(k_v_scale_max, dim3((unsigned)B * WQ_VS_PARTS), dim3(256), 0, st, B, *pk);
     WQ_HIP_CHECK(ctx, hipGetLastError());
     return WQ_OK;
 }

@@ -103,6 +103,9 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
             d.cls_off[c] = 0x3000
             d.cls_len[c] = 0x3000
         d.off16, d.len16 = 0x3000, 0x3000
+        assert lib.wq_decode_attention(h, one, W.BF16, 1, 28, C.byref(d), 0.1, 0, 100, 0, one, None) == -1
+        assert b"v_scale_max" in lib.wq_last_error(h)
+        d.v_scale_max = 0x3000
         d.hd = 96
         assert lib.wq_decode_attention(h, one, W.BF16, 1, 28, C.byref(d), 0.1, 0, 100, 0, one, None) == -2
         d.hd = 128

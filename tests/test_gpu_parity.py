@@ -843,8 +843,9 @@ def test_adversarial_softmax(hd, g):
     forms (weight x value scale) in fp16.  Cases built to stress exactly that, each against the fp64 oracle over the same
     dequantized values: logits that rise along the stream (the reference keeps moving), one token far above all others in
     each of the four segments (the rest of the mass sits 14 nats lower and must not be lost), a zero query and identical
-    keys (uniform softmax), value groups with the largest scale the kernel is specified for, and all of it once more with
-    every window in the 8-bit class, whose value scales are the smallest."""
+    keys (uniform softmax), value groups with scales just below 16, and all of it once more with every window in the 8-bit
+    class, whose value scales are the smallest, and in the 2-bit class; then values of very different magnitudes (the kernel
+    places its f16 weights by the sequence's largest value scale, which the quantizer records)."""
     H = _h()
     from oracle import wq_oracle as O
     from paper_2605_02262_amd import binding as W
@@ -887,7 +888,7 @@ def test_adversarial_softmax(hd, g):
         # (c) uniform softmax: a zero query; and every key the same
         cases["zero-query"] = (base.K, base.V, np.zeros_like(base.q))
         cases["equal-keys"] = (np.broadcast_to(base.K[:1], base.K.shape).copy(), base.V, base.q)
-        # (d) values as wide as the kernel is specified for: group scales just below 16 in every class
+        # (d) wide values: group scales just below 16 in every class
         Vw = base.V.copy()
         for c, (qmax, wins) in enumerate(((3, order[nw - quota[2]:] if quota[2] else []), (15, order[quota[0]:quota[0] + quota[1]]), (255, order[:quota[0]]))):
             for win in wins:
@@ -909,14 +910,19 @@ def test_adversarial_softmax(hd, g):
                 lg = (K[:, 0].astype(np.float64) @ q[0, 0].astype(np.float64)) * sm
                 top = 1.0 / np.exp(lg - lg[tok]).sum()
                 assert 0.8 < top < 0.97 and lg[tok] - np.median(lg) > 9.0, (name, top)
-    # a value group wider than specified is reported by the quantizer
+    # the kernel places its f16 weights by the sequence's largest value scale: one group 400 times wider than the rest, and
+    # values 2^-12 and 2^11 times the usual size under a peaked softmax, all through the matrix-core kernel
+    K_dom, _, q_dom = cases["dominant-low-class"]
     Vbig = base.V.copy()
     Vbig[3, 0, :g] *= 400.0
-    bt = synth.Batch(w, base.t, base.E_t, base.E_v, base.K, synth.round_bf16(Vbig), base.q)
-    g_run = H.run_gpu(bt, splits=3, with_scores=False, scores_override=sc, algo=W.DECODE_GENERIC)
-    o = H.run_oracle(bt, scores_override=sc, with_scores=False)
-    assert g_run.ctx.device_status() == W.DEV_V_RANGE
-    assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL
+    for name, (K, V, q) in {"one-wide-group": (base.K, Vbig, base.q), "tiny-values-peaked": (K_dom, base.V * np.float32(2.0 ** -12), q_dom),
+                            "huge-values-peaked": (K_dom, base.V * np.float32(2.0 ** 11), q_dom)}.items():
+        bt = synth.Batch(w, base.t, base.E_t, base.E_v, np.ascontiguousarray(K), synth.round_bf16(V), np.ascontiguousarray(q))
+        g_run = H.run_gpu(bt, splits=3, with_scores=False, scores_override=sc, algo=W.DECODE_MFMA)
+        o = H.run_oracle(bt, scores_override=sc, with_scores=False)
+        assert g_run.ctx.device_status() == 0, name
+        H.assert_packed_equal(g_run, o)
+        assert H.attention_error(g_run.out.cpu().numpy(), o.out) <= H.ATTN_TOL, name
 
 
 @pytest.mark.gpu

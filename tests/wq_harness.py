@@ -134,8 +134,10 @@ def run_gpu(bt: synth.Batch, scores_override: Optional[np.ndarray] = None, mode:
 # comparisons
 # ------------------------------------------------------------------------------------------------------------
 def assert_packed_equal(g: GpuRun, o: OracleRun):
-    """Bit-exact: class tables, packed codes and metadata of every used block, 16-bit rows."""
+    """Bit-exact: class tables, packed codes and metadata of every used block, 16-bit rows, and the table of each
+    sequence's largest value scale (read off the oracle's own metadata)."""
     B = o.pk.B
+    largest_v_scale = np.zeros(B, np.float32)
     for c in range(3):
         assert np.array_equal(g.pk.cls_off[c].cpu().numpy(), o.pk.cls_off[c]), f"cls_off[{c}]"
         assert np.array_equal(g.pk.cls_len[c].cpu().numpy(), o.pk.cls_len[c]), f"cls_len[{c}]"
@@ -151,7 +153,14 @@ def assert_packed_equal(g: GpuRun, o: OracleRun):
         meta = o.pk.packed_meta(c)
         gm = g.pk.meta[c].cpu().numpy().view(np.uint32)
         assert np.array_equal(gm[:, :, :used * G], meta[:, :, :used * G]), f"metadata of class {b}-bit differ"
+        v_meta = meta[1].reshape(meta.shape[1], -1, G, 16)                      # [head][tile of 16 tokens][group][token]: s | m << 16
+        for bb in range(B):
+            t0, t1 = int(o.pk.cls_off[c][bb]) // 16, int(o.pk.cls_off[c][bb + 1]) // 16
+            if t1 > t0:
+                sc = (v_meta[:, t0:t1] & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float32)
+                largest_v_scale[bb] = max(largest_v_scale[bb], float(sc.max()))
     assert np.array_equal(g.pk.len16.cpu().numpy(), o.pk.len16), "len16"
+    assert np.array_equal(g.pk.v_scale_max[:B].cpu().numpy(), largest_v_scale), "largest value scale per sequence"
     k16 = g.pk.k16.float().cpu().numpy()
     v16 = g.pk.v16.float().cpu().numpy()
     for bb in range(B):
