@@ -957,12 +957,8 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
         // cost at which split x starts: floor(total * x / S) up to rounding (one reciprocal, the same bits in every
         // wavefront of the launch); split 0 starts at cost 0, the last one ends behind everything
         const float rS = __builtin_amdgcn_rcpf((float)S);
-        // workgroups are dispatched in the order of their numbers, the last split's some 0.9 us after the first's: the
-        // early ones get a little more of the axis (8 % more per unit of the axis at its start, 8 % less at its end)
         auto start_of = [&](int x) {
-            const float u = (float)x * rS;
-            const float f = u * (1.0f + 0.08f * (1.0f - u));
-            return min(total, (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((float)total * f)));
+            return min(total, (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((float)total * ((float)x * rS))));
         };
         const unsigned G0 = split == 0 ? 0u : start_of(split);
         const unsigned G1 = split == S - 1 ? total : start_of(split + 1);
