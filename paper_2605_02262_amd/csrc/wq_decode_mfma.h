@@ -211,7 +211,6 @@ struct MfmaSmem {
     float qx[4][2][64];                                  // ... with the head's power of two and the group's query sum
     float ml[WQ_WAVES][WQ_MAX_REP][2];
     unsigned next_ticket;                                // the workgroup's block counter
-    int last;                                            // this workgroup is the last of its (sequence, KV head) to finish
 };
 
 
@@ -1089,33 +1088,32 @@ __device__ void wq_decode_mfma_body(const DecodeArgs& a, void* smem_raw)
     WQ_STAMP(5);
     if (!a.fused) return;
 
-    // ---- the last workgroup of (b, kvh) to get here merges the partials of all splits, in split order ----
-    // The partial was stored with device-scope stores, which go through to memory.  Every thread waits here until the
-    // memory system has acknowledged its stores (vmcnt(0): what a workgroup-scope fence does not make the compiler emit);
-    // only after the barrier that follows does one thread report the workgroup in, so a workgroup that finds itself last
-    // reads partials that have arrived, with device-scope loads that do not stop at a cache.  This costs one memory round
-    // trip; a device-scope release fence would add a write-back of the whole L2 (measured: 19 us per call).
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    WQ_STAMP(56);
-    if (tid == 0) {
-        const unsigned old = __hip_atomic_fetch_add(a.arrive + unit * WQ_ARRIVE_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm.last = old == (unsigned)S - 1u;
-    }
-    __syncthreads();
-    WQ_STAMP(57);
-    if (!sm.last) {
-        finish_append(a, b, kvh, split, new_row);
-        return;
-    }
-    if (tid == 0) __hip_atomic_store(a.arrive + unit * WQ_ARRIVE_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-    // What follows runs once per (b, kvh) while the rest of the chip waits, and a wavefront's vector instruction takes
-    // four cycles: every instruction counts.  Wavefront r merges head r on its own: lane s holds (m, l) of split s (the
-    // launch takes this path with at most 64 splits), the weights come from reductions inside the wavefront, lane s's
-    // weight is read back as a scalar for the sum over the splits; no LDS, no barrier.  The partials are read through
-    // a buffer descriptor, whose range check returns zero beyond the last split.
+    // ---- the last workgroup of (b, kvh) to get here merges the partials of all splits, in split order; head by head:
+    //      head r's partial was written by wavefront r alone, so wavefront r reports in for it on a counter of its own
+    //      and, if it is the last to do so, merges head r, without a word to the other wavefronts ----
+    // The partial was stored with device-scope stores, which go through to memory.  The wavefront waits until the
+    // memory system has acknowledged its stores (vmcnt(0): what a fence of narrower scope does not make the compiler
+    // emit) and only then counts itself, so the wavefront that finds itself last reads partials that have arrived, with
+    // device-scope loads that do not stop at a cache.  This costs one memory round trip; a device-scope release fence
+    // would add a write-back of the whole L2 (measured: 19 us per call).
+    bool last = false;
     if (wave < a.rep) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        WQ_STAMP(56);
+        unsigned* const counter = a.arrive + unit * WQ_ARRIVE_STRIDE + wave;
+        static_assert(WQ_ARRIVE_STRIDE >= WQ_MAX_REP, "one counter per head inside a unit's piece");
+        unsigned old = 0u;
+        if (lane == 0) old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = (unsigned)__builtin_amdgcn_readfirstlane((int)old) == (unsigned)S - 1u;
+        WQ_STAMP(57);
+        if (last && lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    }
+    // What follows runs once per (b, kvh, head) while the rest of the chip waits, and a wavefront's vector instruction
+    // takes four cycles: every instruction counts.  Lane s holds (m, l) of split s (the launch takes this path with at
+    // most 64 splits), the weights come from reductions inside the wavefront, lane s's weight is read back as a scalar
+    // for the sum over the splits; no LDS, no barrier.  The partials are read through a buffer descriptor, whose range
+    // check returns zero beyond the last split.
+    if (last) {
         const int np = S;                          // (the splits are all the partials there are in a launch that merges them itself)
         const unsigned pbytes = (unsigned)pstride * 4u;
         const __amdgpu_buffer_rsrc_t parts = __builtin_amdgcn_make_buffer_rsrc(pbase, 0, np * (int)pbytes, 0x00020000);
