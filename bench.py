@@ -12,7 +12,7 @@ caches and decodes from the one written longest ago; with 8 copies about 3 GB of
 write of a cache from its read.
 
 Prints ONE JSON line.  `value` is the decode-attention rate: algorithmic bytes of the packed cache divided
-by the duration of a decode call: 10 warm-up calls, then 128 calls on rotated caches timed as 16 batches of 8
+by the duration of a decode call: 10 warm-up calls, then 512 calls on rotated caches timed as 16 batches of 32
 back-to-back calls (HIP events on the launch stream around each batch); the median of the batch means, with
 p10/p90 next to it.  The call is one kernel (it streams the cache and its last workgroups merge the splits).  The
 roofline entry takes that kernel's own duration: the same calls captured in a HIP graph (64 per replay, 20 replays, one
@@ -39,7 +39,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 N_COPIES = 8
-DECODE_BATCHES, DECODE_PER_BATCH = 16, 8      # 128 timed decode calls
+DECODE_BATCHES, DECODE_PER_BATCH = 16, 32     # 512 timed decode calls (8 calls per event pair read 1-2 us more per call: the markers)
 
 
 def log(*a):
@@ -314,8 +314,8 @@ def main():
         return e0.elapsed_time(e1) * 1e3 / n
 
     # ---- the decode call on rotated caches: 10 warm-up calls, then DECODE_BATCHES batches of DECODE_PER_BATCH back-to-back
-    #      calls, one pair of HIP events around each batch (a pair around every call would put several microseconds of
-    #      marker overhead into a kernel of under 30 us); median and spread over the batch means -----------------------
+    #      calls, one pair of HIP events around each batch (a pair around every call puts 1-3 us of marker overhead into a
+    #      kernel of under 30 us, a pair around 8 calls still 1-2 us per call); median and spread over the batch means ------
     dec = lambda algo: (lambda i: W.wq_decode_attention(ctx, q, copies[i % N_COPIES], sm_scale, args.splits, max_tok, algo | by_length, out=out, lse=lse))
 
     def decode_stats(algo):
