@@ -242,9 +242,10 @@ constexpr int PA_Q = PA_KS / 32;         // quarters of a step: one matrix instr
 constexpr int PA_PITCH = PA_KS + 16;     // LDS row pitch in elements (288 bytes: rows start 32 bytes apart in the banks; measured free of bank conflicts, a pitch of 272 bytes is not)
 constexpr int PA_WCOLS = 64;             // text columns per wavefront and pass
 constexpr int PA_CT = PA_WCOLS / 16;     // column tiles per wavefront
-constexpr int PA_PPR = PA_KS / 8;        // 16-byte pieces per row and step
-constexpr int PA_RPT = PA_THREADS / PA_PPR;   // rows that the workgroup stages at a time
-constexpr int PA_NU = PA_ROWS / PA_RPT;  // pieces per thread and step
+constexpr int PA_PCS = PA_PITCH / 8;     // 16-byte pieces per LDS row, the padding included
+constexpr int PA_DMA = (PA_ROWS * PA_PCS + 64 * PA_WAVES - 1) / (64 * PA_WAVES);   // loads to LDS per wavefront and step (64 pieces each)
+constexpr int PA_ROW_POLICY = 2;         // cache policy of the visual rows' loads: non-temporal (read once; measured 1 % fewer cycles)
+constexpr int PA_BUF = PA_WAVES * PA_DMA * 64 * 8;                                 // elements of one LDS buffer
 
 // Tiles of 16 text rows in operand order.  Sequence b's tiles start at tile txt_off[b] / 16 + b: room for
 // ceil(N_b / 16) tiles each, whatever the lengths.  Rows past N_b are zero.
@@ -271,54 +272,106 @@ __global__ __launch_bounds__(256) void k_pack_text(const uint16_t* __restrict__ 
     packed[item * 64 + lane] = v;
 }
 
+// The two buffers of visual rows are separate arrays on purpose: the compiler then knows that a read of one cannot
+// see a load in flight to the other, and makes a wavefront wait for exactly the loads it reads behind.
+__shared__ __attribute__((aligned(16))) uint16_t pair_a0[PA_BUF];
+__shared__ __attribute__((aligned(16))) uint16_t pair_a1[PA_BUF];
+
+// x of the lane that a data-parallel-primitive control pairs this lane with (rows of 16 lanes)
+template <int CTRL>
+__device__ __forceinline__ float pair_lane(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+
+// One stage of a sum over the 16 lanes of a row, for NV values per lane at once: the lane and its partner (which
+// differ in `upper`) split the values between them, each adding the other's half of the pair's sums to its own, so
+// the lane is left with NV / 2 values, v[0 .. NV/2): the lower half of the indices if !upper, else the upper half.
+// With a single value left both keep the sum.
+template <int CTRL, int NV>
+__device__ __forceinline__ void pair_halve(float (&v)[32], bool upper)
+{
+    if constexpr (NV >= 2) {
+#pragma unroll
+        for (int j = 0; j < NV / 2; j++) {
+            const float give = upper ? v[j] : v[j + NV / 2];
+            const float keep = upper ? v[j + NV / 2] : v[j];
+            v[j] = keep + pair_lane<CTRL>(give);
+        }
+    } else {
+        v[0] += pair_lane<CTRL>(v[0]);
+    }
+}
+
 struct PairSmem {
-    __attribute__((aligned(16))) uint16_t A[2][PA_ROWS * PA_PITCH];
     float W[PA_WAVES * PA_WCOLS];        // 1/|t_j| of the pass (0 past the end)
     float R[PA_WAVES][PA_ROWS];          // row sums, one array per column block
     float N2[PA_ROWS];                   // |w_k|^2
 };
 
-// RT row tiles of 16 per wavefront: 8 -> the eight wavefronts are eight column blocks of a 512-column pass,
-// 4 -> two row halves x four column blocks (256 columns), 2 -> four row quarters x two column blocks (128).
-template <bool BF, int RT>
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+template <int P> struct PairBuf { static constexpr int value = P; };
+
+// The eight wavefronts are NCB column blocks of 64 text columns x 8 / NCB row groups of RT row tiles of 16:
+// (RT, NCB) = (8, 8): 128 rows x a 512-column pass; (4, 4): two row halves x 256 columns; (2, 2): four row quarters
+// x 128 columns; (7, 8) and (6, 8): 112 and 96 rows x 512 columns, for launches whose number of 128-row workgroups
+// would leave most of the chip idle in the last round.  A wavefront walks its row tiles starting at the one with
+// its column block's number, so that the wavefronts of a row group start on different tiles; the first tile of a
+// wavefront whose column block's number is below RT is the one whose |w_k|^2 it sums on the way.
+template <bool BF, int RT, int NCB>
 __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
-                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, float (&nsq)[PA_NU])
+                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, int rows, float& nsq)
 {
-    constexpr int NCB = RT, PASS = NCB * PA_WCOLS;        // column blocks per pass
+    constexpr int PASS = NCB * PA_WCOLS;                  // columns per pass
+    constexpr int DMA = (RT * (PA_WAVES / NCB) * 16 * PA_PCS + 64 * PA_WAVES - 1) / (64 * PA_WAVES);   // loads to LDS per wavefront and step
+    static_assert(DMA <= PA_DMA, "LDS buffers too small");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lj = lane >> 4, lm = lane & 15;
     const int cb = wave % NCB, rb = (wave / NCB) * RT;
-    const int pp = tid % PA_PPR, pr = tid / PA_PPR;       // visual rows to LDS: thread -> 16-byte piece pp of rows pr + PA_RPT u
-    const uint16_t* pa[PA_NU];
-#pragma unroll
-    for (int u = 0; u < PA_NU; u++) pa[u] = va + (int64_t)min(row0 + pr + PA_RPT * u, M - 1) * D + pp * 8;   // rows past the end re-read the last
     const int steps = D / PA_KS, ntile = (N + 15) >> 4;
 
-    auto load_a = [&](int s, uint4 (&ga)[PA_NU]) {
+    // visual rows: memory -> LDS without passing registers.  A load instruction fills 64 consecutive 16-byte pieces
+    // of the buffer, one per lane; piece p is column p % PA_PCS of row p / PA_PCS.  The descriptor covers this
+    // workgroup's rows only: padding columns and rows past the sequence's end lie outside it and read as zero.
+    const int rows_here = min(rows, M - row0);
+    const __amdgpu_buffer_rsrc_t vrows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(va + (int64_t)row0 * D), 0,
+                                                                           rows_here * D * 2, 0x00020000);
+    int voff[DMA];
 #pragma unroll
-        for (int u = 0; u < PA_NU; u++) ga[u] = *reinterpret_cast<const uint4*>(pa[u] + s * PA_KS);
-    };
-    // count: 1 when these rows have not been summed into |w_k|^2 yet, else 0 (a factor, not a branch: the loop body
-    // stays one block, which keeps the wait counts of the loads in flight exact)
-    auto store_a = [&](int buf, const uint4 (&ga)[PA_NU], float count) {
+    for (int t = 0; t < DMA; t++) {
+        const int p = (wave + PA_WAVES * t) * 64 + lane, r = p / PA_PCS, c = p - r * PA_PCS;
+        voff[t] = (c < PA_KS / 8 && r < rows_here) ? (r * D + c * 8) * 2 : (int)0x80000000;
+    }
+    auto send_rows = [&](auto P, int s) {                 // step s of D -> buffer P
+        uint16_t* const dst = decltype(P)::value ? pair_a1 : pair_a0;
 #pragma unroll
-        for (int u = 0; u < PA_NU; u++) {
-            *reinterpret_cast<uint4*>(&sm.A[0][(pr + PA_RPT * u) * PA_PITCH + pp * 8] + buf * (PA_ROWS * PA_PITCH)) = ga[u];
-            nsq[u] = fmaf(sumsq8<BF>(ga[u]), count, nsq[u]);
-        }
+        for (int t = 0; t < DMA; t++)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrows, (lds_ptr_t)(dst + (wave + PA_WAVES * t) * 512), 16, voff[t],
+                                                     s * (PA_KS * 2), 0, PA_ROW_POLICY);
     };
+    // byte offsets of this lane's operand pieces, row tile by row tile in the wavefront's own order
+    int ro[RT];
+#pragma unroll
+    for (int i = 0; i < RT; i++) ro[i] = (((rb + (i + cb) % RT) * 16 + lm) * PA_PITCH + lj * 8) * 2;
+    // A read from the buffer that this wavefront has sent loads for: the compiler puts the wait for those loads in
+    // front of it (loads land in the order sent), whatever else it has moved around them.
+    auto peek = [&](auto P) {
+        const char* const src = reinterpret_cast<const char*>(decltype(P)::value ? pair_a1 : pair_a0);
+        return *reinterpret_cast<const uint32_t*>(src + ro[0]);
+    };
+    auto use = [&](uint32_t x) { asm volatile("" ::"v"(x)); };
 
     for (int c0 = 0; c0 < N; c0 += PASS) {
-        const bool first_pass = c0 == 0;
-        // this wavefront's column tiles in the packed text: byte offsets (32 bits: checked by the host) of the lane's
-        // 16 bytes in the tile's first operand; tiles past the end re-read the last one (their weights are zero)
-        uint32_t ob[PA_CT];
+        const float count = (c0 == 0 && cb < RT) ? 1.f : 0.f;   // |w_k|^2 is summed during the first pass, by the tile's owner (a factor, not a branch)
+        // this wavefront's column tiles in the packed text (tiles past the end re-read the last one: their weights
+        // are zero); a lane's 16 bytes of operand c of a tile sit at 1024 c + 16 lane
+        const char* tile[PA_CT];
 #pragma unroll
-        for (int k = 0; k < PA_CT; k++)
-            ob[k] = (uint32_t)min((c0 + cb * PA_WCOLS) / 16 + k, ntile - 1) * (uint32_t)(D / 32) * 1024u + (uint32_t)lane * 16u;
+        for (int k = 0; k < PA_CT; k++) tile[k] = tbb + (int64_t)min((c0 + cb * PA_WCOLS) / 16 + k, ntile - 1) * (D / 32) * 1024;
         auto load_b = [&](int c, uint4 (&gb)[PA_CT]) {    // elements 32 c .. 32 c + 31 of D
+            const uint32_t off = (uint32_t)(c * 1024) + (uint32_t)lane * 16u;
 #pragma unroll
-            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tbb + (ob[k] + (uint32_t)(c * 1024)));
+            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tile[k] + off);
         };
         floatx4s acc[RT][PA_CT];
 #pragma unroll
@@ -326,65 +379,95 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
 #pragma unroll
             for (int k = 0; k < PA_CT; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
 
-        __syncthreads();                                  // the previous pass is done with W and with both A buffers
+        __syncthreads();                                  // the previous pass is done with W and with both buffers
         for (int k = tid; k < PASS; k += PA_THREADS) sm.W[k] = (c0 + k < N) ? inv_tn[c0 + k] : 0.f;
-        // gx, gy: B operands of the even and odd quarters of a step; ga: visual rows of the next step
-        uint4 ga[PA_NU], gx[PA_CT], gy[PA_CT];
+        __syncthreads();
+        // gq[q]: B operands of quarter q of a step, sent for a whole step ahead (replaced one by one during the following
+        // quarter, three quarters ahead, they cost 8 % more cycles: the text does not always come from the nearest cache)
+        uint4 gq[PA_Q][PA_CT];
         const int last_c = D / 32 - 1;
-        load_b(0, gx);
-        load_b(1, gy);
-        load_a(0, ga);
-        store_a(0, ga, first_pass ? 1.f : 0.f);
-        load_a(min(1, steps - 1), ga);
+        send_rows(PairBuf<0>{}, 0);
+#pragma unroll
+        for (int q = 0; q < PA_Q; q++) load_b(min(q, last_c), gq[q]);
+        use(peek(PairBuf<0>{}));
 
         // step s: LDS buffer s % 2 x the B operands, a quarter (32 elements of D) at a time.  No branches: the body
         // stays one block, which keeps the wait counts of the loads in flight exact.  Past the end the last
         // operands are fetched again, unused.
-        for (int s = 0; s < steps; s++) {
-            const int buf = s & 1;
-            __syncthreads();                              // A tile of step s is written; the other buffer is free
+        auto step = [&](auto P, int s) {
+            using Cur = decltype(P);
+            using Nxt = PairBuf<1 - Cur::value>;
+            // every wavefront's rows of step s have landed (each waited for its own before it came here), and all
+            // are done reading the other buffer.  No fence: a fence would wait for the B operands in flight.
+            asm volatile("s_barrier" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
-            const uint16_t* sa = &sm.A[0][(rb * 16 + lm) * PA_PITCH + lj * 8] + buf * (PA_ROWS * PA_PITCH);
+            send_rows(Nxt{}, min(s + 1, steps - 1));
+            const char* const sa = reinterpret_cast<const char*>(Cur::value ? pair_a1 : pair_a0);
             // PA_Q RT groups of PA_CT products: row tile i, quarter q; the A operand is read from LDS two groups
-            // ahead.  A quarter's B operands are replaced as soon as their last product has issued, so they have
-            // a quarter of a step to arrive (the packed text is in L2).
-            auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + (g % RT) * 16 * PA_PITCH + (g / RT) * 32); };
+            // ahead.  A quarter's B operands are replaced as soon as their last product has issued.
+            auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + ro[g % RT] + (g / RT) * 64); };
             uint4 f[3];
+            uint32_t landed = 0u;
             f[0] = read_a(0);
             f[1] = read_a(1);
 #pragma unroll
             for (int g = 0; g < PA_Q * RT; g++) {
                 const int i = g % RT, q = g / RT;
                 if (g + 2 < PA_Q * RT) f[(g + 2) % 3] = read_a(g + 2);
+                if (g == PA_Q * RT - 2) landed = peek(Nxt{});         // waits for the next step's rows, as late as it can
+                if (i == 0) nsq = fmaf(sumsq8<BF>(f[g % 3]), count, nsq);
 #pragma unroll
-                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], (q & 1) == 0 ? gx[k] : gy[k], acc[i][k]);
-                if (i == RT - 1) {                        // quarter q is done: its buffer takes quarter q + 2
-                    const int c = min(PA_Q * s + q + 2, last_c);
-                    if ((q & 1) == 0) load_b(c, gx); else load_b(c, gy);
-                }
+                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], gq[q][k], acc[i][k]);
+                if (i == RT - 1) load_b(min(PA_Q * (s + 1) + q, last_c), gq[q]);
                 __builtin_amdgcn_sched_barrier(0);        // issue order as written: one LDS read, then the group's products
             }
-            // the next step's rows (sent for a step ago) go to the other LDS buffer; then send for the rows after them
-            store_a(buf ^ 1, ga, (first_pass && s + 1 < steps) ? 1.f : 0.f);
-            load_a(min(s + 2, steps - 1), ga);
+            use(landed);
+        };
+        int s = 0;
+        for (; s + 1 < steps; s += 2) {
+            step(PairBuf<0>{}, s);
+            step(PairBuf<1>{}, s + 1);
         }
+        if (s < steps) step(PairBuf<0>{}, s);
 
-        // epilogue: lane holds rows 4 lj + e of row tile i, column lm of column tile k
+        // epilogue: the lane holds, of its i-th row tile, rows 4 lj + e at column lm of column tile k.  Scale by
+        // 1/|t_j| and sum over the wavefront's 64 columns: over k in the lane, over lm across the 16 lanes of a row
+        // in four stages of pairwise exchanges, each of which halves the number of values a lane carries (the
+        // partners are lm ^ 8, lm ^ 7, lm ^ 2, lm ^ 1; the stages split on bits 3, 2, 1, 0 of lm).
         float wk[PA_CT];
 #pragma unroll
         for (int k = 0; k < PA_CT; k++) wk[k] = sm.W[cb * PA_WCOLS + k * 16 + lm];
+        float v[32];
 #pragma unroll
-        for (int i = 0; i < RT; i++) {
+        for (int i = 0; i < RT; i++)
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                float v = 0.f;
+                float x = 0.f;
 #pragma unroll
-                for (int k = 0; k < PA_CT; k++) v = fmaf(acc[i][k][e], wk[k], v);
-                v += __shfl_xor(v, 1, 64);
-                v += __shfl_xor(v, 2, 64);
-                v += __shfl_xor(v, 4, 64);
-                v += __shfl_xor(v, 8, 64);
-                if (lm == 0) sm.R[cb][(rb + i) * 16 + 4 * lj + e] += v;     // one writer per (column block, row)
+                for (int k = 0; k < PA_CT; k++) x = fmaf(acc[i][k][e], wk[k], x);
+                v[i * 4 + e] = x;
+            }
+        constexpr int NV = RT > 4 ? 32 : RT * 4;            // a power of two
+#pragma unroll
+        for (int j = RT * 4; j < NV; j++) v[j] = 0.f;
+        pair_halve<0x128, NV>(v, (lm & 8) != 0);                    // row_ror:8
+        pair_halve<0x141, NV / 2>(v, (lm & 4) != 0);                // row_half_mirror
+        pair_halve<0x4E, (NV >= 4 ? NV / 4 : 1)>(v, (lm & 2) != 0); // quad_perm [2,3,0,1]
+        pair_halve<0xB1, (NV >= 8 ? NV / 8 : 1)>(v, (lm & 1) != 0); // quad_perm [1,0,3,2]
+        // what is left: values j0 .. j0 + KEEP - 1 of the NV (j = 4 i + e), j0 made of the bits of lm that split a
+        // stage; a stage that did not split left the sum in both lanes, the lower one writes
+        constexpr int KEEP = NV >= 16 ? NV / 16 : 1;
+        int j0 = 0;
+        bool writer = true;
+        if constexpr (NV >= 2) j0 += (lm & 8) ? NV / 2 : 0;
+        if constexpr (NV >= 4) j0 += (lm & 4) ? NV / 4 : 0;
+        if constexpr (NV >= 8) j0 += (lm & 2) ? NV / 8 : 0; else writer = writer && !(lm & 2);
+        if constexpr (NV >= 16) j0 += (lm & 1) ? NV / 16 : 0; else writer = writer && !(lm & 1);
+        if (writer) {
+#pragma unroll
+            for (int r = 0; r < KEEP; r++) {
+                const int j = j0 + r, tile = rb + ((j >> 2) + cb) % RT;
+                if ((j >> 2) < RT) sm.R[cb][tile * 16 + 4 * lj + (j & 3)] += v[r];    // one writer per (column block, row)
             }
         }
     }
@@ -394,38 +477,39 @@ template <bool BF>
 __global__ __launch_bounds__(PA_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_pair_mfma(const uint16_t* __restrict__ vis, const uint4* __restrict__ packed_txt,
                                                           const float* __restrict__ inv_tnorm, int D,
                                                           const int32_t* __restrict__ vis_off, const int32_t* __restrict__ txt_off,
-                                                          float* __restrict__ tok_score)
+                                                          int rows, float* __restrict__ tok_score)
 {
     __shared__ PairSmem sm;
     const int b = blockIdx.y;
     const int m0 = vis_off[b], M = vis_off[b + 1] - m0;
     const int n0 = txt_off[b], N = txt_off[b + 1] - n0;
-    const int row0 = blockIdx.x * PA_ROWS;
+    const int row0 = blockIdx.x * rows;                 // rows: 128, 112 or 96 visual rows per workgroup
     if (row0 >= M) return;
     const int tid = threadIdx.x;
     for (int k = tid; k < PA_WAVES * PA_ROWS; k += PA_THREADS) sm.R[k / PA_ROWS][k % PA_ROWS] = 0.f;
-    float nsq[PA_NU];
-#pragma unroll
-    for (int u = 0; u < PA_NU; u++) nsq[u] = 0.f;
+    float nsq = 0.f;
     const uint16_t* va = vis + (int64_t)m0 * D;
     const char* tb = reinterpret_cast<const char*>(packed_txt) + (int64_t)pair_tile_base(txt_off, b) * (D / 32) * 1024;
-    if (N > 4 * PA_WCOLS)
-        pair_body<BF, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
-    else if (N > 2 * PA_WCOLS)
-        pair_body<BF, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
-    else
-        pair_body<BF, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, nsq);
-    // |w_k|^2: the PA_PPR threads that staged a row hold its 16-byte pieces of every step
-    const int pp = tid % PA_PPR, pr = tid / PA_PPR;
-#pragma unroll
-    for (int u = 0; u < PA_NU; u++) {
-        float v = nsq[u];
-#pragma unroll
-        for (int o = 1; o < PA_PPR; o <<= 1) v += __shfl_xor(v, o, 64);
-        if (pp == 0) sm.N2[pr + PA_RPT * u] = v;
+    if (N > 4 * PA_WCOLS) {
+        if (rows == 128)
+            pair_body<BF, 8, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
+        else if (rows == 112)
+            pair_body<BF, 7, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
+        else
+            pair_body<BF, 6, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
+    } else if (N > 2 * PA_WCOLS) {                        // (fewer rows than 128: the last row tiles are empty)
+        pair_body<BF, 4, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
+    } else {
+        pair_body<BF, 2, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
     }
+    // |w_k|^2: a wavefront summed row tile number `wave` (in every tiling the first tile it walks; with seven or six
+    // tiles the last wavefronts summed nothing and write zeros to rows that do not exist); its lane (lm, lj) holds the
+    // sum over the pieces lj, lj + 4, ... of row lm
+    nsq += __shfl_xor(nsq, 16, 64);
+    nsq += __shfl_xor(nsq, 32, 64);
+    if ((tid & 63) < 16) sm.N2[(tid >> 6) * 16 + (tid & 15)] = nsq;
     __syncthreads();
-    if (tid < PA_ROWS && row0 + tid < M) {
+    if (tid < rows && row0 + tid < M) {
         float r = 0.f;
 #pragma unroll
         for (int c = 0; c < PA_WAVES; c++) r += sm.R[c][tid];
@@ -507,12 +591,27 @@ int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, i
         if (total_vis > 0) {
             const int64_t items = tiles * (D / 32);
             hipLaunchKernelGGL(k_pack_text, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, st, t16, D, B, txt_off, tiles, packed);
+            // rows per workgroup: a workgroup occupies a compute unit, so the launch runs in rounds of as many
+            // workgroups as the chip has compute units; take the size whose rounds cover the fewest rows in all
+            static int cus = 0;
+            if (cus <= 0) {
+                int dev = 0;
+                if (hipGetDevice(&dev) != hipSuccess ||
+                    hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+                    cus = 256;
+            }
+            int rows = PA_ROWS;
+            int64_t best = 0;
+            for (int r = PA_ROWS; r >= 96; r -= 16) {
+                const int64_t wgs = (total_vis + r - 1) / r, cost = ((wgs + cus - 1) / cus) * r;
+                if (r == PA_ROWS || cost < best) { best = cost; rows = r; }
+            }
             // any one sequence has at most total_vis rows: row tiles past a sequence's end return at once
-            const dim3 grid((unsigned)((total_vis + PA_ROWS - 1) / PA_ROWS), B);
+            const dim3 grid((unsigned)((total_vis + rows - 1) / rows), B);
             if (dtype == WQ_BF16)
-                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, rows, tok_score);
             else
-                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, rows, tok_score);
         }
         hipLaunchKernelGGL(k_window_mean, dim3((unsigned)((total_win + 3) / 4)), dim3(256), 0, st, tok_score, B, vis_off, txt_off,
                            win_size, win_off, total_win, scores);
