@@ -303,24 +303,32 @@ __device__ __forceinline__ void pair_halve(float (&v)[32], bool upper)
     }
 }
 
+constexpr int PA_WCAP = 1024;            // text columns whose 1/|t_j| stay in LDS for a whole run
 struct PairSmem {
-    float W[PA_WAVES * PA_WCOLS];        // 1/|t_j| of the pass (0 past the end)
+    float W[PA_WCAP];                    // 1/|t_j| (0 past the end): of all passes if they fit, else of the current one
     float R[PA_WAVES][PA_ROWS];          // row sums, one array per column block
     float N2[PA_ROWS];                   // |w_k|^2
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 template <int P> struct PairBuf { static constexpr int value = P; };
+struct PairUnit { int tile, pass; };     // a row tile of the sequence x a pass of columns
 
+// A run: `ntiles` consecutive row tiles of one sequence, from tile `tile0`, each walked in ceil(N / PASS) passes of PASS
+// text columns; a (tile, pass) is a unit of D / 128 steps.  All units of a run form one pipeline: during a unit's last
+// step the first rows and text operands of the next unit are already sent for, so the matrix cores do not wait for
+// memory at the start of a tile, and what a unit leaves behind (scaling by 1/|t_j|, the sum over its columns, at a
+// tile's end the scores) happens while those loads are in flight.
 // The eight wavefronts are NCB column blocks of 64 text columns x 8 / NCB row groups of RT row tiles of 16:
 // (RT, NCB) = (8, 8): 128 rows x a 512-column pass; (4, 4): two row halves x 256 columns; (2, 2): four row quarters
-// x 128 columns; (7, 8) and (6, 8): 112 and 96 rows x 512 columns, for launches whose number of 128-row workgroups
+// x 128 columns; (7, 8) and (6, 8): 112 and 96 rows x 512 columns, for launches whose number of 128-row tiles
 // would leave most of the chip idle in the last round.  A wavefront walks its row tiles starting at the one with
 // its column block's number, so that the wavefronts of a row group start on different tiles; the first tile of a
 // wavefront whose column block's number is below RT is the one whose |w_k|^2 it sums on the way.
 template <bool BF, int RT, int NCB>
-__device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
-                                          const float* __restrict__ inv_tn, int D, int M, int N, int row0, int rows, float& nsq)
+__device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
+                                         const float* __restrict__ inv_tn, int D, int M, int N, int tile0, int ntiles, int rows,
+                                         float* __restrict__ out)
 {
     constexpr int PASS = NCB * PA_WCOLS;                  // columns per pass
     constexpr int DMA = (RT * (PA_WAVES / NCB) * 16 * PA_PCS + 64 * PA_WAVES - 1) / (64 * PA_WAVES);   // loads to LDS per wavefront and step
@@ -328,26 +336,29 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lj = lane >> 4, lm = lane & 15;
     const int cb = wave % NCB, rb = (wave / NCB) * RT;
-    const int steps = D / PA_KS, ntile = (N + 15) >> 4;
+    const int steps = D / PA_KS, ntile = (N + 15) >> 4, npass = (N + PASS - 1) / PASS;
 
     // visual rows: memory -> LDS without passing registers.  A load instruction fills 64 consecutive 16-byte pieces
-    // of the buffer, one per lane; piece p is column p % PA_PCS of row p / PA_PCS.  The descriptor covers this
-    // workgroup's rows only: padding columns and rows past the sequence's end lie outside it and read as zero.
-    const int rows_here = min(rows, M - row0);
-    const __amdgpu_buffer_rsrc_t vrows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(va + (int64_t)row0 * D), 0,
-                                                                           rows_here * D * 2, 0x00020000);
+    // of the buffer, one per lane; piece p is column p % PA_PCS of row p / PA_PCS.  The descriptor covers the tile's
+    // rows only: rows past the sequence's end lie outside it and read as zero, as do the padding columns and the
+    // rows past the tile, whose offsets are out of any range.
+    auto rows_of = [&](PairUnit u) {
+        const int row0 = u.tile * rows;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(va + (int64_t)row0 * D), 0, min(rows, M - row0) * D * 2,
+                                                 0x00020000);
+    };
     int voff[DMA];
 #pragma unroll
     for (int t = 0; t < DMA; t++) {
         const int p = (wave + PA_WAVES * t) * 64 + lane, r = p / PA_PCS, c = p - r * PA_PCS;
-        voff[t] = (c < PA_KS / 8 && r < rows_here) ? (r * D + c * 8) * 2 : (int)0x80000000;
+        voff[t] = (c < PA_KS / 8 && r < rows) ? (r * D + c * 8) * 2 : (int)0x80000000;
     }
-    auto send_rows = [&](auto P, int s) {                 // step s of D -> buffer P
+    auto send_rows = [&](auto P, __amdgpu_buffer_rsrc_t tile_rows, int byte0) {     // 256 bytes of every row, from byte0 -> buffer P
         uint16_t* const dst = decltype(P)::value ? pair_a1 : pair_a0;
 #pragma unroll
         for (int t = 0; t < DMA; t++)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrows, (lds_ptr_t)(dst + (wave + PA_WAVES * t) * 512), 16, voff[t],
-                                                     s * (PA_KS * 2), 0, PA_ROW_POLICY);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(tile_rows, (lds_ptr_t)(dst + (wave + PA_WAVES * t) * 512), 16, voff[t], byte0, 0,
+                                                     PA_ROW_POLICY);
     };
     // byte offsets of this lane's operand pieces, row tile by row tile in the wavefront's own order
     int ro[RT];
@@ -360,83 +371,67 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
         return *reinterpret_cast<const uint32_t*>(src + ro[0]);
     };
     auto use = [&](uint32_t x) { asm volatile("" ::"v"(x)); };
+    // the wavefront's column tiles of a pass in the packed text (tiles past the end re-read the last one: their
+    // weights are zero); a lane's 16 bytes of operand c of a tile sit at 1024 c + 16 lane
+    auto text_of = [&](PairUnit u, const char* (&t)[PA_CT]) {
+#pragma unroll
+        for (int k = 0; k < PA_CT; k++)
+            t[k] = tbb + (int64_t)min((u.pass * PASS + cb * PA_WCOLS) / 16 + k, ntile - 1) * (D / 32) * 1024;
+    };
+    auto load_b = [&](const char* const (&t)[PA_CT], int c, uint4 (&gb)[PA_CT]) {      // elements 32 c .. 32 c + 31 of D
+        const uint32_t off = (uint32_t)(c * 1024) + (uint32_t)lane * 16u;
+#pragma unroll
+        for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(t[k] + off);
+    };
+    auto after = [&](PairUnit u) {                        // the unit after u; the run's last unit is followed by itself
+        if (++u.pass == npass) { u.pass = 0; ++u.tile; }
+        if (u.tile == tile0 + ntiles) { u.tile = tile0 + ntiles - 1; u.pass = npass - 1; }
+        return u;
+    };
+    // 1/|t_j| in LDS: all passes' at once if they fit, else pass by pass (the slow way: behind a barrier at a unit's end)
+    const bool w_all = npass * PASS <= PA_WCAP;
+    auto stage_weights = [&](int col0, int n) {
+        for (int k = threadIdx.x; k < n; k += PA_THREADS) sm.W[k] = col0 + k < N ? inv_tn[col0 + k] : 0.f;
+    };
 
-    for (int c0 = 0; c0 < N; c0 += PASS) {
-        const float count = (c0 == 0 && cb < RT) ? 1.f : 0.f;   // |w_k|^2 is summed during the first pass, by the tile's owner (a factor, not a branch)
-        // this wavefront's column tiles in the packed text (tiles past the end re-read the last one: their weights
-        // are zero); a lane's 16 bytes of operand c of a tile sit at 1024 c + 16 lane
-        const char* tile[PA_CT];
+    // uc: the unit whose products are being summed; un: the one after it; dc, tc: where the loads being sent go to
+    // in memory (uc's rows and text until uc's last step, then un's)
+    PairUnit uc{tile0, 0}, un = after(uc);
+    __amdgpu_buffer_rsrc_t dc = rows_of(uc);
+    const char* tc[PA_CT];
+    text_of(uc, tc);
+    floatx4s acc[RT][PA_CT];
 #pragma unroll
-        for (int k = 0; k < PA_CT; k++) tile[k] = tbb + (int64_t)min((c0 + cb * PA_WCOLS) / 16 + k, ntile - 1) * (D / 32) * 1024;
-        auto load_b = [&](int c, uint4 (&gb)[PA_CT]) {    // elements 32 c .. 32 c + 31 of D
-            const uint32_t off = (uint32_t)(c * 1024) + (uint32_t)lane * 16u;
+    for (int i = 0; i < RT; i++)
 #pragma unroll
-            for (int k = 0; k < PA_CT; k++) gb[k] = *reinterpret_cast<const uint4*>(tile[k] + off);
-        };
-        floatx4s acc[RT][PA_CT];
-#pragma unroll
-        for (int i = 0; i < RT; i++)
-#pragma unroll
-            for (int k = 0; k < PA_CT; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < PA_CT; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
+    float nsq = 0.f;
+    int s = 0;
 
-        __syncthreads();                                  // the previous pass is done with W and with both buffers
-        for (int k = tid; k < PASS; k += PA_THREADS) sm.W[k] = (c0 + k < N) ? inv_tn[c0 + k] : 0.f;
-        __syncthreads();
-        // gq[q]: B operands of quarter q of a step, sent for a whole step ahead (replaced one by one during the following
-        // quarter, three quarters ahead, they cost 8 % more cycles: the text does not always come from the nearest cache)
-        uint4 gq[PA_Q][PA_CT];
-        const int last_c = D / 32 - 1;
-        send_rows(PairBuf<0>{}, 0);
+    __syncthreads();                                      // whoever used the buffers before is done with them
+    stage_weights(0, w_all ? npass * PASS : PASS);
+    __syncthreads();
+    // gq[q]: B operands of quarter q of a step, sent for a whole step ahead (replaced one by one during the following
+    // quarter, three quarters ahead, they cost 8 % more cycles: the text does not always come from the nearest cache)
+    uint4 gq[PA_Q][PA_CT];
+    send_rows(PairBuf<0>{}, dc, 0);
 #pragma unroll
-        for (int q = 0; q < PA_Q; q++) load_b(min(q, last_c), gq[q]);
-        use(peek(PairBuf<0>{}));
+    for (int q = 0; q < PA_Q; q++) load_b(tc, q, gq[q]);
+    use(peek(PairBuf<0>{}));
 
-        // step s: LDS buffer s % 2 x the B operands, a quarter (32 elements of D) at a time.  No branches: the body
-        // stays one block, which keeps the wait counts of the loads in flight exact.  Past the end the last
-        // operands are fetched again, unused.
-        auto step = [&](auto P, int s) {
-            using Cur = decltype(P);
-            using Nxt = PairBuf<1 - Cur::value>;
-            // every wavefront's rows of step s have landed (each waited for its own before it came here), and all
-            // are done reading the other buffer.  No fence: a fence would wait for the B operands in flight.
-            asm volatile("s_barrier" ::: "memory");
-            __builtin_amdgcn_sched_barrier(0);
-            send_rows(Nxt{}, min(s + 1, steps - 1));
-            const char* const sa = reinterpret_cast<const char*>(Cur::value ? pair_a1 : pair_a0);
-            // PA_Q RT groups of PA_CT products: row tile i, quarter q; the A operand is read from LDS two groups
-            // ahead.  A quarter's B operands are replaced as soon as their last product has issued.
-            auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + ro[g % RT] + (g / RT) * 64); };
-            uint4 f[3];
-            uint32_t landed = 0u;
-            f[0] = read_a(0);
-            f[1] = read_a(1);
-#pragma unroll
-            for (int g = 0; g < PA_Q * RT; g++) {
-                const int i = g % RT, q = g / RT;
-                if (g + 2 < PA_Q * RT) f[(g + 2) % 3] = read_a(g + 2);
-                if (g == PA_Q * RT - 2) landed = peek(Nxt{});         // waits for the next step's rows, as late as it can
-                if (i == 0) nsq = fmaf(sumsq8<BF>(f[g % 3]), count, nsq);
-#pragma unroll
-                for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], gq[q][k], acc[i][k]);
-                if (i == RT - 1) load_b(min(PA_Q * (s + 1) + q, last_c), gq[q]);
-                __builtin_amdgcn_sched_barrier(0);        // issue order as written: one LDS read, then the group's products
-            }
-            use(landed);
-        };
-        int s = 0;
-        for (; s + 1 < steps; s += 2) {
-            step(PairBuf<0>{}, s);
-            step(PairBuf<1>{}, s + 1);
-        }
-        if (s < steps) step(PairBuf<0>{}, s);
-
-        // epilogue: the lane holds, of its i-th row tile, rows 4 lj + e at column lm of column tile k.  Scale by
-        // 1/|t_j| and sum over the wavefront's 64 columns: over k in the lane, over lm across the 16 lanes of a row
-        // in four stages of pairwise exchanges, each of which halves the number of values a lane carries (the
-        // partners are lm ^ 8, lm ^ 7, lm ^ 2, lm ^ 1; the stages split on bits 3, 2, 1, 0 of lm).
+    // What a unit leaves behind.  The lane holds, of its i-th row tile, rows 4 lj + e at column lm of column tile k.
+    // Scale by 1/|t_j| and sum over the wavefront's 64 columns: over k in the lane, over lm across the 16 lanes of a
+    // row in four stages of pairwise exchanges, each of which halves the number of values a lane carries (the
+    // partners are lm ^ 8, lm ^ 7, lm ^ 2, lm ^ 1; the stages split on bits 3, 2, 1, 0 of lm).
+    // (Both work from a copy of the thread's number that the compiler cannot trace: what they derive from it is then
+    // computed here, once per unit, rather than kept in registers throughout the steps.)
+    auto unit_done = [&]() {
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        const int lm = t & 15, lj = (t >> 4) & 3;
         float wk[PA_CT];
 #pragma unroll
-        for (int k = 0; k < PA_CT; k++) wk[k] = sm.W[cb * PA_WCOLS + k * 16 + lm];
+        for (int k = 0; k < PA_CT; k++) wk[k] = sm.W[(w_all ? uc.pass * PASS : 0) + cb * PA_WCOLS + k * 16 + lm];
         float v[32];
 #pragma unroll
         for (int i = 0; i < RT; i++)
@@ -447,6 +442,10 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
                 for (int k = 0; k < PA_CT; k++) x = fmaf(acc[i][k][e], wk[k], x);
                 v[i * 4 + e] = x;
             }
+#pragma unroll
+        for (int i = 0; i < RT; i++)
+#pragma unroll
+            for (int k = 0; k < PA_CT; k++) acc[i][k] = floatx4s{0.f, 0.f, 0.f, 0.f};
         constexpr int NV = RT > 4 ? 32 : RT * 4;            // a power of two
 #pragma unroll
         for (int j = RT * 4; j < NV; j++) v[j] = 0.f;
@@ -470,51 +469,138 @@ __device__ __forceinline__ void pair_body(PairSmem& sm, const uint16_t* __restri
                 if ((j >> 2) < RT) sm.R[cb][tile * 16 + 4 * lj + (j & 3)] += v[r];    // one writer per (column block, row)
             }
         }
+    };
+    // A tile's last unit is done: its scores.  |w_k|^2: a wavefront summed row tile number `wave` (in every tiling the
+    // first tile it walks; with seven or six tiles the last wavefronts summed nothing and write zeros to rows that do
+    // not exist); its lane (lm, lj) holds the sum over the pieces lj, lj + 4, ... of row lm.
+    auto tile_done = [&](int tile) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        nsq += __shfl_xor(nsq, 16, 64);
+        nsq += __shfl_xor(nsq, 32, 64);
+        if (lane < 16) sm.N2[wave * 16 + lane] = nsq;
+        nsq = 0.f;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // (no fence: loads for the next unit are in flight)
+        const int row = tile * rows + tid;
+        if (tid < PA_ROWS) {
+            float r = 0.f;
+#pragma unroll
+            for (int c = 0; c < PA_WAVES; c++) {
+                r += sm.R[c][tid];
+                sm.R[c][tid] = 0.f;                       // for the next tile; the barriers of its steps come before its sums
+            }
+            const float nn = sm.N2[tid];
+            if (tid < rows && row < M) out[row] = nn > 0.f ? r / (sqrtf(nn) * (float)N) : 0.f;
+        }
+    };
+
+    // A step: LDS buffer P x the B operands, a quarter (32 elements of D) at a time.  The products' part has no
+    // branches: it stays one block, which keeps the wait counts of the loads in flight exact.
+    auto step = [&](auto P) {
+        using Cur = decltype(P);
+        using Nxt = PairBuf<1 - Cur::value>;
+        // every wavefront's rows of this step have landed (each waited for its own before it came here), and all are
+        // done reading the other buffer.  No fence: a fence would wait for the B operands in flight.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        // the step after this one: of this unit, or the first of the next unit
+        const bool last = s == steps - 1;
+        const int sx = last ? 0 : s + 1;
+        if (last) {
+            dc = rows_of(un);
+            text_of(un, tc);
+        }
+        send_rows(Nxt{}, dc, sx * (PA_KS * 2));
+        const float count = (uc.pass == 0 && cb < RT) ? 1.f : 0.f;   // |w_k|^2 is summed during the first pass, by the tile's owner (a factor, not a branch)
+        const char* const sa = reinterpret_cast<const char*>(Cur::value ? pair_a1 : pair_a0);
+        // PA_Q RT groups of PA_CT products: row tile i, quarter q; the A operand is read from LDS two groups
+        // ahead.  A quarter's B operands are replaced as soon as their last product has issued.
+        auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + ro[g % RT] + (g / RT) * 64); };
+        uint4 f[3];
+        uint32_t landed = 0u;
+        f[0] = read_a(0);
+        f[1] = read_a(1);
+#pragma unroll
+        for (int g = 0; g < PA_Q * RT; g++) {
+            const int i = g % RT, q = g / RT;
+            if (g + 2 < PA_Q * RT) f[(g + 2) % 3] = read_a(g + 2);
+            if (g == PA_Q * RT - 2) landed = peek(Nxt{});             // waits for the next step's rows, as late as it can
+            if (i == 0) nsq = fmaf(sumsq8<BF>(f[g % 3]), count, nsq);
+#pragma unroll
+            for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], gq[q][k], acc[i][k]);
+            if (i == RT - 1) load_b(tc, PA_Q * sx + q, gq[q]);
+            __builtin_amdgcn_sched_barrier(0);            // issue order as written: one LDS read, then the group's products
+        }
+        use(landed);
+        if (last) {
+            unit_done();
+            if (uc.pass == npass - 1) tile_done(uc.tile);
+            if (!w_all) {
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // all have read this unit's weights
+                stage_weights(un.pass * PASS, PASS);
+            }
+            s = 0;
+            uc = un;
+            un = after(un);
+        } else {
+            ++s;
+        }
+    };
+    const int total = ntiles * npass * steps;
+    int gs = 0;
+    for (; gs + 1 < total; gs += 2) {
+        step(PairBuf<0>{});
+        step(PairBuf<1>{});
     }
+    if (gs < total) step(PairBuf<0>{});
 }
 
+// The launch's row tiles (`rows` = 128, 112 or 96 visual rows) are numbered sequence after sequence; a workgroup takes
+// a contiguous share of them and walks it as runs of tiles of one sequence.
 template <bool BF>
 __global__ __launch_bounds__(PA_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_pair_mfma(const uint16_t* __restrict__ vis, const uint4* __restrict__ packed_txt,
-                                                          const float* __restrict__ inv_tnorm, int D,
+                                                          const float* __restrict__ inv_tnorm, int D, int B,
                                                           const int32_t* __restrict__ vis_off, const int32_t* __restrict__ txt_off,
                                                           int rows, float* __restrict__ tok_score)
 {
     __shared__ PairSmem sm;
-    const int b = blockIdx.y;
-    const int m0 = vis_off[b], M = vis_off[b + 1] - m0;
-    const int n0 = txt_off[b], N = txt_off[b + 1] - n0;
-    const int row0 = blockIdx.x * rows;                 // rows: 128, 112 or 96 visual rows per workgroup
-    if (row0 >= M) return;
     const int tid = threadIdx.x;
-    for (int k = tid; k < PA_WAVES * PA_ROWS; k += PA_THREADS) sm.R[k / PA_ROWS][k % PA_ROWS] = 0.f;
-    float nsq = 0.f;
-    const uint16_t* va = vis + (int64_t)m0 * D;
-    const char* tb = reinterpret_cast<const char*>(packed_txt) + (int64_t)pair_tile_base(txt_off, b) * (D / 32) * 1024;
-    if (N > 4 * PA_WCOLS) {
-        if (rows == 128)
-            pair_body<BF, 8, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
-        else if (rows == 112)
-            pair_body<BF, 7, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
-        else
-            pair_body<BF, 6, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
-    } else if (N > 2 * PA_WCOLS) {                        // (fewer rows than 128: the last row tiles are empty)
-        pair_body<BF, 4, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
-    } else {
-        pair_body<BF, 2, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, row0, rows, nsq);
-    }
-    // |w_k|^2: a wavefront summed row tile number `wave` (in every tiling the first tile it walks; with seven or six
-    // tiles the last wavefronts summed nothing and write zeros to rows that do not exist); its lane (lm, lj) holds the
-    // sum over the pieces lj, lj + 4, ... of row lm
-    nsq += __shfl_xor(nsq, 16, 64);
-    nsq += __shfl_xor(nsq, 32, 64);
-    if ((tid & 63) < 16) sm.N2[(tid >> 6) * 16 + (tid & 15)] = nsq;
-    __syncthreads();
-    if (tid < rows && row0 + tid < M) {
-        float r = 0.f;
-#pragma unroll
-        for (int c = 0; c < PA_WAVES; c++) r += sm.R[c][tid];
-        const float nn = sm.N2[tid];
-        tok_score[m0 + row0 + tid] = (nn > 0.f && N > 0) ? r / (sqrtf(nn) * (float)N) : 0.f;
+    uint32_t T = 0;
+    for (int b = 0; b < B; b++) T += (uint32_t)(vis_off[b + 1] - vis_off[b] + rows - 1) / (uint32_t)rows;
+    int g = (int)((uint64_t)T * blockIdx.x / gridDim.x);
+    const int end = (int)((uint64_t)T * (blockIdx.x + 1) / gridDim.x);
+    if (g >= end) return;
+    for (int k = tid; k < PA_WAVES * PA_ROWS; k += PA_THREADS) sm.R[k / PA_ROWS][k % PA_ROWS] = 0.f;     // (a run starts with a barrier)
+    int b = 0, first = 0;                                 // first: number of sequence b's first tile
+    while (g < end) {
+        int Tb = (vis_off[b + 1] - vis_off[b] + rows - 1) / rows;
+        while (g >= first + Tb) {
+            first += Tb;
+            ++b;
+            Tb = (vis_off[b + 1] - vis_off[b] + rows - 1) / rows;
+        }
+        const int n = min(end, first + Tb) - g, tile0 = g - first;
+        const int m0 = vis_off[b], M = vis_off[b + 1] - m0;
+        const int n0 = txt_off[b], N = txt_off[b + 1] - n0;
+        const uint16_t* va = vis + (int64_t)m0 * D;
+        const char* tb = reinterpret_cast<const char*>(packed_txt) + (int64_t)pair_tile_base(txt_off, b) * (D / 32) * 1024;
+        float* out = tok_score + m0;
+        if (N <= 0) {
+            for (int r = tile0 * rows + tid; r < min(M, (tile0 + n) * rows); r += PA_THREADS) out[r] = 0.f;
+        } else if (N > 4 * PA_WCOLS) {
+            if (rows == 128)
+                pair_run<BF, 8, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, tile0, n, rows, out);
+            else if (rows == 112)
+                pair_run<BF, 7, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, tile0, n, rows, out);
+            else
+                pair_run<BF, 6, 8>(sm, va, tb, inv_tnorm + n0, D, M, N, tile0, n, rows, out);
+        } else if (N > 2 * PA_WCOLS) {                    // (fewer rows than 128: the last row tiles are empty)
+            pair_run<BF, 4, 4>(sm, va, tb, inv_tnorm + n0, D, M, N, tile0, n, rows, out);
+        } else {
+            pair_run<BF, 2, 2>(sm, va, tb, inv_tnorm + n0, D, M, N, tile0, n, rows, out);
+        }
+        g += n;
     }
 }
 
@@ -606,12 +692,13 @@ int wq_launch_scores(wq_ctx* ctx, const void* vis, const void* txt, int dtype, i
                 const int64_t wgs = (total_vis + r - 1) / r, cost = ((wgs + cus - 1) / cus) * r;
                 if (r == PA_ROWS || cost < best) { best = cost; rows = r; }
             }
-            // any one sequence has at most total_vis rows: row tiles past a sequence's end return at once
-            const dim3 grid((unsigned)((total_vis + rows - 1) / rows), B);
+            // one workgroup per compute unit, or fewer if there are fewer tiles (a sequence has at most one partial tile)
+            const int64_t tiles_most = (total_vis + rows - 1) / rows + B;
+            const dim3 grid((unsigned)(tiles_most < cus ? tiles_most : cus));
             if (dtype == WQ_BF16)
-                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, rows, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<true>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, B, vis_off, txt_off, rows, tok_score);
             else
-                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, vis_off, txt_off, rows, tok_score);
+                hipLaunchKernelGGL(k_pair_mfma<false>, grid, dim3(PA_THREADS), 0, st, v16, packed, inv_norm, D, B, vis_off, txt_off, rows, tok_score);
         }
         hipLaunchKernelGGL(k_window_mean, dim3((unsigned)((total_win + 3) / 4)), dim3(256), 0, st, tok_score, B, vis_off, txt_off,
                            win_size, win_off, total_win, scores);

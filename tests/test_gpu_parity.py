@@ -173,6 +173,32 @@ def test_scores_random_shapes_both_forms():
         H.assert_scores_close(s_pool, want)
 
 
+def test_scores_pairwise_runs_of_tiles_per_workgroup():
+    """More row tiles than the chip has compute units: a workgroup of the matrix-core kernel then walks a contiguous run
+    of tiles, handing the loads of a tile's first step over from the last step of the tile (or pass) before it, and a
+    run ends where a sequence ends.  Four sequences whose text lengths take the kernel through its 128-, 256- and
+    512-column tilings, one, two and three passes (three: the weights do not fit LDS at once), 112-row tiles, ragged
+    ends; against the fp64 oracle's literal pairwise form."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    specs = [synth.SeqSpec(600, 49, 49, 20, (1, 1, 1)),              # 29 400 rows, 20 text tokens
+             synth.SeqSpec(640, 64, 64, 700, (1, 1, 1), tail=7),     # 40 967 rows, two passes of 512 columns
+             synth.SeqSpec(100, 49, 49, 1100, (1, 1, 1)),            # 4 900 rows, three passes
+             synth.SeqSpec(60, 49, 49, 200, (1, 1, 1))]              # 2 940 rows, 256-column tiling
+    w = synth.Workload("pair-runs", synth.BF16, synth.BF16, 28, 4, 128, 64, 128, 1.5, specs, 21)
+    t = synth.tables(w)
+    ets, evs = zip(*[synth.embeddings(w, b) for b in range(w.B)])
+    Et, Ev = np.concatenate(ets), np.concatenate(evs)
+    ctx = W.Context(W.workspace_bytes(w.B, 0, 0, 0, Ev.shape[0], Et.shape[0], w.D))
+    args = (H.to_dev(Ev, w.dtype), H.to_dev(Et, w.dtype), H.i32(t.vis_off), H.i32(t.txt_off), H.i32(t.win_size), H.i32(t.win_off),
+            Ev.shape[0], Et.shape[0], int(t.win_off[-1]))
+    s_mfma = W.wq_window_scores(ctx, *args, algo=W.SCORE_PAIRWISE_MFMA)
+    torch.cuda.synchronize()
+    want = O.window_scores(Ev, Et, t.vis_off, t.txt_off, t.win_size, t.win_off, form="pairwise")
+    H.assert_scores_close(s_mfma, want)
+
+
 def test_decode_fixed_shares_is_reproducible_and_agrees_with_block_pool():
     """WQ_DECODE_FIXED_SHARES: the same bits on every run; the default (blocks handed out as wavefronts get free)
     sums in a run-dependent order and agrees to rounding.  Both are checked against the oracle."""
