@@ -389,8 +389,10 @@ def main():
     n = max(args.steps, 2 * N_COPIES)
     sc_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
                                                total_win, scores=scores), n)
-    scm_us = timed(lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
-                                                total_win, algo=W.SCORE_PAIRWISE_MFMA, scores=scores), max(4, n // 8))
+    pairwise = lambda i: W.wq_window_scores(ctx, E_v, E_t, vis_off, txt_off, win_size, win_off, total_vis, total_txt,
+                                            total_win, algo=W.SCORE_PAIRWISE_MFMA, scores=scores)
+    pairwise(0)                                            # (its first call loads the kernel)
+    scm_us = timed(pairwise, 8)
     pair_flops = sum(2.0 * sq.n_win * sq.win_size * sq.n_text * w.D for sq in w.seqs)
     as_us = timed(lambda i: W.wq_assign_bits(ctx, scores, win_off, max_win, W.MODE_QUOTA, quota, None, w.top_bits, w.pin_first), n)
     rq_us = timed(lambda i: W.wq_reorder_quantize(ctx, K, V, kv_off, win_size, win_off, perm, seg, total_rows, copies[i % N_COPIES]), n)

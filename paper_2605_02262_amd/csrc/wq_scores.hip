@@ -180,26 +180,28 @@ __global__ __launch_bounds__(256) void k_window_mean(const float* __restrict__ t
 
 // ---- pairwise path on the matrix cores --------------------------------------------------------------------------
 // The similarity equation taken literally: C = E_v E_t^T (every window token against every text token), then
-// c_k = 1/(N |w_k|) sum_j C[k,j] / |t_j|.  One workgroup of eight wavefronts owns 128 visual rows of one sequence and
-// walks the text tokens in passes of up to 512 columns, so that the visual rows are read from memory once when the
-// sequence has at most 512 text tokens.  Over D it goes in steps of 128 elements (two 128-byte lines per row):
-//   visual rows   global -> registers (a step ahead) -> LDS (two buffers, one barrier per step) -> A operands of
-//                 all wavefronts, read two products groups ahead of their use;
+// c_k = 1/(N |w_k|) sum_j C[k,j] / |t_j|.  A tile is 128 (112, 96) visual rows of one sequence; its text tokens are
+// walked in passes of up to 512 columns, so that the visual rows are read from memory once when the sequence has at
+// most 512 text tokens.  One workgroup of eight wavefronts per compute unit takes a contiguous share of the launch's
+// tiles.  Over D it goes in steps of 128 elements (two 128-byte lines per row):
+//   visual rows   memory -> LDS directly (buffer loads with the LDS bit, a step ahead, two buffers, one barrier per
+//                 step) -> A operands of all wavefronts, read two product groups ahead of their use;
 //   text rows     each wavefront owns 64 columns of the pass, so its B operands are private to it.  An operand is
 //                 16 rows x 16 bytes per lane group: read from the row-major text that is 64 scattered pieces per
 //                 load, which the memory pipeline takes one lane at a time.  k_pack_text therefore rewrites the text
 //                 once (a few MB) into operand order, [tile of 16 rows][32 elements of D][lane][8 elements], so that
 //                 a wavefront's operand is one contiguous KB; it goes from there (L2) straight into registers, a
-//                 quarter of a step ahead.
+//                 whole step ahead.
 // A wavefront multiplies a [16 RT] x 64 tile per step with v_mfma_f32_16x16x32 bf16/f16 (RT = 8 row tiles: 128
 // accumulator registers, two wavefronts per SIMD).  Sequences with at most 256 (128) text tokens use passes of 256
-// (128) columns and split the rows between wavefronts instead, RT = 4 (2).  The epilogue of a pass multiplies by
-// 1/|t_j| and reduces over the columns, so C never leaves the registers.  |w_k|^2 comes from the visual rows on
-// their way to LDS during the first pass.  Reductions have a fixed order: results are deterministic.
-// With operands that change from product to product the matrix cores of this GPU sustain about two thirds of their
-// nominal rate (wq_probe_mfma measures it: the clock drops under the load); this kernel reaches somewhat more than
-// half of that.  Variants measured and dropped because they were not faster: visual rows sent straight into LDS
-// (no registers) with B operands three quarters of a step ahead; steps of 64 elements.
+// (128) columns and split the rows between wavefronts instead, RT = 4 (2).  At the end of a pass the products are
+// multiplied by 1/|t_j| and summed over the columns, so C never leaves the registers.  |w_k|^2 comes from the A
+// operands of one row tile per wavefront during the first pass.  Reductions have a fixed order: results are
+// deterministic.
+// With operands that change from product to product the matrix cores of this GPU sustain about three quarters of
+// their nominal rate (wq_probe_mfma measures it: the clock drops under the load); this kernel keeps them busy three
+// quarters of its cycles.  Variants measured and dropped because they were not faster: steps of 64 elements; text
+// operands sent for one by one, three quarters of a step ahead; the 32x32x16 form of the instruction.
 typedef float floatx4s __attribute__((ext_vector_type(4)));
 typedef _Float16 half8s __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
