@@ -128,11 +128,46 @@ __global__ __launch_bounds__(256) void k_v_scale_max(int B, wq_packed_kv pk)
 // bits -> class index
 __host__ __device__ constexpr int cls_index(int bits) { return bits == 2 ? 0 : (bits == 4 ? 1 : 2); }
 
+// V codes of a 32-token block on their way into operand order, one byte each: the 8 tokens x HD/16 channel tiles of a
+// lane of the decode kernel's matrix operand (lane = 16 jj + mm holds channels 16 ct + mm of tokens 16 (tau >> 2) +
+// 4 jj + (tau & 3)) lie together, [ct][tau], at lane x VT_PITCH; the 16 bytes of padding keep the readers' 16-byte
+// reads in different banks
 template <int HD>
 struct QuantSmem {
-    uint32_t v[32][HD / 4 + 1];                 // V codes, 4 per word, rows padded by one word (conflict-free column reads)
+    static constexpr int VT_PITCH = (HD / 16) * 8 + 16;
+    __attribute__((aligned(16))) uint8_t vt[64 * VT_PITCH];
     uint32_t meta[2][4][32];                    // [plane][group][token]
 };
+
+template <int CTRL>
+__device__ __forceinline__ float lanes_moved_f(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+
+// 16 codes of BITS bits, one per byte of x[0..3], as consecutive fields: 2 BITS bytes in y
+template <int BITS>
+__device__ __forceinline__ void pack16(const uint32_t (&x)[4], uint32_t (&y)[4])
+{
+    if constexpr (BITS == 8) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) y[i] = x[i];
+    } else if constexpr (BITS == 4) {
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const uint32_t a = x[2 * i] | (x[2 * i] >> 4), b = x[2 * i + 1] | (x[2 * i + 1] >> 4);     // bytes 0 and 2 hold two codes each
+            y[i] = __builtin_amdgcn_perm(b, a, 0x06040200u);                                          // a.b0 a.b2 b.b0 b.b2
+        }
+    } else {
+        uint32_t z[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const uint32_t a = x[i] | (x[i] >> 6);          // bytes 0 and 2 hold two codes each
+            z[i] = a | (a >> 12);                           // byte 0 holds all four
+        }
+        y[0] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(z[3], z[2], 0x0C0C0400u), __builtin_amdgcn_perm(z[1], z[0], 0x0C0C0400u), 0x05040100u);
+    }
+}
 
 // one (32-token destination block `blk` of class BITS, KV head `kvh`)
 template <typename T, int HD, int BITS>
@@ -146,7 +181,6 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
     constexpr int QMAX = (1 << BITS) - 1;
     constexpr int CPT = HD / 8;                 // channels per thread: 8 threads share one token row
     constexpr int PER_DW = 32 / BITS;           // codes per output dword
-    auto& s_v = sm.v;
     auto& s_meta = sm.meta;
     const int tid = threadIdx.x;
     const int Hkv = pk.Hkv;
@@ -191,9 +225,17 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
             for (int i = 0; i < CPT; i++) x[i] = 0.f;
             lo = hi = 0.f;
         }
-        for (int o = 1; o < tpg; o <<= 1) {     // lanes p..p+tpg-1 of a token are adjacent lanes of one wavefront
-            lo = fminf(lo, __shfl_xor(lo, o, 64));
-            hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+        // lanes p..p+tpg-1 of a token are adjacent lanes of one wavefront: partners p ^ 1, p ^ 2, p ^ 7 (lane moves
+        // inside quads and half rows, no LDS)
+        lo = fminf(lo, lanes_moved_f<0xB1>(lo));
+        hi = fmaxf(hi, lanes_moved_f<0xB1>(hi));
+        if (tpg >= 4) {
+            lo = fminf(lo, lanes_moved_f<0x4E>(lo));
+            hi = fmaxf(hi, lanes_moved_f<0x4E>(hi));
+        }
+        if (tpg >= 8) {
+            lo = fminf(lo, lanes_moved_f<0x141>(lo));
+            hi = fmaxf(hi, lanes_moved_f<0x141>(hi));
         }
         if (lo == 0.0f) lo = 0.0f;               // a zero minimum is stored as +0
         const __half mh = __float2half_rn(lo);
@@ -208,24 +250,25 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
         }
         const float inv = 1.0f / s;
         // This thread's codes: the K plane takes them as consecutive BITS-wide fields of its token's row quarter
-        // (pw, stored below); the V plane as bytes, 4 per word (cw), for the transposition through LDS.
+        // (pw, stored below); the V plane goes through LDS, a byte per code, to where the operand order wants it.
         // A token past the end has x = 0 everywhere, which gives m = 0, s = 1 and codes 0.
         constexpr int NB = CPT * BITS / 8;      // bytes of the K fields: 2..16
-        uint32_t cw[CPT / 4], pw[(NB + 3) / 4];
-#pragma unroll
-        for (int i = 0; i < CPT / 4; i++) cw[i] = 0;
+        uint32_t pw[(NB + 3) / 4];
 #pragma unroll
         for (int i = 0; i < (NB + 3) / 4; i++) pw[i] = 0;
+        uint8_t* const vt = sm.vt + ((u >> 2) & 3) * (16 * QuantSmem<HD>::VT_PITCH) + (u & 3) + 4 * (u >> 4);    // lane 16 jj (+ mm), byte tau (+ 8 ct)
 #pragma unroll
         for (int i = 0; i < CPT; i++) {
             float t = (x[i] - m) * inv;         // contraction is off: subtract, round, multiply, round
             float q = rintf(t);
-            q = fminf(fmaxf(q, 0.0f), (float)QMAX);
+            q = __builtin_amdgcn_fmed3f(q, 0.0f, (float)QMAX);      // (the clamp: no NaN comes here)
             const uint32_t code = (uint32_t)(int)q;
-            if (plane == 0)
+            if (plane == 0) {
                 pw[(i * BITS) >> 5] |= code << ((i * BITS) & 31);
-            else
-                cw[i >> 2] |= code << (8 * (i & 3));
+            } else {
+                const int ch = p * CPT + i;     // (ch & 15, ch >> 4 are fixed per i once p is known: CPT divides 16)
+                vt[(ch & 15) * QuantSmem<HD>::VT_PITCH + (ch >> 4) * 8] = (uint8_t)code;
+            }
         }
         if (plane == 0) {
             constexpr int Q = HD / 4;
@@ -241,9 +284,6 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
             } else {
                 *reinterpret_cast<uint4*>(out) = uint4{pw[0], pw[1], pw[2], pw[3]};
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < CPT / 4; i++) s_v[u][p * (CPT / 4) + i] = cw[i];
         }
         if ((p * CPT) % group == 0) {
             uint32_t word = valid ? ((uint32_t)__half_as_ushort(sh) | ((uint32_t)__half_as_ushort(mh) << 16)) : 0u;
@@ -262,24 +302,22 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
         if (tid == 0) pk.v_scale_max[v_scale_slot(pk, B, C, blk, kvh)] = wq_f16_bits_to_float(top);
     }
 
-    // ---- V plane: block of 32 tokens, field n = ((jj*16 + mm)*(HD/16) + ct)*8 + tau ----------------------
+    // ---- V plane: block of 32 tokens, field n = ((jj*16 + mm)*(HD/16) + ct)*8 + tau: LDS holds the codes in this
+    //      order, a byte each; a thread packs 16 of them (two channel tiles of a lane) into 2 BITS bytes ----------
     {
         constexpr int CT = HD / 16;
-        constexpr int BLK_DW = 32 * HD * BITS / 32;
-        uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(pk.codes[C]) +
-                                                   (((int64_t)Hkv + kvh) * pk.cap[C] + tok0) * HD * BITS / 8);
-        for (int w = tid; w < BLK_DW; w += 256) {
-            uint32_t word = 0;
-#pragma unroll
-            for (int k = 0; k < PER_DW; k++) {
-                int n = w * PER_DW + k;
-                int tau = n & 7, ct = (n >> 3) % CT, lane = (n >> 3) / CT;
-                int jj = lane >> 4, mm = lane & 15;
-                int tok = 16 * (tau >> 2) + 4 * jj + (tau & 3);
-                const int ch = 16 * ct + mm;
-                word |= ((s_v[tok][ch >> 2] >> (8 * (ch & 3))) & 0xFFu) << (k * BITS);
-            }
-            out[w] = word;
+        uint8_t* out = static_cast<uint8_t*>(pk.codes[C]) + (((int64_t)Hkv + kvh) * pk.cap[C] + tok0) * HD * BITS / 8;
+        for (int r = tid; r < 64 * CT / 2; r += 256) {
+            const uint4 c = *reinterpret_cast<const uint4*>(sm.vt + (r / (CT / 2)) * QuantSmem<HD>::VT_PITCH + (r % (CT / 2)) * 16);
+            const uint32_t x[4] = {c.x, c.y, c.z, c.w};
+            uint32_t y[4];
+            pack16<BITS>(x, y);
+            if constexpr (BITS == 8)
+                *reinterpret_cast<uint4*>(out + r * 16) = uint4{y[0], y[1], y[2], y[3]};
+            else if constexpr (BITS == 4)
+                *reinterpret_cast<uint2*>(out + r * 8) = uint2{y[0], y[1]};
+            else
+                *reinterpret_cast<uint32_t*>(out + r * 4) = y[0];
         }
     }
     // ---- metadata: [tile of 16][group][16 tokens] ---------------------------------------------------------
