@@ -321,11 +321,14 @@ __device__ __forceinline__ void quantize_block(QuantSmem<HD>& sm, int blk, int k
         }
     }
     // ---- metadata: [tile of 16][group][16 tokens] ---------------------------------------------------------
-    for (int w = tid; w < 2 * 32 * G; w += 256) {
-        int plane = w / (32 * G), r = w - plane * 32 * G;
-        int tile = r / (16 * G), gi = (r / 16) % G, mrow = r % 16;
-        uint32_t* out = static_cast<uint32_t*>(pk.meta[C]) + (((int64_t)plane * Hkv + kvh) * pk.cap[C] + tok0) * G;
-        out[r] = s_meta[plane][gi][tile * 16 + mrow];
+    {
+        const int lg = G >> 1;                  // log2 of G = 1, 2 or 4: at most 256 words, one per thread
+        if (tid < (64 << lg)) {
+            const int plane = tid >> (5 + lg), r = tid & ((32 << lg) - 1);
+            const int tile = r >> (4 + lg), gi = (r >> 4) & (G - 1), mrow = r & 15;
+            uint32_t* out = static_cast<uint32_t*>(pk.meta[C]) + (((int64_t)plane * Hkv + kvh) * pk.cap[C] + tok0) * G;
+            out[r] = s_meta[plane][gi][tile * 16 + mrow];
+        }
     }
 }
 
