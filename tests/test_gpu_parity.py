@@ -173,13 +173,14 @@ def test_scores_random_shapes_both_forms():
         H.assert_scores_close(s_pool, want)
 
 
-@pytest.mark.parametrize("case", ["112-row tiles", "128-row tiles"])
+@pytest.mark.parametrize("case", ["112-row tiles", "128-row tiles", "96-row tiles"])
 def test_scores_pairwise_runs_of_tiles_per_workgroup(case):
     """More row tiles than the chip has compute units: a workgroup of the matrix-core kernel then walks a contiguous run
     of tiles, handing the loads of a tile's first step over from the last step of the tile (or pass) before it, and a
     run ends where a sequence ends.  First case: four sequences whose text lengths take the kernel through its 128-,
     256- and 512-column tilings, one, two and three passes (three: the weights do not fit LDS at once), 112-row tiles,
-    ragged ends.  Second case: a row count for which the host picks 128-row tiles, two passes.  Against the fp64 oracle's
+    ragged ends.  Second case: a row count for which the host picks 128-row tiles, two passes.  Third case: 96-row tiles and
+    an odd number of steps over D (the two LDS buffers change roles from one unit to the next).  Against the fp64 oracle's
     literal pairwise form."""
     H = _h()
     from oracle import wq_oracle as O
@@ -189,10 +190,14 @@ def test_scores_pairwise_runs_of_tiles_per_workgroup(case):
                  synth.SeqSpec(640, 64, 64, 700, (1, 1, 1), tail=7),     # 40 967 rows, two passes of 512 columns
                  synth.SeqSpec(100, 49, 49, 1100, (1, 1, 1)),            # 4 900 rows, three passes
                  synth.SeqSpec(60, 49, 49, 200, (1, 1, 1))]              # 2 940 rows, 256-column tiling
-    else:
+    elif case == "128-row tiles":
         specs = [synth.SeqSpec(625, 64, 64, 600, (1, 1, 1)),             # 40 000 rows
                  synth.SeqSpec(399, 64, 64, 530, (1, 1, 1))]             # 25 536 rows: 65 536 in all = 2 x 256 tiles of 128
-    w = synth.Workload("pair-runs", synth.BF16, synth.BF16, 28, 4, 128, 64, 128, 1.5, specs, 21)
+    else:
+        specs = [synth.SeqSpec(400, 50, 50, 600, (1, 1, 1)),             # 20 000 rows
+                 synth.SeqSpec(260, 50, 50, 530, (1, 1, 1), tail=3)]     # 13 003 rows: 345 tiles of 96
+    D = 384 if case == "96-row tiles" else 128
+    w = synth.Workload("pair-runs", synth.BF16, synth.BF16, 28, 4, 128, 64, D, 1.5, specs, 21)
     t = synth.tables(w)
     ets, evs = zip(*[synth.embeddings(w, b) for b in range(w.B)])
     Et, Ev = np.concatenate(ets), np.concatenate(evs)
