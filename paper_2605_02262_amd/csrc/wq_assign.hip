@@ -11,34 +11,50 @@ __device__ __forceinline__ int class_of(int bits) { return bits == 2 ? 0 : (bits
 
 constexpr int ASSIGN_THREADS = 1024;
 
-// matches of byte `me` among the four bytes of w
-__device__ __forceinline__ int count_eq_bytes(uint32_t w, uint32_t me)
+// Widths of one sequence are in s_bits: writes them out, counts the classes and lists the windows class by class
+// (2-, 4-, 8-, 16-bit), each class in index order.  A window's place is its class's first place plus the number of
+// earlier windows of its class: counted per chunk of 64 windows with a ballot per class (the earlier lanes of the
+// wavefront), plus the classes' counts over the chunks before it (s_chunk, made a running sum by four lanes).
+constexpr int ASSIGN_CHUNKS = WQ_MAX_WINDOWS / 64;
+__device__ __forceinline__ void emit_class_order(const uint8_t* s_bits, int* s_cnt, int (*s_chunk)[4], int W, int w0, int b,
+                                                 uint8_t* __restrict__ bits, int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
 {
-    return (int)((w & 0xFFu) == me) + (int)(((w >> 8) & 0xFFu) == me) + (int)(((w >> 16) & 0xFFu) == me) + (int)((w >> 24) == me);
-}
-
-// Widths of one sequence are in s_bits (padded with zeros to a multiple of four): writes them out, counts the
-// classes and lists the windows class by class (2-, 4-, 8-, 16-bit), each class in index order.
-__device__ __forceinline__ void emit_class_order(const uint8_t* s_bits, int* s_cnt, int W, int w0, int b, uint8_t* __restrict__ bits,
-                                                 int32_t* __restrict__ perm, int32_t* __restrict__ seg_windows)
-{
-    const int tid = threadIdx.x;
-    for (int i = tid; i < W; i += ASSIGN_THREADS) {
-        bits[w0 + i] = s_bits[i];
-        atomicAdd(&s_cnt[class_of(s_bits[i])], 1);   // integer counts: order-independent
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = ASSIGN_THREADS / 64;
+    const int chunks = (W + 63) >> 6;
+    const unsigned long long earlier = (1ull << lane) - 1ull;
+    for (int ch = wave; ch < chunks; ch += nwaves) {
+        const int i = ch * 64 + lane;
+        const int c = i < W ? class_of(s_bits[i]) : -1;
+        if (i < W) bits[w0 + i] = s_bits[i];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const unsigned long long m = __ballot(c == k);
+            if (lane == 0) s_chunk[ch][k] = __popcll(m);
+        }
     }
     __syncthreads();
-    if (tid < 4) seg_windows[4 * b + tid] = s_cnt[tid];
-    const uint32_t* bits4 = reinterpret_cast<const uint32_t*>(s_bits);
-    for (int i = tid; i < W; i += ASSIGN_THREADS) {
-        int c = class_of(s_bits[i]);
+    if (tid < 4) {                               // a class's count, and its chunks' counts as sums over the chunks before
+        int run = 0;
+        for (int ch = 0; ch < chunks; ch++) {
+            const int n = s_chunk[ch][tid];
+            s_chunk[ch][tid] = run;
+            run += n;
+        }
+        s_cnt[tid] = run;
+        seg_windows[4 * b + tid] = run;
+    }
+    __syncthreads();
+    for (int ch = wave; ch < chunks; ch += nwaves) {
+        const int i = ch * 64 + lane;
+        const int c = i < W ? class_of(s_bits[i]) : -1;
         int pos = 0;
-        for (int k = 0; k < c; k++) pos += s_cnt[k];
-        const uint32_t me = s_bits[i];
-        const int full = i >> 2;
-        for (int j = 0; j < full; j++) pos += count_eq_bytes(bits4[j], me);
-        for (int j = full * 4; j < i; j++) pos += (s_bits[j] == me) ? 1 : 0;
-        perm[w0 + pos] = i;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const unsigned long long m = __ballot(c == k);
+            if (c == k) pos += s_chunk[ch][k] + __popcll(m & earlier);
+            if (c > k) pos += s_cnt[k];          // (accumulates the first places of the classes before c)
+        }
+        if (i < W) perm[w0 + pos] = i;
     }
 }
 
@@ -51,6 +67,7 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_vote(const uint8_t* __restri
 {
     __shared__ __align__(16) uint8_t s_bits[WQ_MAX_WINDOWS + 4];
     __shared__ int s_cnt[4];
+    __shared__ int s_chunk[ASSIGN_CHUNKS][4];
     const int b = blockIdx.x;
     const int w0 = win_off[b];
     int W = win_off[b + 1] - w0;
@@ -75,7 +92,7 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_vote(const uint8_t* __restri
         s_bits[p] = p < W ? (uint8_t)(best == 0 ? 2 : (best == 1 ? 4 : (best == 2 ? 8 : 16))) : (uint8_t)0;
     }
     __syncthreads();                 // every lane is done reading bits_in before anything is written (it may alias bits)
-    emit_class_order(s_bits, s_cnt, W, w0, b, bits, perm, seg_windows);
+    emit_class_order(s_bits, s_cnt, s_chunk, W, w0, b, bits, perm, seg_windows);
 }
 
 __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restrict__ scores, const int32_t* __restrict__ win_off, int mode,
@@ -89,6 +106,7 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restri
     __shared__ __align__(16) float s_key[WQ_MAX_WINDOWS + 4];
     __shared__ __align__(16) uint8_t s_bits[WQ_MAX_WINDOWS + 4];
     __shared__ int s_cnt[4];
+    __shared__ int s_chunk[ASSIGN_CHUNKS][4];
     const int b = blockIdx.x;
     const int w0 = win_off[b];
     int W = win_off[b + 1] - w0;
@@ -150,7 +168,7 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(const float* __restri
         }
     }
     __syncthreads();
-    emit_class_order(s_bits, s_cnt, W, w0, b, bits, perm, seg_windows);
+    emit_class_order(s_bits, s_cnt, s_chunk, W, w0, b, bits, perm, seg_windows);
 }
 
 // Debug aid: is perm[win_off[b] .. win_off[b+1]) a permutation of 0 .. W_b-1, and do the four class counts of the sequence
