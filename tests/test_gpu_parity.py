@@ -963,6 +963,51 @@ def test_adversarial_softmax(hd, g):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("sizes", [(5, 64, 320), (321, 7, 0, 1000), (8192, 640), (3000,)])
+def test_assign_bits_few_and_many_windows(sizes):
+    """wq_assign_bits on both of its ways (one workgroup per sequence up to 320 windows in the longest sequence; widths by
+    several workgroups per sequence, then the class order, above that), bit for bit against the oracle: tied scores, NaN
+    and infinite scores, the first-window pin on and off, both top widths, quota and threshold mode, quotas larger than
+    the sequence, an empty sequence, and a bound on the windows per sequence below the real count (reported, Sec. 3.2.1,
+    Sec. 3.2.2, Alg. 2 prefill loop)."""
+    H = _h()
+    from oracle import wq_oracle as O
+    from paper_2605_02262_amd import binding as W
+    rng = np.random.default_rng(sum(sizes))
+    win_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    nw, B, max_w = int(win_off[-1]), len(sizes), max(sizes)
+    sc = np.round(rng.random(nw) * 40).astype(np.float32) / 40          # many ties
+    sc[rng.integers(0, nw, max(nw // 50, 1))] = np.nan
+    sc[rng.integers(0, nw, 3)] = np.inf
+    sc[rng.integers(0, nw, 3)] = -np.inf
+    quota = np.stack([np.array([n // 10, n // 2, n], dtype=np.int32) for n in sizes])     # (the last class takes what is left)
+    quota[0] = [sizes[0] + 5, 3, 0]                                      # more top windows than the sequence has
+    th = np.stack([np.array([0.3, 0.7], dtype=np.float32) for _ in sizes])
+    ctx = W.Context(W.workspace_bytes(B, 0, 0, 0))
+    for mode, top, pin in [(W.MODE_QUOTA, 8, 1), (W.MODE_QUOTA, 16, 0), (W.MODE_THRESHOLD, 8, 1), (W.MODE_THRESHOLD, 16, 0)]:
+        bits, perm, seg = W.wq_assign_bits(ctx, torch.from_numpy(sc).cuda(), H.i32(win_off), max_w, mode,
+                                           H.i32(quota) if mode == W.MODE_QUOTA else None,
+                                           torch.from_numpy(th).cuda() if mode == W.MODE_THRESHOLD else None, top, pin)
+        torch.cuda.synchronize()
+        assert ctx.device_status() == 0
+        wb, wp, ws = O.assign_bits(sc, win_off, mode, quota, th, top, pin)
+        assert np.array_equal(bits.cpu().numpy(), wb) and np.array_equal(perm.cpu().numpy(), wp)
+        assert np.array_equal(seg.cpu().numpy().reshape(B, 4), ws)
+    # a bound below the longest sequence's count: reported; the windows inside the bound are assigned as if they were all
+    if max_w > 8:
+        bound = max_w - 3
+        bits, perm, seg = W.wq_assign_bits(ctx, torch.from_numpy(sc).cuda(), H.i32(win_off), bound, W.MODE_QUOTA, H.i32(quota), None, 8, 1)
+        torch.cuda.synchronize()
+        assert ctx.device_status() & W.DEV_TOO_MANY_WINDOWS
+        seg = seg.cpu().numpy().reshape(B, 4)
+        for b, n in enumerate(sizes):
+            m = min(n, bound)
+            cut_off = np.array([0, m], dtype=np.int32)
+            wb, wp, ws = O.assign_bits(sc[win_off[b]:win_off[b] + m], cut_off, W.MODE_QUOTA, quota[b:b + 1], None, 8, 1)
+            assert np.array_equal(bits.cpu().numpy()[win_off[b]:win_off[b] + m], wb)
+            assert np.array_equal(perm.cpu().numpy()[win_off[b]:win_off[b] + m], wp) and np.array_equal(seg[b], ws[0])
+
+
 def test_device_side_validation_of_an_assignment():
     """wq_reorder_quantize gathers whatever rows perm names; wq_validate_assignment is the debug check of tables that do not
     come straight from wq_assign_bits: a permutation per sequence, class counts that add up.  Also: more windows than the
