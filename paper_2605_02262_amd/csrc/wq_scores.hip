@@ -274,10 +274,17 @@ __global__ __launch_bounds__(256) void k_pack_text(const uint16_t* __restrict__ 
     packed[item * 64 + lane] = v;
 }
 
-// The two buffers of visual rows are separate arrays on purpose: the compiler then knows that a read of one cannot
-// see a load in flight to the other, and makes a wavefront wait for exactly the loads it reads behind.
+// The three buffers of visual rows are separate arrays on purpose: the compiler then knows that a read of one cannot
+// see a load in flight to another, and makes a wavefront wait for exactly the loads it reads behind.
 __shared__ __attribute__((aligned(16))) uint16_t pair_a0[PA_BUF];
 __shared__ __attribute__((aligned(16))) uint16_t pair_a1[PA_BUF];
+__shared__ __attribute__((aligned(16))) uint16_t pair_a2[PA_BUF];
+template <int P>
+__device__ __forceinline__ uint16_t* pair_buf()
+{
+    static_assert(P >= 0 && P < 3, "three buffers");
+    return P == 0 ? pair_a0 : (P == 1 ? pair_a1 : pair_a2);
+}
 
 // x of the lane that a data-parallel-primitive control pairs this lane with (rows of 16 lanes)
 template <int CTRL>
@@ -315,18 +322,18 @@ struct PairSmem {
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 template <int P> struct PairBuf { static constexpr int value = P; };
 struct PairUnit { int tile, pass; };     // a row tile of the sequence x a pass of columns
+struct PairCursor { PairUnit u; int s; }; // a step of a unit
 
 // A run: `ntiles` consecutive row tiles of one sequence, from tile `tile0`, each walked in ceil(N / PASS) passes of PASS
-// text columns; a (tile, pass) is a unit of D / 128 steps.  All units of a run form one pipeline: during a unit's last
-// step the first rows and text operands of the next unit are already sent for, so the matrix cores do not wait for
+// text columns; a (tile, pass) is a unit of D / 128 steps.  All units of a run form one pipeline: visual rows are sent
+// for two steps ahead and text operands one step ahead, across the ends of units, so the matrix cores do not wait for
 // memory at the start of a tile, and what a unit leaves behind (scaling by 1/|t_j|, the sum over its columns, at a
 // tile's end the scores) happens while those loads are in flight.
 // The eight wavefronts are NCB column blocks of 64 text columns x 8 / NCB row groups of RT row tiles of 16:
 // (RT, NCB) = (8, 8): 128 rows x a 512-column pass; (4, 4): two row halves x 256 columns; (2, 2): four row quarters
 // x 128 columns; (7, 8) and (6, 8): 112 and 96 rows x 512 columns, for launches whose number of 128-row tiles
-// would leave most of the chip idle in the last round.  A wavefront walks its row tiles starting at the one with
-// its column block's number, so that the wavefronts of a row group start on different tiles; the first tile of a
-// wavefront whose column block's number is below RT is the one whose |w_k|^2 it sums on the way.
+// would leave most of the chip idle in the last round.  A wavefront whose column block's number is below RT also
+// sums |w_k|^2 of the row tile of that number in its row group (read from LDS once more, a quarter at a time).
 template <bool BF, int RT, int NCB>
 __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restrict__ va, const char* __restrict__ tbb,
                                          const float* __restrict__ inv_tn, int D, int M, int N, int tile0, int ntiles, int rows,
@@ -356,21 +363,21 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
         voff[t] = (c < PA_KS / 8 && r < rows) ? (r * D + c * 8) * 2 : (int)0x80000000;
     }
     auto send_rows = [&](auto P, __amdgpu_buffer_rsrc_t tile_rows, int byte0) {     // 256 bytes of every row, from byte0 -> buffer P
-        uint16_t* const dst = decltype(P)::value ? pair_a1 : pair_a0;
+        uint16_t* const dst = pair_buf<decltype(P)::value>();
 #pragma unroll
         for (int t = 0; t < DMA; t++)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(tile_rows, (lds_ptr_t)(dst + (wave + PA_WAVES * t) * 512), 16, voff[t], byte0, 0,
                                                      PA_ROW_POLICY);
     };
-    // byte offsets of this lane's operand pieces, row tile by row tile in the wavefront's own order
-    int ro[RT];
-#pragma unroll
-    for (int i = 0; i < RT; i++) ro[i] = (((rb + (i + cb) % RT) * 16 + lm) * PA_PITCH + lj * 8) * 2;
+    // byte offset of this lane's operand piece in a row tile's first quarter: of the wavefront's first tile (the
+    // tiles follow each other by 16 rows), and of the tile whose |w_k|^2 it sums
+    constexpr int TILE_BYTES = 16 * PA_PITCH * 2;
+    const int ro = ((rb * 16 + lm) * PA_PITCH + lj * 8) * 2, ro_own = ro + (cb < RT ? cb : 0) * TILE_BYTES;
     // A read from the buffer that this wavefront has sent loads for: the compiler puts the wait for those loads in
     // front of it (loads land in the order sent), whatever else it has moved around them.
     auto peek = [&](auto P) {
-        const char* const src = reinterpret_cast<const char*>(decltype(P)::value ? pair_a1 : pair_a0);
-        return *reinterpret_cast<const uint32_t*>(src + ro[0]);
+        const char* const src = reinterpret_cast<const char*>(pair_buf<decltype(P)::value>());
+        return *reinterpret_cast<const uint32_t*>(src + ro);
     };
     auto use = [&](uint32_t x) { asm volatile("" ::"v"(x)); };
     // the wavefront's column tiles of a pass in the packed text (tiles past the end re-read the last one: their
@@ -396,9 +403,17 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
         for (int k = threadIdx.x; k < n; k += PA_THREADS) sm.W[k] = col0 + k < N ? inv_tn[col0 + k] : 0.f;
     };
 
-    // uc: the unit whose products are being summed; un: the one after it; dc, tc: where the loads being sent go to
-    // in memory (uc's rows and text until uc's last step, then un's)
-    PairUnit uc{tile0, 0}, un = after(uc);
+    // Three cursors walk the run's steps: (uc, s) the step whose products are being summed; cb_, one step ahead, the
+    // step whose text operands are sent for (tc: its unit's text); ca, two steps ahead, the step whose visual rows are
+    // sent for (dc: its tile's rows).  Past the run's end they stay in its last unit.
+    auto advance = [&](PairCursor& c) {                   // true when it has entered another unit
+        if (++c.s < steps) return false;
+        c.s = 0;
+        c.u = after(c.u);
+        return true;
+    };
+    PairUnit uc{tile0, 0};
+    PairCursor cb_{uc, 0}, ca{uc, 0};
     __amdgpu_buffer_rsrc_t dc = rows_of(uc);
     const char* tc[PA_CT];
     text_of(uc, tc);
@@ -417,8 +432,12 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
     // quarter, three quarters ahead, they cost 8 % more cycles: the text does not always come from the nearest cache)
     uint4 gq[PA_Q][PA_CT];
     send_rows(PairBuf<0>{}, dc, 0);
+    if (advance(ca)) dc = rows_of(ca.u);
+    send_rows(PairBuf<1>{}, dc, ca.s * (PA_KS * 2));
+    if (advance(ca)) dc = rows_of(ca.u);
 #pragma unroll
     for (int q = 0; q < PA_Q; q++) load_b(tc, q, gq[q]);
+    if (advance(cb_)) text_of(cb_.u, tc);
     use(peek(PairBuf<0>{}));
 
     // What a unit leaves behind.  The lane holds, of its i-th row tile, rows 4 lj + e at column lm of column tile k.
@@ -467,7 +486,7 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
         if (writer) {
 #pragma unroll
             for (int r = 0; r < KEEP; r++) {
-                const int j = j0 + r, tile = rb + ((j >> 2) + cb) % RT;
+                const int j = j0 + r, tile = rb + (j >> 2);
                 if ((j >> 2) < RT) sm.R[cb][tile * 16 + 4 * lj + (j & 3)] += v[r];    // one writer per (column block, row)
             }
         }
@@ -501,25 +520,20 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
     // branches: it stays one block, which keeps the wait counts of the loads in flight exact.
     auto step = [&](auto P) {
         using Cur = decltype(P);
-        using Nxt = PairBuf<1 - Cur::value>;
+        using Nxt = PairBuf<(Cur::value + 1) % 3>;
+        using Far = PairBuf<(Cur::value + 2) % 3>;
         // every wavefront's rows of this step have landed (each waited for its own before it came here), and all are
-        // done reading the other buffer.  No fence: a fence would wait for the B operands in flight.
+        // done reading the buffer of the step before, which takes the rows two steps ahead.  No fence: a fence would
+        // wait for the B operands in flight.
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        // the step after this one: of this unit, or the first of the next unit
-        const bool last = s == steps - 1;
-        const int sx = last ? 0 : s + 1;
-        if (last) {
-            dc = rows_of(un);
-            text_of(un, tc);
-        }
-        send_rows(Nxt{}, dc, sx * (PA_KS * 2));
+        send_rows(Far{}, dc, ca.s * (PA_KS * 2));
         const float count = (uc.pass == 0 && cb < RT) ? 1.f : 0.f;   // |w_k|^2 is summed during the first pass, by the tile's owner (a factor, not a branch)
-        const char* const sa = reinterpret_cast<const char*>(Cur::value ? pair_a1 : pair_a0);
+        const char* const sa = reinterpret_cast<const char*>(pair_buf<Cur::value>());
         // PA_Q RT groups of PA_CT products: row tile i, quarter q; the A operand is read from LDS two groups
         // ahead.  A quarter's B operands are replaced as soon as their last product has issued.
-        auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + ro[g % RT] + (g / RT) * 64); };
-        uint4 f[3];
+        auto read_a = [&](int g) { return *reinterpret_cast<const uint4*>(sa + ro + (g % RT) * TILE_BYTES + (g / RT) * 64); };
+        uint4 f[3], own;
         uint32_t landed = 0u;
         f[0] = read_a(0);
         f[1] = read_a(1);
@@ -527,15 +541,17 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
         for (int g = 0; g < PA_Q * RT; g++) {
             const int i = g % RT, q = g / RT;
             if (g + 2 < PA_Q * RT) f[(g + 2) % 3] = read_a(g + 2);
+            if (i == 0) own = *reinterpret_cast<const uint4*>(sa + ro_own + q * 64);
             if (g == PA_Q * RT - 2) landed = peek(Nxt{});             // waits for the next step's rows, as late as it can
-            if (i == 0) nsq = fmaf(sumsq8<BF>(f[g % 3]), count, nsq);
+            if (i == RT - 1) nsq = fmaf(sumsq8<BF>(own), count, nsq);
 #pragma unroll
             for (int k = 0; k < PA_CT; k++) acc[i][k] = mfma_s<BF>(f[g % 3], gq[q][k], acc[i][k]);
-            if (i == RT - 1) load_b(tc, PA_Q * sx + q, gq[q]);
+            if (i == RT - 1) load_b(tc, PA_Q * cb_.s + q, gq[q]);
             __builtin_amdgcn_sched_barrier(0);            // issue order as written: one LDS read, then the group's products
         }
         use(landed);
-        if (last) {
+        if (s == steps - 1) {
+            const PairUnit un = after(uc);
             unit_done();
             if (uc.pass == npass - 1) tile_done(uc.tile);
             if (!w_all) {
@@ -544,18 +560,24 @@ __device__ __forceinline__ void pair_run(PairSmem& sm, const uint16_t* __restric
             }
             s = 0;
             uc = un;
-            un = after(un);
         } else {
             ++s;
         }
+        if (advance(cb_)) text_of(cb_.u, tc);
+        if (advance(ca)) dc = rows_of(ca.u);
     };
     const int total = ntiles * npass * steps;
     int gs = 0;
-    for (; gs + 1 < total; gs += 2) {
+    for (; gs + 2 < total; gs += 3) {
         step(PairBuf<0>{});
         step(PairBuf<1>{});
+        step(PairBuf<2>{});
     }
     if (gs < total) step(PairBuf<0>{});
+    if (gs + 1 < total) step(PairBuf<1>{});
+    use(peek(PairBuf<0>{}));                              // nothing of this run is in flight to LDS any more
+    use(peek(PairBuf<1>{}));
+    use(peek(PairBuf<2>{}));
 }
 
 // The launch's row tiles (`rows` = 128, 112 or 96 visual rows) are numbered sequence after sequence; a workgroup takes
