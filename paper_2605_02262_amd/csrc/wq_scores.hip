@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void k_window_mean(const float* __restrict__ t
 // walked in passes of up to 512 columns, so that the visual rows are read from memory once when the sequence has at
 // most 512 text tokens.  One workgroup of eight wavefronts per compute unit takes a contiguous share of the launch's
 // tiles.  Over D it goes in steps of 128 elements (two 128-byte lines per row):
-//   visual rows   memory -> LDS directly (buffer loads with the LDS bit, a step ahead, two buffers, one barrier per
+//   visual rows   memory -> LDS directly (buffer loads with the LDS bit, two steps ahead, three buffers, one barrier per
 //                 step) -> A operands of all wavefronts, read two product groups ahead of their use;
 //   text rows     each wavefront owns 64 columns of the pass, so its B operands are private to it.  An operand is
 //                 16 rows x 16 bytes per lane group: read from the row-major text that is 64 scattered pieces per
